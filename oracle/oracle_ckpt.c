@@ -1,0 +1,283 @@
+/*
+ * CPU oracle for the checkpoint snapshot path. TEST INFRASTRUCTURE ONLY: it may be called from
+ * tests/, the smoke check and the benchmark's cpu_baseline leg, never from the product path.
+ *
+ * What it computes (paper: design principles "lazy non-blocking copies" and the three-phase save
+ * of the Implementation section): the checkpoint of iteration i is the serialization of the exact
+ * bytes every registered tensor holds after update i. The asynchronous machinery changes when
+ * bytes move, never which bytes, so the oracle is the plain synchronous serializer: the caller
+ * reads every tensor back with blocking copies at the iteration boundary and hands the host byte
+ * arrays in; the oracle computes the header (file offset per tensor) and writes header, then each
+ * tensor followed by zero padding, with sequential write() calls. The file layout is the one in
+ * docs/FORMAT.md, implemented here from that page alone.
+ *
+ * One thread, no chunking, no overlap, no ring. Shares no code with the HIP library.
+ */
+#define _GNU_SOURCE
+#include <errno.h>
+#include <fcntl.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#include <sys/stat.h>
+#include <unistd.h>
+
+#define ORACLE_ALIGN 4096ull
+#define ORACLE_FIXED 64ull
+
+enum { ORACLE_OK = 0, ORACLE_BAD_ARG = 1, ORACLE_IO = 2, ORACLE_BAD_FILE = 3, ORACLE_MISMATCH = 4, ORACLE_NOMEM = 5 };
+
+typedef struct {
+    const char *name;      /* UTF-8, NUL terminated here; stored without the NUL */
+    int32_t dtype;         /* 1 bf16, 2 f32, 3 f16, 4 u8, 5 i32, 6 i64 */
+    uint32_t ndim;         /* 0..8 */
+    const int64_t *shape;  /* ndim entries */
+    void *host_bytes;      /* nbytes bytes on the host; may be NULL for header-only calls */
+    uint64_t nbytes;
+} oracle_tensor;
+
+static const uint8_t MAGIC[8] = { 'D', 'S', 'L', 'L', 'M', 'C', 'K', 0x01 };
+
+static uint64_t round_up(uint64_t x) { return (x + ORACLE_ALIGN - 1) / ORACLE_ALIGN * ORACLE_ALIGN; }
+
+static uint64_t elsize(int32_t dtype)
+{
+    switch (dtype) {
+    case 1: return 2; case 2: return 4; case 3: return 2; case 4: return 1; case 5: return 4; case 6: return 8;
+    default: return 0;
+    }
+}
+
+static void put_le(uint8_t *p, uint64_t v, int nbytes) { for (int i = 0; i < nbytes; i++) p[i] = (uint8_t)(v >> (8 * i)); }
+static uint64_t get_le(const uint8_t *p, int nbytes) { uint64_t v = 0; for (int i = 0; i < nbytes; i++) v |= (uint64_t)p[i] << (8 * i); return v; }
+
+static int tensor_ok(const oracle_tensor *t)
+{
+    if (!t->name) return 0;
+    size_t len = strlen(t->name);
+    if (len < 1 || len > 65535) return 0;
+    uint64_t es = elsize(t->dtype);
+    if (es == 0 || t->ndim > 8) return 0;
+    uint64_t numel = 1;
+    for (uint32_t d = 0; d < t->ndim; d++) { if (t->shape[d] < 0) return 0; numel *= (uint64_t)t->shape[d]; }
+    return t->nbytes > 0 && t->nbytes == es * numel;
+}
+
+static uint64_t entry_len(const oracle_tensor *t) { return 2 + strlen(t->name) + 1 + 1 + 8ull * t->ndim + 8 + 8; }
+
+/* header_bytes for a tensor list: the fixed part plus all entries, rounded up to the alignment unit. */
+uint64_t oracle_header_bytes(const oracle_tensor *ts, size_t n)
+{
+    uint64_t used = ORACLE_FIXED;
+    for (size_t k = 0; k < n; k++) used += entry_len(&ts[k]);
+    return round_up(used);
+}
+
+uint64_t oracle_data_bytes(const oracle_tensor *ts, size_t n)
+{
+    uint64_t total = 0;
+    for (size_t k = 0; k < n; k++) total += round_up(ts[k].nbytes);
+    return total;
+}
+
+/* File offset of tensor k: tensors follow the header in registration order, each starting on an
+ * alignment boundary (FORMAT.md, data region). */
+uint64_t oracle_tensor_offset(const oracle_tensor *ts, size_t n, size_t k)
+{
+    uint64_t off = oracle_header_bytes(ts, n);
+    for (size_t j = 0; j < k; j++) off += round_up(ts[j].nbytes);
+    return off;
+}
+
+/* Write the whole header (fixed part, table, zero fill) into out[0 .. header_bytes). */
+int oracle_build_header(const oracle_tensor *ts, size_t n, uint64_t iter, uint8_t *out, uint64_t cap)
+{
+    for (size_t k = 0; k < n; k++) if (!tensor_ok(&ts[k])) return ORACLE_BAD_ARG;
+    uint64_t hb = oracle_header_bytes(ts, n), db = oracle_data_bytes(ts, n);
+    if (cap < hb) return ORACLE_BAD_ARG;
+    memset(out, 0, hb);
+    memcpy(out, MAGIC, 8);
+    put_le(out + 8, 1, 4);
+    put_le(out + 12, ORACLE_ALIGN, 4);
+    put_le(out + 16, iter, 8);
+    put_le(out + 24, n, 8);
+    put_le(out + 32, hb, 8);
+    put_le(out + 40, db, 8);
+    put_le(out + 48, hb + db, 8);
+    put_le(out + 56, 0, 8);
+    uint8_t *p = out + ORACLE_FIXED;
+    uint64_t off = hb;
+    for (size_t k = 0; k < n; k++) {
+        size_t len = strlen(ts[k].name);
+        put_le(p, len, 2); p += 2;
+        memcpy(p, ts[k].name, len); p += len;
+        *p++ = (uint8_t)ts[k].dtype;
+        *p++ = (uint8_t)ts[k].ndim;
+        for (uint32_t d = 0; d < ts[k].ndim; d++) { put_le(p, (uint64_t)ts[k].shape[d], 8); p += 8; }
+        put_le(p, off, 8); p += 8;
+        put_le(p, ts[k].nbytes, 8); p += 8;
+        off += round_up(ts[k].nbytes);
+    }
+    return ORACLE_OK;
+}
+
+static int write_all(int fd, const void *buf, uint64_t len)
+{
+    const uint8_t *p = (const uint8_t *)buf;
+    while (len > 0) {
+        size_t want = len > (1ull << 30) ? (size_t)(1ull << 30) : (size_t)len;
+        ssize_t w = write(fd, p, want);
+        if (w < 0) { if (errno == EINTR) continue; return ORACLE_IO; }
+        p += w; len -= (uint64_t)w;
+    }
+    return ORACLE_OK;
+}
+
+static int read_all(int fd, void *buf, uint64_t len)
+{
+    uint8_t *p = (uint8_t *)buf;
+    while (len > 0) {
+        size_t want = len > (1ull << 30) ? (size_t)(1ull << 30) : (size_t)len;
+        ssize_t r = read(fd, p, want);
+        if (r < 0) { if (errno == EINTR) continue; return ORACLE_IO; }
+        if (r == 0) return ORACLE_BAD_FILE;
+        p += r; len -= (uint64_t)r;
+    }
+    return ORACLE_OK;
+}
+
+/* The serializer: header, then tensor after tensor with its zero padding, sequential write(). */
+int oracle_serialize_file(const oracle_tensor *ts, size_t n, uint64_t iter, const char *path)
+{
+    uint64_t hb = oracle_header_bytes(ts, n);
+    uint8_t *hdr = (uint8_t *)malloc(hb);
+    if (!hdr) return ORACLE_NOMEM;
+    int rc = oracle_build_header(ts, n, iter, hdr, hb);
+    if (rc) { free(hdr); return rc; }
+    for (size_t k = 0; k < n; k++) if (!ts[k].host_bytes) { free(hdr); return ORACLE_BAD_ARG; }
+    int fd = open(path, O_WRONLY | O_CREAT | O_TRUNC, 0644);
+    if (fd < 0) { free(hdr); return ORACLE_IO; }
+    static const uint8_t zeros[ORACLE_ALIGN] = { 0 };
+    rc = write_all(fd, hdr, hb);
+    for (size_t k = 0; k < n && rc == ORACLE_OK; k++) {
+        rc = write_all(fd, ts[k].host_bytes, ts[k].nbytes);
+        if (rc == ORACLE_OK) rc = write_all(fd, zeros, round_up(ts[k].nbytes) - ts[k].nbytes);
+    }
+    if (close(fd) != 0 && rc == ORACLE_OK) rc = ORACLE_IO;
+    free(hdr);
+    return rc;
+}
+
+/* Same bytes into memory (for small cases). Returns file_bytes through *written. */
+int oracle_serialize_mem(const oracle_tensor *ts, size_t n, uint64_t iter, uint8_t *out, uint64_t cap, uint64_t *written)
+{
+    uint64_t hb = oracle_header_bytes(ts, n), db = oracle_data_bytes(ts, n);
+    if (cap < hb + db) return ORACLE_BAD_ARG;
+    int rc = oracle_build_header(ts, n, iter, out, cap);
+    if (rc) return rc;
+    uint8_t *p = out + hb;
+    for (size_t k = 0; k < n; k++) {
+        if (!ts[k].host_bytes) return ORACLE_BAD_ARG;
+        uint64_t padded = round_up(ts[k].nbytes);
+        memcpy(p, ts[k].host_bytes, ts[k].nbytes);
+        memset(p + ts[k].nbytes, 0, padded - ts[k].nbytes);
+        p += padded;
+    }
+    if (written) *written = hb + db;
+    return ORACLE_OK;
+}
+
+/* Streaming comparison of an existing file against what the oracle would write, without holding a
+ * second copy of the data: returns ORACLE_MISMATCH and the first differing file offset. */
+int oracle_compare_file(const oracle_tensor *ts, size_t n, uint64_t iter, const char *path, uint64_t *first_diff)
+{
+    uint64_t hb = oracle_header_bytes(ts, n), db = oracle_data_bytes(ts, n);
+    if (first_diff) *first_diff = UINT64_MAX;
+    uint8_t *hdr = (uint8_t *)malloc(hb);
+    if (!hdr) return ORACLE_NOMEM;
+    int rc = oracle_build_header(ts, n, iter, hdr, hb);
+    if (rc) { free(hdr); return rc; }
+    int fd = open(path, O_RDONLY);
+    if (fd < 0) { free(hdr); return ORACLE_IO; }
+    struct stat st;
+    if (fstat(fd, &st) != 0) { close(fd); free(hdr); return ORACLE_IO; }
+    if ((uint64_t)st.st_size != hb + db) { close(fd); free(hdr); if (first_diff) *first_diff = (uint64_t)st.st_size < hb + db ? (uint64_t)st.st_size : hb + db; return ORACLE_MISMATCH; }
+    const uint64_t BUF = 8ull << 20;
+    uint8_t *buf = (uint8_t *)malloc(BUF);
+    if (!buf) { close(fd); free(hdr); return ORACLE_NOMEM; }
+    uint64_t pos = 0;
+    /* header */
+    for (uint64_t done = 0; done < hb && rc == ORACLE_OK; ) {
+        uint64_t m = hb - done < BUF ? hb - done : BUF;
+        rc = read_all(fd, buf, m);
+        if (rc == ORACLE_OK) for (uint64_t i = 0; i < m; i++) if (buf[i] != hdr[done + i]) { if (first_diff) *first_diff = pos + i; rc = ORACLE_MISMATCH; break; }
+        done += m; pos += m;
+    }
+    for (size_t k = 0; k < n && rc == ORACLE_OK; k++) {
+        const uint8_t *src = (const uint8_t *)ts[k].host_bytes;
+        uint64_t padded = round_up(ts[k].nbytes);
+        for (uint64_t done = 0; done < padded && rc == ORACLE_OK; ) {
+            uint64_t m = padded - done < BUF ? padded - done : BUF;
+            rc = read_all(fd, buf, m);
+            if (rc == ORACLE_OK) for (uint64_t i = 0; i < m; i++) {
+                uint8_t want = done + i < ts[k].nbytes ? src[done + i] : 0;
+                if (buf[i] != want) { if (first_diff) *first_diff = pos + i; rc = ORACLE_MISMATCH; break; }
+            }
+            done += m; pos += m;
+        }
+    }
+    free(buf); free(hdr); close(fd);
+    return rc;
+}
+
+/* Restore: read the file, check it against FORMAT.md's reader checks and against the expected tensor
+ * list (names, dtypes, shapes, sizes), then copy each tensor's bytes into host_bytes. The caller
+ * moves them to the device with blocking copies. */
+int oracle_restore_file(const char *path, oracle_tensor *ts, size_t n, uint64_t *iter_out)
+{
+    int fd = open(path, O_RDONLY);
+    if (fd < 0) return ORACLE_IO;
+    struct stat st;
+    if (fstat(fd, &st) != 0) { close(fd); return ORACLE_IO; }
+    uint8_t fixed[ORACLE_FIXED];
+    if ((uint64_t)st.st_size < ORACLE_FIXED || read_all(fd, fixed, ORACLE_FIXED) != ORACLE_OK) { close(fd); return ORACLE_BAD_FILE; }
+    uint64_t hb = get_le(fixed + 32, 8), db = get_le(fixed + 40, 8), fb = get_le(fixed + 48, 8);
+    if (memcmp(fixed, MAGIC, 8) != 0 || get_le(fixed + 8, 4) != 1 || get_le(fixed + 12, 4) != ORACLE_ALIGN ||
+        hb % ORACLE_ALIGN != 0 || hb < ORACLE_FIXED || fb != hb + db || fb != (uint64_t)st.st_size || get_le(fixed + 56, 8) != 0) { close(fd); return ORACLE_BAD_FILE; }
+    if (get_le(fixed + 24, 8) != n) { close(fd); return ORACLE_MISMATCH; }
+    uint8_t *hdr = (uint8_t *)malloc(hb);
+    if (!hdr) { close(fd); return ORACLE_NOMEM; }
+    memcpy(hdr, fixed, ORACLE_FIXED);
+    int rc = read_all(fd, hdr + ORACLE_FIXED, hb - ORACLE_FIXED);
+    const uint8_t *p = hdr + ORACLE_FIXED, *end = hdr + hb;
+    uint64_t expect_off = hb;
+    for (size_t k = 0; k < n && rc == ORACLE_OK; k++) {
+        if (end - p < 2) { rc = ORACLE_BAD_FILE; break; }
+        uint64_t len = get_le(p, 2); p += 2;
+        if ((uint64_t)(end - p) < len + 2) { rc = ORACLE_BAD_FILE; break; }
+        const uint8_t *name = p; p += len;
+        int32_t dtype = *p++; uint32_t ndim = *p++;
+        if (ndim > 8 || (uint64_t)(end - p) < 8ull * ndim + 16) { rc = ORACLE_BAD_FILE; break; }
+        uint64_t numel = 1; int64_t shape[8];
+        for (uint32_t d = 0; d < ndim; d++) { shape[d] = (int64_t)get_le(p, 8); p += 8; if (shape[d] < 0) rc = ORACLE_BAD_FILE; else numel *= (uint64_t)shape[d]; }
+        uint64_t off = get_le(p, 8); p += 8;
+        uint64_t nb = get_le(p, 8); p += 8;
+        if (rc != ORACLE_OK) break;
+        if (off != expect_off || nb == 0 || nb != elsize(dtype) * numel || off + nb > fb) { rc = ORACLE_BAD_FILE; break; }
+        if (len != strlen(ts[k].name) || memcmp(name, ts[k].name, len) != 0 || dtype != ts[k].dtype || ndim != ts[k].ndim || nb != ts[k].nbytes) { rc = ORACLE_MISMATCH; break; }
+        for (uint32_t d = 0; d < ndim; d++) if (shape[d] != ts[k].shape[d]) rc = ORACLE_MISMATCH;
+        expect_off += round_up(nb);
+    }
+    if (rc == ORACLE_OK && expect_off != fb) rc = ORACLE_BAD_FILE;
+    /* data: sequential read, padding skipped */
+    for (size_t k = 0; k < n && rc == ORACLE_OK; k++) {
+        if (!ts[k].host_bytes) { rc = ORACLE_BAD_ARG; break; }
+        rc = read_all(fd, ts[k].host_bytes, ts[k].nbytes);
+        uint64_t pad = round_up(ts[k].nbytes) - ts[k].nbytes;
+        if (rc == ORACLE_OK && pad) { uint8_t skip[ORACLE_ALIGN]; rc = read_all(fd, skip, pad); }
+    }
+    if (rc == ORACLE_OK && iter_out) *iter_out = get_le(fixed + 16, 8);
+    free(hdr); close(fd);
+    return rc;
+}
