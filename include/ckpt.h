@@ -1,0 +1,197 @@
+/*
+ * libdsllm_ckpt — lazy asynchronous snapshot of one GPU's training-state shard (MI355X / gfx950).
+ *
+ * The operations follow the paper's system design: a pre-allocated, pre-pinned host cache that all
+ * checkpoints reuse ("coalescing of shards to host memory"); device-to-host copies that overlap the
+ * forward and backward passes, in which parameters and optimizer state are immutable, and that
+ * must be over before the update mutates them ("lazy non-blocking copies"); flushing of every piece
+ * to storage as soon as it is on the host, with back-pressure when the host cache is full
+ * ("streamlined multi-level flushing"); and the three-phase save of the Implementation section
+ * (tensor list -> header with a file offset per tensor -> asynchronous transfers and writes).
+ * Here phases one and two run once, at registration.
+ *
+ * Plain C ABI: plain pointers and sizes only. "dev" pointers are device (HBM) addresses valid on
+ * the context's GPU; every other pointer is a host pointer. A stream argument is a hipStream_t
+ * passed as void*. All calls return a ckpt_status (0 = ok, negative = error) and never throw or
+ * abort; ckpt_last_error() gives the text of the last error of the calling thread.
+ *
+ * File layout: docs/FORMAT.md (fixed 64-byte header, tensor table, 4 KiB-aligned data).
+ */
+#ifndef DSLLM_CKPT_H
+#define DSLLM_CKPT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ckpt_ctx ckpt_ctx;    /* opaque, library-owned */
+typedef struct ckpt_plan ckpt_plan;  /* opaque, library-owned */
+
+typedef enum {
+    CKPT_OK = 0,
+    CKPT_EINVAL = -1,    /* bad argument (null, zero-size tensor, nbytes != dtype x shape, bad config) */
+    CKPT_ENOMEM = -2,    /* host or device allocation failed */
+    CKPT_EIO = -3,       /* open/write/read/rename failed (also latched from the flush threads) */
+    CKPT_EHIP = -4,      /* a HIP runtime call failed */
+    CKPT_ESTATE = -5,    /* call out of order (see each function) */
+    CKPT_EFORMAT = -6,   /* restore: not a well-formed checkpoint file */
+    CKPT_EMISMATCH = -7  /* restore: file's tensor table differs from the registered tensors */
+} ckpt_status;
+
+typedef enum { CKPT_BF16 = 1, CKPT_F32 = 2, CKPT_F16 = 3, CKPT_U8 = 4, CKPT_I32 = 5, CKPT_I64 = 6 } ckpt_dtype;
+
+/* One tensor of the shard. Caller-owned; the library copies name and shape at registration.
+ * dev_ptr must be aligned to the element size only. The memory must stay allocated, at this
+ * address, for as long as the registration lives. */
+typedef struct {
+    const char *name;      /* UTF-8, NUL-terminated, 1..65535 bytes */
+    int32_t dtype;         /* ckpt_dtype */
+    uint32_t ndim;         /* 0..8; 0 = scalar */
+    const int64_t *shape;  /* ndim entries, each >= 0 */
+    void *dev_ptr;         /* device address of the first element (ignored by ckpt_plan_create) */
+    uint64_t nbytes;       /* must equal elsize(dtype) * product(shape) and be > 0 */
+} ckpt_tensor_desc;
+
+/* when the update may start: after the last device-to-host copy of the pending snapshot (the
+ * paper's rule), or as soon as the last pack kernel has read the tensors (the packed bytes then
+ * sit in device staging memory, which only makes a difference when staging holds the whole shard
+ * or its tail) */
+typedef enum { CKPT_WINDOW_D2H = 0, CKPT_WINDOW_PACK = 1 } ckpt_window_policy;
+
+/* Zero in a size/count field selects the default given in the comment. */
+typedef struct {
+    int32_t device;                 /* HIP device ordinal */
+    const char *out_dir;            /* directory of the checkpoint files; must exist */
+    uint64_t host_ring_bytes;       /* pinned host ring; the paper's one knob. default 8 GiB; rounded down to
+                                       whole DMA chunks, at least 2 chunks */
+    uint64_t dma_chunk_bytes;       /* one device-to-host copy and one ring slot. default 64 MiB; multiple of 64 KiB */
+    uint64_t pack_superchunk_bytes; /* bytes one pack launch produces. default 1 GiB; multiple of dma_chunk_bytes */
+    uint64_t dev_staging_bytes;     /* device staging; default 2 super-chunks; rounded down to whole super-chunks, at least 2
+                                       (or the whole data region when that is smaller) */
+    int32_t n_dma_streams;          /* default 2, at most 8 */
+    int32_t n_io_threads;           /* host threads that write (and, on restore, read) ring slots. default 4, at most 64 */
+    int32_t window_policy;          /* ckpt_window_policy */
+    int32_t o_direct;               /* 1: open files with O_DIRECT (all offsets and sizes are 4 KiB multiples) */
+    int32_t fsync_on_commit;        /* 1: fsync before the rename that commits a file */
+    int32_t reserved[7];            /* must be zero */
+} ckpt_config;
+
+/* Sizes that follow from a tensor list and a configuration. */
+typedef struct {
+    uint64_t n_tensors;
+    uint64_t header_bytes, data_bytes, file_bytes; /* docs/FORMAT.md */
+    uint64_t payload_bytes;                        /* sum of nbytes, without padding */
+    uint64_t n_tiles;                              /* pack work items (one wavefront each) */
+    uint64_t n_chunks;                             /* DMA chunks per snapshot */
+    uint64_t n_superchunks;                        /* pack launches per snapshot */
+    uint64_t dma_chunk_bytes, pack_superchunk_bytes, tile_bytes;
+} ckpt_layout;
+
+/* One pack work item: `copy_bytes` bytes from device address `src` go to offset `dst_off` of the data
+ * region (file offset minus header_bytes), followed by zero bytes up to `total_bytes`. dst_off and
+ * total_bytes are multiples of 16; a tile never crosses a super-chunk boundary or a tensor boundary. */
+typedef struct {
+    uint64_t src;
+    uint64_t dst_off;
+    uint32_t copy_bytes;
+    uint32_t total_bytes;
+    uint64_t reserved;
+} ckpt_tile;
+
+/* Per-snapshot measurements. Times in milliseconds on the device timeline (HIP events) unless
+ * marked host. A field is -1 while not yet known. */
+typedef struct {
+    uint64_t iter;
+    uint64_t payload_bytes, data_bytes, file_bytes;
+    int32_t d2h_done, committed;      /* 1 once the last copy has landed / the file has its final name */
+    int32_t pack_launches;
+    int32_t reserved0;
+    double pack_ms_sum;               /* sum over pack launches of (end - start) on the pack stream */
+    double request_to_d2h_end_ms;     /* boundary event on the caller's stream -> last copy done */
+    double d2h_span_ms;               /* first copy start -> last copy done */
+    double request_to_pack_end_ms;    /* boundary event -> last pack kernel done */
+    double host_submit_ms;            /* host: request -> every pack and copy enqueued (includes ring back-pressure) */
+    double host_request_to_commit_ms; /* host: request -> file renamed */
+    double host_backpressure_ms;      /* host: time the submit thread spent waiting for a free ring slot */
+    double host_snapshot_call_ms;     /* host: time the caller spent inside ckpt_snapshot_async */
+} ckpt_stats;
+
+#define CKPT_ITER_ALL UINT64_MAX
+
+/* ---- planning without a device (also used internally by registration) ---- */
+
+/* Computes header, offsets, tile table and chunk table for a tensor list; dev_ptr values are taken
+ * as given and never dereferenced. CKPT_EINVAL on a bad description or configuration. */
+int ckpt_plan_create(const ckpt_tensor_desc *tensors, size_t n, const ckpt_config *cfg, ckpt_plan **out);
+int ckpt_plan_layout(const ckpt_plan *plan, ckpt_layout *out);
+/* Copies the header_bytes bytes of the header for iteration `iter` into buf (cap >= header_bytes). */
+int ckpt_plan_header(const ckpt_plan *plan, uint64_t iter, void *buf, uint64_t cap);
+/* File offset of every tensor, in registration order (cap >= n_tensors entries). */
+int ckpt_plan_offsets(const ckpt_plan *plan, uint64_t *out, size_t cap);
+/* Copies tiles [first, first+count) into out; first_tile_of_superchunk (n_superchunks+1 entries) may be NULL. */
+int ckpt_plan_tiles(const ckpt_plan *plan, uint64_t first, uint64_t count, ckpt_tile *out);
+int ckpt_plan_superchunk_tiles(const ckpt_plan *plan, uint64_t *first_tile_of_superchunk, size_t cap);
+void ckpt_plan_destroy(ckpt_plan *plan);
+
+/* ---- the snapshot path ---- */
+
+/* Allocates and pins the host ring once, touches every page, creates streams, events and threads.
+ * The ring is reused by every later snapshot and restore (paper: pre-allocated, pre-pinned cache). */
+int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out);
+
+/* Registers the shard's tensors, once per context: builds header, file offsets, the tile table
+ * (uploaded to the device) and the chunk table, and allocates device staging. CKPT_ESTATE if
+ * tensors are already registered. Overlapping device ranges are allowed (serialized twice). */
+int ckpt_register_tensors(ckpt_ctx *ctx, const ckpt_tensor_desc *tensors, size_t n);
+
+/* Requests the snapshot of iteration `iter`: the state captured is what the tensors hold once all
+ * work already enqueued on `hip_stream_compute` has run. Returns without waiting for any copy; the
+ * caller goes on with the next forward/backward pass. Pack kernels, copies and file writes are
+ * issued by library threads; if the ring is full they wait for flushed slots (never for the
+ * caller). CKPT_ESTATE: nothing registered, or a previous snapshot's window was never closed with
+ * ckpt_wait_immutable_window_end / ckpt_flush, or `iter` is still in flight. A latched I/O error of
+ * an earlier snapshot is returned here (CKPT_EIO / CKPT_EHIP) and cleared. */
+int ckpt_snapshot_async(ckpt_ctx *ctx, uint64_t iter, void *hip_stream_compute);
+
+/* The one call a conventional save/load engine does not have: to be made before the update that
+ * mutates the registered tensors. Orders all later work on `hip_stream_compute` after the pending
+ * snapshot's last read of the tensors (per window_policy) with a device-side wait; with
+ * host_block != 0 it also blocks the calling thread until then. The host is blocked in any case
+ * until the library has enqueued all of the snapshot's copies, which takes longer than a moment
+ * only when the ring is smaller than the shard and the flush is behind. No-op without a pending
+ * snapshot. Does not wait for file writes: those may overlap the update. */
+int ckpt_wait_immutable_window_end(ckpt_ctx *ctx, void *hip_stream_compute, int32_t host_block);
+
+/* Blocks until the file of `iter` (or of every requested snapshot, CKPT_ITER_ALL) is written,
+ * optionally fsync'ed, and renamed to its final name. Returns the latched asynchronous error, if
+ * any, and clears it. CKPT_EINVAL if `iter` was never requested. */
+int ckpt_flush(ckpt_ctx *ctx, uint64_t iter);
+
+/* Reads a checkpoint file back into the registered tensors: header checked against the
+ * registration (CKPT_EFORMAT / CKPT_EMISMATCH), data read into ring slots by the I/O threads,
+ * copied host-to-device into staging, scattered by a kernel. Returns when everything is enqueued
+ * (the file has been read by then); `hip_stream` is made to wait for the last scatter kernel.
+ * iter_out may be NULL. CKPT_ESTATE while a snapshot is in flight. */
+int ckpt_restore(ckpt_ctx *ctx, const char *path, void *hip_stream, uint64_t *iter_out);
+
+int ckpt_get_layout(ckpt_ctx *ctx, ckpt_layout *out);
+/* Measurements of one requested snapshot; CKPT_EINVAL if unknown. Device-timeline fields are filled
+ * once d2h_done is set. */
+int ckpt_get_stats(ckpt_ctx *ctx, uint64_t iter, ckpt_stats *out);
+/* Writes "<out_dir>/ckpt_iter<20 digits>.dsl" into buf. */
+int ckpt_file_name(ckpt_ctx *ctx, uint64_t iter, char *buf, size_t cap);
+
+/* Text of the calling thread's last error; library-owned, valid until that thread's next failing call. */
+const char *ckpt_last_error(void);
+
+/* Drains every pending snapshot (as ckpt_flush(ALL)), stops the threads, frees ring, staging,
+ * streams and events. */
+int ckpt_destroy(ckpt_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,271 @@
+"""ctypes binding of libdsllm_ckpt.so: same names as the C ABI (include/ckpt.h, include/ckpt_proxy.h),
+argument marshalling only. There is no fallback: if the library has not been built, importing this
+module raises."""
+import ctypes as C
+import os
+
+# The library must use the same HIP runtime as whoever owns the device memory and the streams it is
+# handed. PyTorch ships a runtime of its own, so when PyTorch is in the process it is loaded first and
+# libdsllm_ckpt.so then binds to that already-loaded libamdhip64 instead of bringing a second one.
+try:
+    import torch  # noqa: F401
+except ImportError:  # a pure C caller links the system runtime; nothing to align with
+    torch = None
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libdsllm_ckpt.so")
+
+CKPT_OK, CKPT_EINVAL, CKPT_ENOMEM, CKPT_EIO, CKPT_EHIP, CKPT_ESTATE, CKPT_EFORMAT, CKPT_EMISMATCH = 0, -1, -2, -3, -4, -5, -6, -7
+CKPT_BF16, CKPT_F32, CKPT_F16, CKPT_U8, CKPT_I32, CKPT_I64 = 1, 2, 3, 4, 5, 6
+CKPT_WINDOW_D2H, CKPT_WINDOW_PACK = 0, 1
+CKPT_ITER_ALL = 0xFFFFFFFFFFFFFFFF
+_STATUS_NAMES = {0: "CKPT_OK", -1: "CKPT_EINVAL", -2: "CKPT_ENOMEM", -3: "CKPT_EIO", -4: "CKPT_EHIP", -5: "CKPT_ESTATE",
+                 -6: "CKPT_EFORMAT", -7: "CKPT_EMISMATCH"}
+
+
+class ckpt_tensor_desc(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("dtype", C.c_int32), ("ndim", C.c_uint32), ("shape", C.POINTER(C.c_int64)),
+                ("dev_ptr", C.c_void_p), ("nbytes", C.c_uint64)]
+
+
+class ckpt_config(C.Structure):
+    _fields_ = [("device", C.c_int32), ("out_dir", C.c_char_p), ("host_ring_bytes", C.c_uint64),
+                ("dma_chunk_bytes", C.c_uint64), ("pack_superchunk_bytes", C.c_uint64), ("dev_staging_bytes", C.c_uint64),
+                ("n_dma_streams", C.c_int32), ("n_io_threads", C.c_int32), ("window_policy", C.c_int32),
+                ("o_direct", C.c_int32), ("fsync_on_commit", C.c_int32), ("reserved", C.c_int32 * 7)]
+
+
+class ckpt_layout(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("n_tensors", "header_bytes", "data_bytes", "file_bytes", "payload_bytes", "n_tiles",
+                                          "n_chunks", "n_superchunks", "dma_chunk_bytes", "pack_superchunk_bytes", "tile_bytes")]
+
+
+class ckpt_tile(C.Structure):
+    _fields_ = [("src", C.c_uint64), ("dst_off", C.c_uint64), ("copy_bytes", C.c_uint32), ("total_bytes", C.c_uint32),
+                ("reserved", C.c_uint64)]
+
+
+class ckpt_stats(C.Structure):
+    _fields_ = [("iter", C.c_uint64), ("payload_bytes", C.c_uint64), ("data_bytes", C.c_uint64), ("file_bytes", C.c_uint64),
+                ("d2h_done", C.c_int32), ("committed", C.c_int32), ("pack_launches", C.c_int32), ("reserved0", C.c_int32),
+                ("pack_ms_sum", C.c_double), ("request_to_d2h_end_ms", C.c_double), ("d2h_span_ms", C.c_double),
+                ("request_to_pack_end_ms", C.c_double), ("host_submit_ms", C.c_double), ("host_request_to_commit_ms", C.c_double),
+                ("host_backpressure_ms", C.c_double), ("host_snapshot_call_ms", C.c_double)]
+
+
+class CkptError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"{_STATUS_NAMES.get(code, code)}: {text}")
+        self.code = code
+        self.text = text
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+                      "(or python paper_2406_10707_amd/build.py) first. There is no fallback path.")
+
+lib = C.CDLL(LIB_PATH)
+
+_vp, _u64, _i32 = C.c_void_p, C.c_uint64, C.c_int32
+_SIGS = {
+    "ckpt_plan_create": (C.c_int, [C.POINTER(ckpt_tensor_desc), C.c_size_t, C.POINTER(ckpt_config), C.POINTER(_vp)]),
+    "ckpt_plan_layout": (C.c_int, [_vp, C.POINTER(ckpt_layout)]),
+    "ckpt_plan_header": (C.c_int, [_vp, _u64, _vp, _u64]),
+    "ckpt_plan_offsets": (C.c_int, [_vp, C.POINTER(_u64), C.c_size_t]),
+    "ckpt_plan_tiles": (C.c_int, [_vp, _u64, _u64, C.POINTER(ckpt_tile)]),
+    "ckpt_plan_superchunk_tiles": (C.c_int, [_vp, C.POINTER(_u64), C.c_size_t]),
+    "ckpt_plan_destroy": (None, [_vp]),
+    "ckpt_init": (C.c_int, [C.POINTER(ckpt_config), C.POINTER(_vp)]),
+    "ckpt_register_tensors": (C.c_int, [_vp, C.POINTER(ckpt_tensor_desc), C.c_size_t]),
+    "ckpt_snapshot_async": (C.c_int, [_vp, _u64, _vp]),
+    "ckpt_wait_immutable_window_end": (C.c_int, [_vp, _vp, _i32]),
+    "ckpt_flush": (C.c_int, [_vp, _u64]),
+    "ckpt_restore": (C.c_int, [_vp, C.c_char_p, _vp, C.POINTER(_u64)]),
+    "ckpt_get_layout": (C.c_int, [_vp, C.POINTER(ckpt_layout)]),
+    "ckpt_get_stats": (C.c_int, [_vp, _u64, C.POINTER(ckpt_stats)]),
+    "ckpt_file_name": (C.c_int, [_vp, C.c_char_p, C.c_size_t]),
+    "ckpt_last_error": (C.c_char_p, []),
+    "ckpt_destroy": (C.c_int, [_vp]),
+    "proxy_gemm_bf16": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _i32, _vp]),
+    "proxy_fill_state": (C.c_int, [_vp, _vp, _vp, _vp, _u64, _u64, _u64, _vp]),
+    "proxy_adam_step": (C.c_int, [_vp, _vp, _vp, _vp, _u64, _u64, _u64, _u64, C.c_float, C.c_float, C.c_float, C.c_float, _vp]),
+    "proxy_fill_words": (C.c_int, [_vp, _u64, _u64, _vp]),
+    "proxy_mutate_words": (C.c_int, [_vp, _u64, _u64, _vp]),
+    "proxy_devcopy": (C.c_int, [_vp, _vp, _u64, _vp]),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _fn = getattr(lib, _name)      # raises if the library does not export the symbol
+    _fn.restype = _res
+    _fn.argtypes = _args
+
+EXPORTED = tuple(_SIGS)
+
+
+def _check(rc):
+    if rc != 0:
+        raise CkptError(rc, (lib.ckpt_last_error() or b"").decode("utf-8", "replace"))
+
+
+def _struct_dict(s):
+    return {n: getattr(s, n) for n, _ in s._fields_ if not n.startswith("reserved")}
+
+
+def make_config(out_dir="", device=0, host_ring_bytes=0, dma_chunk_bytes=0, pack_superchunk_bytes=0, dev_staging_bytes=0,
+                n_dma_streams=0, n_io_threads=0, window_policy=CKPT_WINDOW_D2H, o_direct=0, fsync_on_commit=0):
+    cfg = ckpt_config()
+    cfg.device = device
+    cfg.out_dir = os.fsencode(out_dir) if out_dir else None
+    cfg.host_ring_bytes = host_ring_bytes
+    cfg.dma_chunk_bytes = dma_chunk_bytes
+    cfg.pack_superchunk_bytes = pack_superchunk_bytes
+    cfg.dev_staging_bytes = dev_staging_bytes
+    cfg.n_dma_streams = n_dma_streams
+    cfg.n_io_threads = n_io_threads
+    cfg.window_policy = window_policy
+    cfg.o_direct = o_direct
+    cfg.fsync_on_commit = fsync_on_commit
+    return cfg
+
+
+def make_descs(tensors):
+    """tensors: iterable of (name, dtype_code, shape, dev_ptr, nbytes). Returns (ctypes array, keepalive list)."""
+    tensors = list(tensors)
+    arr = (ckpt_tensor_desc * max(1, len(tensors)))()
+    keep = []
+    for k, (name, dtype, shape, ptr, nbytes) in enumerate(tensors):
+        shp = (C.c_int64 * max(1, len(shape)))(*[int(s) for s in shape])
+        nm = name.encode("utf-8") if isinstance(name, str) else name
+        keep += [shp, nm]
+        arr[k] = ckpt_tensor_desc(nm, dtype, len(shape), C.cast(shp, C.POINTER(C.c_int64)), ptr, nbytes)
+    return arr, keep
+
+
+class Plan:
+    """ckpt_plan_*: layout, header, offsets and tile table of a tensor list, no device needed."""
+
+    def __init__(self, tensors, cfg=None):
+        cfg = cfg or make_config()
+        tensors = list(tensors)
+        arr, keep = make_descs(tensors)
+        self._h = _vp()
+        _check(lib.ckpt_plan_create(arr, len(tensors), C.byref(cfg), C.byref(self._h)))
+
+    def layout(self):
+        out = ckpt_layout()
+        _check(lib.ckpt_plan_layout(self._h, C.byref(out)))
+        return _struct_dict(out)
+
+    def header(self, it):
+        n = self.layout()["header_bytes"]
+        buf = C.create_string_buffer(n)
+        _check(lib.ckpt_plan_header(self._h, it, buf, n))
+        return buf.raw
+
+    def offsets(self):
+        n = self.layout()["n_tensors"]
+        out = (_u64 * n)()
+        _check(lib.ckpt_plan_offsets(self._h, out, n))
+        return list(out)
+
+    def tiles(self):
+        n = self.layout()["n_tiles"]
+        out = (ckpt_tile * n)()
+        _check(lib.ckpt_plan_tiles(self._h, 0, n, out))
+        return out
+
+    def superchunk_tiles(self):
+        n = self.layout()["n_superchunks"] + 1
+        out = (_u64 * n)()
+        _check(lib.ckpt_plan_superchunk_tiles(self._h, out, n))
+        return list(out)
+
+    def close(self):
+        if self._h:
+            lib.ckpt_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+
+class Checkpointer:
+    """One ckpt_ctx. Method names are the C entry points without the prefix."""
+
+    def __init__(self, cfg):
+        self._h = _vp()
+        self._cfg = cfg
+        _check(lib.ckpt_init(C.byref(cfg), C.byref(self._h)))
+
+    def register_tensors(self, tensors):
+        tensors = list(tensors)
+        arr, keep = make_descs(tensors)
+        _check(lib.ckpt_register_tensors(self._h, arr, len(tensors)))
+
+    def snapshot_async(self, it, stream):
+        _check(lib.ckpt_snapshot_async(self._h, it, stream))
+
+    def wait_immutable_window_end(self, stream, host_block=False):
+        _check(lib.ckpt_wait_immutable_window_end(self._h, stream, 1 if host_block else 0))
+
+    def flush(self, it=CKPT_ITER_ALL):
+        _check(lib.ckpt_flush(self._h, it))
+
+    def restore(self, path, stream):
+        it = _u64(0)
+        _check(lib.ckpt_restore(self._h, os.fsencode(path), stream, C.byref(it)))
+        return it.value
+
+    def layout(self):
+        out = ckpt_layout()
+        _check(lib.ckpt_get_layout(self._h, C.byref(out)))
+        return _struct_dict(out)
+
+    def stats(self, it):
+        out = ckpt_stats()
+        _check(lib.ckpt_get_stats(self._h, it, C.byref(out)))
+        return _struct_dict(out)
+
+    def file_name(self, it):
+        buf = C.create_string_buffer(4096)
+        _check(lib.ckpt_file_name(self._h, it, buf, 4096))
+        return os.fsdecode(buf.value)
+
+    def destroy(self):
+        if self._h:
+            h, self._h = self._h, None
+            _check(lib.ckpt_destroy(h))
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def _proxy(rc, what):
+    if rc != 0:
+        raise CkptError(rc, what + " failed")
+
+
+def proxy_gemm_bf16(a, b, c, m, n, k, stream):
+    _proxy(lib.proxy_gemm_bf16(a, b, c, m, n, k, stream), "proxy_gemm_bf16")
+
+
+def proxy_fill_state(p, master, m, v, numel, seed, tensor, stream):
+    _proxy(lib.proxy_fill_state(p, master, m, v, numel, seed, tensor, stream), "proxy_fill_state")
+
+
+def proxy_adam_step(p, master, m, v, numel, seed, tensor, step, stream, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8):
+    _proxy(lib.proxy_adam_step(p, master, m, v, numel, seed, tensor, step, lr, beta1, beta2, eps, stream), "proxy_adam_step")
+
+
+def proxy_fill_words(w, n_words, seed, stream):
+    _proxy(lib.proxy_fill_words(w, n_words, seed, stream), "proxy_fill_words")
+
+
+def proxy_mutate_words(w, n_words, step, stream):
+    _proxy(lib.proxy_mutate_words(w, n_words, step, stream), "proxy_mutate_words")
+
+
+def proxy_devcopy(dst, src, nbytes, stream):
+    _proxy(lib.proxy_devcopy(dst, src, nbytes, stream), "proxy_devcopy")

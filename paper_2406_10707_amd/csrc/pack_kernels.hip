@@ -1,0 +1,229 @@
+// Pack and scatter kernels for gfx950: pure byte movement between scattered tensors and the
+// contiguous, 4 KiB-aligned staging image of the checkpoint's data region. HBM-bound.
+//
+// One wavefront (64 lanes) walks one tile of the descriptor table: up to 64 KiB of destination,
+// 16 bytes per lane per step, 1 KiB per wavefront step, several steps in flight. The staging side is
+// always 16-byte aligned. The tensor side is aligned to its element size only; when it is not
+// 16-byte aligned each lane reads the two aligned 16-byte words that cover its bytes and
+// byte-shifts them together (v_alignbyte), so every global access is an aligned 128-bit one. An
+// aligned 16-byte word that holds at least one byte of a tensor lies in the tensor's page, so those
+// reads stay inside mapped memory; words that hold no byte of the tensor are never read.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ckpt.h"
+
+namespace dsllm {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = 64 * kWavesPerBlock;
+constexpr int kUnroll = 8;
+
+__device__ __forceinline__ u32x4 ld16(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void st16(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+
+// A value that is the same in every lane of the wavefront, moved to scalar registers. The builtin
+// returns a signed int: each half goes through uint32_t before widening, or the low half would be
+// sign-extended into the high one.
+__device__ __forceinline__ uint32_t uniform_u32(uint32_t v) { return uint32_t(__builtin_amdgcn_readfirstlane(v)); }
+__device__ __forceinline__ uint64_t uniform_u64(uint64_t v) {
+    const uint32_t lo = uniform_u32(uint32_t(v)), hi = uniform_u32(uint32_t(v >> 32));
+    return (uint64_t(hi) << 32) | uint64_t(lo);
+}
+
+// bytes [sh, sh+16) of the 32-byte string lo||hi, for sh = 4*W + b, 1 <= sh <= 15
+template <int W>
+__device__ __forceinline__ u32x4 funnel(u32x4 lo, u32x4 hi, uint32_t b) {
+    uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    u32x4 o;
+    o.x = __builtin_amdgcn_alignbyte(w[W + 1], w[W + 0], b);
+    o.y = __builtin_amdgcn_alignbyte(w[W + 2], w[W + 1], b);
+    o.z = __builtin_amdgcn_alignbyte(w[W + 3], w[W + 2], b);
+    o.w = __builtin_amdgcn_alignbyte(w[W + 4], w[W + 3], b);
+    return o;
+}
+
+// keep the first `keep` bytes (0..16) of v, zero the rest
+__device__ __forceinline__ u32x4 keep_bytes(u32x4 v, uint32_t keep) {
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        uint32_t lo = 4u * j;
+        if (keep <= lo) w[j] = 0;
+        else if (keep < lo + 4) w[j] &= (1u << (8 * (keep - lo))) - 1u;
+    }
+    return u32x4{w[0], w[1], w[2], w[3]};
+}
+
+// ---------------------------------------------------------------- pack: tensors -> staging
+
+// Copies the full 16-byte words of a tile whose source is misaligned by 4*W+b bytes.
+template <int W>
+__device__ __forceinline__ void pack_shifted(const u32x4 *src_al, u32x4 *dst, uint32_t n_full, uint32_t b, uint32_t lane) {
+    uint32_t i = lane;
+    for (; i + 64 * (kUnroll - 1) < n_full; i += 64 * kUnroll) {
+        u32x4 lo[kUnroll], hi[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; u++) { lo[u] = ld16(src_al + i + 64 * u); hi[u] = ld16(src_al + i + 64 * u + 1); }
+#pragma unroll
+        for (int u = 0; u < kUnroll; u++) st16(dst + i + 64 * u, funnel<W>(lo[u], hi[u], b));
+    }
+    for (; i < n_full; i += 64) st16(dst + i, funnel<W>(ld16(src_al + i), ld16(src_al + i + 1), b));
+}
+
+__global__ __launch_bounds__(kBlock) void pack_kernel(const ckpt_tile *__restrict__ tiles, uint64_t n_tiles,
+                                                     uint8_t *__restrict__ slot_base, uint64_t slot_data_off) {
+    const uint32_t lane = threadIdx.x & 63;
+    const uint64_t t = uint64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+    if (t >= n_tiles) return;
+    // the descriptor is the same for the whole wavefront: keep it in scalar registers
+    const ckpt_tile *tp = tiles + t;
+    const uint64_t src = uniform_u64(tp->src);
+    const uint64_t dst_off = uniform_u64(tp->dst_off);
+    const uint32_t copy_bytes = uniform_u32(tp->copy_bytes);
+    const uint32_t total_bytes = uniform_u32(tp->total_bytes);
+
+    u32x4 *dst = reinterpret_cast<u32x4 *>(slot_base + (dst_off - slot_data_off));
+    const uint32_t n_total = total_bytes >> 4;   // 16-byte words to write
+    const uint32_t n_full = copy_bytes >> 4;     // of which fully covered by source bytes
+    const uint32_t tail = copy_bytes & 15;       // source bytes in word n_full
+    const uint32_t sh = uint32_t(src) & 15;
+
+    if (sh == 0) {
+        const u32x4 *s = reinterpret_cast<const u32x4 *>(src);
+        uint32_t i = lane;
+        for (; i + 64 * (kUnroll - 1) < n_full; i += 64 * kUnroll) {
+            u32x4 v[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; u++) v[u] = ld16(s + i + 64 * u);
+#pragma unroll
+            for (int u = 0; u < kUnroll; u++) st16(dst + i + 64 * u, v[u]);
+        }
+        for (; i < n_full; i += 64) st16(dst + i, ld16(s + i));
+        if (tail && lane == 0) st16(dst + n_full, keep_bytes(ld16(s + n_full), tail));
+    } else {
+        const u32x4 *s = reinterpret_cast<const u32x4 *>(src - sh);
+        const uint32_t b = sh & 3;
+        switch (sh >> 2) {
+            case 0: pack_shifted<0>(s, dst, n_full, b, lane); break;
+            case 1: pack_shifted<1>(s, dst, n_full, b, lane); break;
+            case 2: pack_shifted<2>(s, dst, n_full, b, lane); break;
+            default: pack_shifted<3>(s, dst, n_full, b, lane); break;
+        }
+        if (tail && lane == 0) {
+            // word n_full of the aligned source holds source bytes; word n_full+1 only if sh + tail > 16
+            u32x4 lo = ld16(s + n_full);
+            u32x4 hi = (sh + tail > 16) ? ld16(s + n_full + 1) : u32x4{0, 0, 0, 0};
+            u32x4 v;
+            switch (sh >> 2) {
+                case 0: v = funnel<0>(lo, hi, b); break;
+                case 1: v = funnel<1>(lo, hi, b); break;
+                case 2: v = funnel<2>(lo, hi, b); break;
+                default: v = funnel<3>(lo, hi, b); break;
+            }
+            st16(dst + n_full, keep_bytes(v, tail));
+        }
+    }
+    // zero padding after the tensor's last byte
+    const uint32_t z0 = n_full + (tail ? 1u : 0u);
+    for (uint32_t i = z0 + lane; i < n_total; i += 64) st16(dst + i, u32x4{0, 0, 0, 0});
+}
+
+// ---------------------------------------------------------------- scatter: staging -> tensors
+
+// Writes destination-aligned 16-byte words [first, first+count) of a tensor range whose start is
+// misaligned by `sh` bytes relative to the (aligned) staging source: word j takes staging bytes
+// [16*j - sh, 16*j - sh + 16).
+template <int W>
+__device__ __forceinline__ void scatter_shifted(const u32x4 *src, u32x4 *dst_al, uint32_t n_words, uint32_t b, uint32_t lane) {
+    // dst_al[j] for j = 1..n_words gets bytes [(16-sh) + 16*(j-1), +16) of src = funnel of src[j-1], src[j] at shift 16-sh
+    uint32_t i = lane;
+    for (; i + 64 * (kUnroll - 1) < n_words; i += 64 * kUnroll) {
+        u32x4 lo[kUnroll], hi[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; u++) { lo[u] = ld16(src + i + 64 * u); hi[u] = ld16(src + i + 64 * u + 1); }
+#pragma unroll
+        for (int u = 0; u < kUnroll; u++) st16(dst_al + 1 + i + 64 * u, funnel<W>(lo[u], hi[u], b));
+    }
+    for (; i < n_words; i += 64) st16(dst_al + 1 + i, funnel<W>(ld16(src + i), ld16(src + i + 1), b));
+}
+
+__global__ __launch_bounds__(kBlock) void scatter_kernel(const ckpt_tile *__restrict__ tiles, uint64_t n_tiles,
+                                                        const uint8_t *__restrict__ slot_base, uint64_t slot_data_off) {
+    const uint32_t lane = threadIdx.x & 63;
+    const uint64_t t = uint64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+    if (t >= n_tiles) return;
+    const ckpt_tile *tp = tiles + t;
+    const uint64_t dstp = uniform_u64(tp->src);
+    const uint64_t off = uniform_u64(tp->dst_off);
+    const uint32_t nbytes = uniform_u32(tp->copy_bytes);
+    if (nbytes == 0) return;
+    const uint8_t *src = slot_base + (off - slot_data_off);   // 16-byte aligned
+    uint8_t *dst = reinterpret_cast<uint8_t *>(dstp);
+    const uint32_t mis = uint32_t(dstp) & 15;
+
+    if (mis == 0) {
+        const u32x4 *s = reinterpret_cast<const u32x4 *>(src);
+        u32x4 *d = reinterpret_cast<u32x4 *>(dst);
+        const uint32_t n_full = nbytes >> 4;
+        uint32_t i = lane;
+        for (; i + 64 * (kUnroll - 1) < n_full; i += 64 * kUnroll) {
+            u32x4 v[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; u++) v[u] = ld16(s + i + 64 * u);
+#pragma unroll
+            for (int u = 0; u < kUnroll; u++) st16(d + i + 64 * u, v[u]);
+        }
+        for (; i < n_full; i += 64) st16(d + i, ld16(s + i));
+        const uint32_t tail = nbytes & 15;       // bytes past the last full word: byte stores only
+        if (lane < tail) dst[(n_full << 4) + lane] = src[(n_full << 4) + lane];
+        return;
+    }
+    // head: bytes up to the first 16-byte boundary of the destination (byte stores; the neighbouring
+    // bytes of that word belong to another tensor and may be written concurrently)
+    const uint32_t head = (16 - mis) < nbytes ? (16 - mis) : nbytes;
+    if (lane < head) dst[lane] = src[lane];
+    const uint32_t rest = nbytes - head;
+    const uint32_t n_words = rest >> 4;            // aligned destination words fully inside the range
+    if (n_words) {
+        // destination word j (1-based from the aligned address below dst) = staging bytes [head + 16*(j-1), +16)
+        // = bytes [sh, sh+16) of staging words (j-1, j) with sh = head (1..15)
+        const u32x4 *s = reinterpret_cast<const u32x4 *>(src);
+        u32x4 *d_al = reinterpret_cast<u32x4 *>(dst - mis);
+        const uint32_t b = head & 3;
+        // staging word index n_words is read as the upper half for the last destination word; it
+        // exists inside the tile because head + 16*n_words <= nbytes <= total_bytes and the upper half
+        // is needed only when head > 0, i.e. 16*n_words < nbytes.
+        switch (head >> 2) {
+            case 0: scatter_shifted<0>(s, d_al, n_words, b, lane); break;
+            case 1: scatter_shifted<1>(s, d_al, n_words, b, lane); break;
+            case 2: scatter_shifted<2>(s, d_al, n_words, b, lane); break;
+            default: scatter_shifted<3>(s, d_al, n_words, b, lane); break;
+        }
+    }
+    const uint32_t tail = rest & 15;
+    const uint32_t done = head + (n_words << 4);
+    if (lane < tail) dst[done + lane] = src[done + lane];
+}
+
+// ---------------------------------------------------------------- launchers (host)
+
+static inline unsigned grid_for(uint64_t n_tiles) { return unsigned((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock); }
+
+hipError_t launch_pack(const ckpt_tile *dev_tiles, uint64_t n_tiles, void *slot_base, uint64_t slot_data_off, hipStream_t stream) {
+    if (n_tiles == 0) return hipSuccess;
+    hipLaunchKernelGGL(pack_kernel, dim3(grid_for(n_tiles)), dim3(kBlock), 0, stream, dev_tiles, n_tiles,
+                       static_cast<uint8_t *>(slot_base), slot_data_off);
+    return hipGetLastError();
+}
+
+hipError_t launch_scatter(const ckpt_tile *dev_tiles, uint64_t n_tiles, const void *slot_base, uint64_t slot_data_off, hipStream_t stream) {
+    if (n_tiles == 0) return hipSuccess;
+    hipLaunchKernelGGL(scatter_kernel, dim3(grid_for(n_tiles)), dim3(kBlock), 0, stream, dev_tiles, n_tiles,
+                       static_cast<const uint8_t *>(slot_base), slot_data_off);
+    return hipGetLastError();
+}
+
+}  // namespace dsllm

@@ -1,0 +1,166 @@
+#include "plan.hpp"
+
+#include <cstring>
+
+namespace dsllm {
+
+static inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+uint64_t dtype_size(int32_t dtype) {
+    switch (dtype) {
+        case CKPT_BF16: case CKPT_F16: return 2;
+        case CKPT_F32: case CKPT_I32: return 4;
+        case CKPT_U8: return 1;
+        case CKPT_I64: return 8;
+        default: return 0;
+    }
+}
+
+int resolve_config(const ckpt_config *in, ResolvedConfig *out, std::string *err) {
+    ResolvedConfig c;
+    c.dma_chunk_bytes = in->dma_chunk_bytes ? in->dma_chunk_bytes : (64ull << 20);
+    c.pack_superchunk_bytes = in->pack_superchunk_bytes ? in->pack_superchunk_bytes : (1ull << 30);
+    c.host_ring_bytes = in->host_ring_bytes ? in->host_ring_bytes : (8ull << 30);
+    c.dev_staging_bytes = in->dev_staging_bytes ? in->dev_staging_bytes : 2 * c.pack_superchunk_bytes;
+    c.n_dma_streams = in->n_dma_streams ? in->n_dma_streams : 2;
+    c.n_io_threads = in->n_io_threads ? in->n_io_threads : 4;
+    c.window_policy = in->window_policy;
+    c.o_direct = in->o_direct;
+    c.fsync_on_commit = in->fsync_on_commit;
+    for (int r : in->reserved) if (r != 0) { *err = "config: reserved fields must be zero"; return CKPT_EINVAL; }
+    if (c.dma_chunk_bytes % kTileBytes != 0) { *err = "config: dma_chunk_bytes must be a multiple of 64 KiB"; return CKPT_EINVAL; }
+    if (c.pack_superchunk_bytes % c.dma_chunk_bytes != 0) { *err = "config: pack_superchunk_bytes must be a multiple of dma_chunk_bytes"; return CKPT_EINVAL; }
+    if (c.pack_superchunk_bytes > (64ull << 30)) { *err = "config: pack_superchunk_bytes above 64 GiB"; return CKPT_EINVAL; }
+    if (c.n_dma_streams < 1 || c.n_dma_streams > 8) { *err = "config: n_dma_streams must be 1..8"; return CKPT_EINVAL; }
+    if (c.n_io_threads < 1 || c.n_io_threads > 64) { *err = "config: n_io_threads must be 1..64"; return CKPT_EINVAL; }
+    if (c.window_policy != CKPT_WINDOW_D2H && c.window_policy != CKPT_WINDOW_PACK) { *err = "config: unknown window_policy"; return CKPT_EINVAL; }
+    c.host_ring_bytes = c.host_ring_bytes / c.dma_chunk_bytes * c.dma_chunk_bytes;
+    if (c.host_ring_bytes < 2 * c.dma_chunk_bytes) c.host_ring_bytes = 2 * c.dma_chunk_bytes;
+    c.dev_staging_bytes = c.dev_staging_bytes / c.pack_superchunk_bytes * c.pack_superchunk_bytes;
+    if (c.dev_staging_bytes < 2 * c.pack_superchunk_bytes) c.dev_staging_bytes = 2 * c.pack_superchunk_bytes;
+    *out = c;
+    return CKPT_OK;
+}
+
+static void put_le(uint8_t *p, uint64_t v, int n) { for (int i = 0; i < n; i++) p[i] = uint8_t(v >> (8 * i)); }
+
+int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cfg, Plan *out, std::string *err) {
+    if (!descs || n == 0) { *err = "no tensors"; return CKPT_EINVAL; }
+    Plan p;
+    p.cfg = cfg;
+    p.tensors.reserve(n);
+    uint64_t table = 0;
+    for (size_t k = 0; k < n; k++) {
+        const ckpt_tensor_desc &d = descs[k];
+        uint64_t es = dtype_size(d.dtype);
+        size_t len = d.name ? strlen(d.name) : 0;
+        if (len < 1 || len > 65535) { *err = "tensor " + std::to_string(k) + ": name must be 1..65535 bytes"; return CKPT_EINVAL; }
+        if (es == 0) { *err = std::string("tensor ") + d.name + ": unknown dtype"; return CKPT_EINVAL; }
+        if (d.ndim > 8 || (d.ndim > 0 && !d.shape)) { *err = std::string("tensor ") + d.name + ": bad ndim/shape"; return CKPT_EINVAL; }
+        uint64_t numel = 1;
+        TensorInfo t;
+        for (uint32_t i = 0; i < d.ndim; i++) {
+            if (d.shape[i] < 0) { *err = std::string("tensor ") + d.name + ": negative dimension"; return CKPT_EINVAL; }
+            numel *= uint64_t(d.shape[i]);
+            t.shape.push_back(d.shape[i]);
+        }
+        if (d.nbytes == 0 || d.nbytes != numel * es) { *err = std::string("tensor ") + d.name + ": nbytes must be > 0 and equal dtype size x shape"; return CKPT_EINVAL; }
+        if (uint64_t(d.dev_ptr) % es != 0) { *err = std::string("tensor ") + d.name + ": address not aligned to its element size"; return CKPT_EINVAL; }
+        t.name.assign(d.name, len);
+        t.dtype = d.dtype;
+        t.dev_addr = uint64_t(d.dev_ptr);
+        t.nbytes = d.nbytes;
+        t.file_off = 0;
+        table += 2 + len + 2 + 8ull * d.ndim + 16;
+        p.payload_bytes += d.nbytes;
+        p.tensors.push_back(std::move(t));
+    }
+    p.header_bytes = align_up(kFixedHeader + table, kAlign);
+    uint64_t off = p.header_bytes;
+    for (auto &t : p.tensors) { t.file_off = off; off += align_up(t.nbytes, kAlign); }
+    p.data_bytes = off - p.header_bytes;
+
+    // header image (iter left zero; patched per snapshot at byte 16)
+    p.header.assign(p.header_bytes, 0);
+    uint8_t *h = p.header.data();
+    static const uint8_t magic[8] = {'D', 'S', 'L', 'L', 'M', 'C', 'K', 1};
+    memcpy(h, magic, 8);
+    put_le(h + 8, 1, 4);
+    put_le(h + 12, kAlign, 4);
+    put_le(h + 24, n, 8);
+    put_le(h + 32, p.header_bytes, 8);
+    put_le(h + 40, p.data_bytes, 8);
+    put_le(h + 48, p.file_bytes(), 8);
+    uint8_t *w = h + kFixedHeader;
+    for (const auto &t : p.tensors) {
+        put_le(w, t.name.size(), 2); w += 2;
+        memcpy(w, t.name.data(), t.name.size()); w += t.name.size();
+        *w++ = uint8_t(t.dtype);
+        *w++ = uint8_t(t.shape.size());
+        for (int64_t s : t.shape) { put_le(w, uint64_t(s), 8); w += 8; }
+        put_le(w, t.file_off, 8); w += 8;
+        put_le(w, t.nbytes, 8); w += 8;
+    }
+
+    // chunks and super-chunks partition the data region at fixed strides
+    const uint64_t SC = cfg.pack_superchunk_bytes, CH = cfg.dma_chunk_bytes;
+    p.n_chunks = (p.data_bytes + CH - 1) / CH;
+    p.n_superchunks = (p.data_bytes + SC - 1) / SC;
+
+    // tiles: each tensor's padded extent is cut at its start and at every global multiple of the tile size,
+    // so no tile crosses a tensor, chunk or super-chunk boundary (those are all multiples of the tile size)
+    p.sc_first_tile.assign(p.n_superchunks + 1, 0);
+    uint64_t next_sc = 0;
+    for (const auto &t : p.tensors) {
+        uint64_t d0 = t.file_off - p.header_bytes;             // data-region offset of the tensor
+        uint64_t dend = d0 + align_up(t.nbytes, kAlign);
+        uint64_t pos = d0;
+        while (pos < dend) {
+            uint64_t stop = (pos / kTileBytes + 1) * kTileBytes;
+            if (stop > dend) stop = dend;
+            while (next_sc < p.n_superchunks && pos >= next_sc * SC) p.sc_first_tile[next_sc++] = p.tiles.size();
+            ckpt_tile tile;
+            uint64_t rel = pos - d0;
+            uint64_t copy = rel >= t.nbytes ? 0 : (t.nbytes - rel < stop - pos ? t.nbytes - rel : stop - pos);
+            tile.src = t.dev_addr + rel;
+            tile.dst_off = pos;
+            tile.copy_bytes = uint32_t(copy);
+            tile.total_bytes = uint32_t(stop - pos);
+            tile.reserved = 0;
+            p.tiles.push_back(tile);
+            pos = stop;
+        }
+    }
+    while (next_sc <= p.n_superchunks) p.sc_first_tile[next_sc++] = p.tiles.size();
+    if (!verify_plan(p, err)) return CKPT_EINVAL;
+    *out = std::move(p);
+    return CKPT_OK;
+}
+
+bool verify_plan(const Plan &p, std::string *err) {
+    const uint64_t SC = p.cfg.pack_superchunk_bytes;
+    uint64_t expect = 0;
+    size_t k = 0;  // tensor the tile should belong to
+    if (p.sc_first_tile.size() != p.n_superchunks + 1 || p.sc_first_tile.back() != p.tiles.size()) { *err = "plan: super-chunk tile index broken"; return false; }
+    for (size_t i = 0; i < p.tiles.size(); i++) {
+        const ckpt_tile &t = p.tiles[i];
+        if (t.dst_off != expect || t.total_bytes == 0 || t.total_bytes % 16 || t.dst_off % 16 || t.copy_bytes > t.total_bytes ||
+            t.total_bytes > kTileBytes) { *err = "plan: tile " + std::to_string(i) + " malformed"; return false; }
+        if (t.dst_off / SC != (t.dst_off + t.total_bytes - 1) / SC) { *err = "plan: tile crosses a super-chunk"; return false; }
+        while (k < p.tensors.size() && t.dst_off >= p.tensors[k].file_off - p.header_bytes + align_up(p.tensors[k].nbytes, kAlign)) k++;
+        if (k >= p.tensors.size()) { *err = "plan: tile beyond last tensor"; return false; }
+        const TensorInfo &ti = p.tensors[k];
+        uint64_t rel = t.dst_off - (ti.file_off - p.header_bytes);
+        if (t.copy_bytes) {
+            if (t.src != ti.dev_addr + rel || rel + t.copy_bytes > ti.nbytes) { *err = "plan: tile source outside its tensor"; return false; }
+        }
+        if (rel + t.total_bytes > align_up(ti.nbytes, kAlign)) { *err = "plan: tile crosses a tensor boundary"; return false; }
+        uint64_t s = t.dst_off / SC;
+        if (i < p.sc_first_tile[s] || i >= p.sc_first_tile[s + 1]) { *err = "plan: tile not in its super-chunk's range"; return false; }
+        expect += t.total_bytes;
+    }
+    if (expect != p.data_bytes) { *err = "plan: tiles do not cover the data region"; return false; }
+    return true;
+}
+
+}  // namespace dsllm

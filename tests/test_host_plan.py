@@ -1,0 +1,145 @@
+"""Host logic of the HIP library, no GPU needed: the shared library loads and exports every symbol
+its headers declare; the plan (header bytes, file offsets, tile table) agrees with the CPU oracle."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2406_10707_amd import binding as B
+from paper_2406_10707_amd import shards
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE_BASE = 0x7000_0000_0000
+
+
+def _declared_symbols():
+    names = []
+    for h in ("ckpt.h", "ckpt_proxy.h"):
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b((?:ckpt|proxy)_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    declared = _declared_symbols()
+    assert len(declared) >= 20
+    raw = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(raw, name), name
+    assert set(declared) == set(B.EXPORTED)
+
+
+def _fake_descs(spec):
+    """Device addresses are never dereferenced by the planner: lay tensors out in a fake address space."""
+    addr = FAKE_BASE
+    flat_base = []
+    for n in spec.flat_buffers:
+        flat_base.append(addr)
+        addr += n + 4096
+    descs = []
+    for t in spec.tensors:
+        if t.buffer >= 0:
+            p = flat_base[t.buffer] + t.offset
+        else:
+            p = addr
+            addr += (t.nbytes + 511) // 512 * 512
+        descs.append((t.name, t.dtype, t.shape, p, t.nbytes))
+    return descs, addr - FAKE_BASE
+
+
+@pytest.mark.parametrize("tiny", [True, False])
+@pytest.mark.parametrize("config", [1, 2, 3, 4, 5])
+def test_header_and_offsets_match_oracle(config, tiny):
+    spec = shards.make_shard(config, tiny=tiny)
+    descs, _ = _fake_descs(spec)
+    plan = B.Plan(descs)
+    ots = [(t.name, t.dtype, t.shape, None) for t in spec.tensors]
+    assert plan.header(77) == oracle.build_header(ots, 77)
+    lay = plan.layout()
+    assert lay["header_bytes"] == oracle.header_bytes(ots)
+    assert lay["data_bytes"] == oracle.data_bytes(ots)
+    assert lay["file_bytes"] == lay["header_bytes"] + lay["data_bytes"]
+    assert lay["payload_bytes"] == spec.payload_bytes
+    if tiny:
+        assert plan.offsets() == oracle.tensor_offsets(ots)
+    plan.close()
+
+
+@pytest.mark.parametrize("config", [1, 5])
+@pytest.mark.parametrize("chunk,superchunk", [(64 << 10, 128 << 10), (128 << 10, 1 << 20)])
+def test_tile_table_reproduces_the_data_region(config, chunk, superchunk):
+    """Walk the tile table on the host over a fake address space and compare the bytes it would
+    produce with the oracle's data region: pins tile sources, destinations, zero padding and that
+    no tile crosses a super-chunk."""
+    spec = shards.make_shard(config, tiny=True)
+    descs, span = _fake_descs(spec)
+    mem = np.full(span + 64, 0xEE, dtype=np.uint8)
+    host = []
+    for k, (name, dtype, shape, p, nb) in enumerate(descs):
+        v = shards.host_values(spec, k)
+        mem[p - FAKE_BASE:p - FAKE_BASE + nb] = v
+        host.append(v)
+    cfg = B.make_config(dma_chunk_bytes=chunk, pack_superchunk_bytes=superchunk)
+    plan = B.Plan(descs, cfg)
+    lay = plan.layout()
+    tiles = plan.tiles()
+    out = np.full(lay["data_bytes"], 0xCC, dtype=np.uint8)
+    pos = 0
+    for t in tiles:
+        assert t.dst_off == pos and t.dst_off % 16 == 0 and t.total_bytes % 16 == 0 and 0 < t.total_bytes <= lay["tile_bytes"]
+        assert t.dst_off // superchunk == (t.dst_off + t.total_bytes - 1) // superchunk
+        s = t.src - FAKE_BASE
+        out[pos:pos + t.copy_bytes] = mem[s:s + t.copy_bytes]
+        out[pos + t.copy_bytes:pos + t.total_bytes] = 0
+        pos += t.total_bytes
+    assert pos == lay["data_bytes"]
+    ots = [(t.name, t.dtype, t.shape, h) for t, h in zip(spec.tensors, host)]
+    want = oracle.serialize_bytes(ots, 0)
+    assert out.tobytes() == want[lay["header_bytes"]:]
+    first = plan.superchunk_tiles()
+    assert first[0] == 0 and first[-1] == len(tiles) and lay["n_superchunks"] == -(-lay["data_bytes"] // superchunk)
+    for s in range(lay["n_superchunks"]):
+        for i in range(first[s], first[s + 1]):
+            assert tiles[i].dst_off // superchunk == s
+    assert lay["n_chunks"] == -(-lay["data_bytes"] // chunk)
+    plan.close()
+
+
+def test_full_size_tile_counts():
+    spec = shards.make_shard(2)
+    descs, _ = _fake_descs(spec)
+    plan = B.Plan(descs)
+    lay = plan.layout()
+    assert lay["n_superchunks"] == -(-lay["data_bytes"] // (1 << 30)) and lay["n_chunks"] == -(-lay["data_bytes"] // (64 << 20))
+    assert lay["data_bytes"] // lay["tile_bytes"] <= lay["n_tiles"] <= lay["data_bytes"] // lay["tile_bytes"] + 2 * lay["n_tensors"]
+    plan.close()
+
+
+def _expect(code, descs, **cfg):
+    with pytest.raises(B.CkptError) as e:
+        B.Plan(descs, B.make_config(**cfg))
+    assert e.value.code == code and e.value.text
+
+
+def test_bad_descriptions_and_configs_are_rejected():
+    ok = ("t", B.CKPT_F32, (4,), FAKE_BASE, 16)
+    B.Plan([ok]).close()
+    _expect(B.CKPT_EINVAL, [("t", 9, (4,), FAKE_BASE, 16)])                   # unknown dtype
+    _expect(B.CKPT_EINVAL, [("t", B.CKPT_F32, (4,), FAKE_BASE, 12)])          # nbytes != dtype x shape
+    _expect(B.CKPT_EINVAL, [("t", B.CKPT_F32, (0,), FAKE_BASE, 0)])           # empty tensor
+    _expect(B.CKPT_EINVAL, [("", B.CKPT_F32, (4,), FAKE_BASE, 16)])           # empty name
+    _expect(B.CKPT_EINVAL, [("t", B.CKPT_F32, (4,), FAKE_BASE + 2, 16)])      # address not element aligned
+    _expect(B.CKPT_EINVAL, [("t", B.CKPT_F32, (-4,), FAKE_BASE, 16)])         # negative dimension
+    _expect(B.CKPT_EINVAL, [])                                                # nothing to register
+    _expect(B.CKPT_EINVAL, [ok], dma_chunk_bytes=4096)                        # not a multiple of the tile size
+    _expect(B.CKPT_EINVAL, [ok], dma_chunk_bytes=1 << 20, pack_superchunk_bytes=(1 << 20) + (64 << 10))
+    _expect(B.CKPT_EINVAL, [ok], n_dma_streams=9)
+    _expect(B.CKPT_EINVAL, [ok], window_policy=7)
+    # scalars are allowed: empty shape, one element
+    p = B.Plan([("s", B.CKPT_I64, (), FAKE_BASE, 8)])
+    assert p.layout()["data_bytes"] == 4096
+    p.close()
