@@ -83,7 +83,7 @@ _SIGS = {
     "ckpt_restore": (C.c_int, [_vp, C.c_char_p, _vp, C.POINTER(_u64)]),
     "ckpt_get_layout": (C.c_int, [_vp, C.POINTER(ckpt_layout)]),
     "ckpt_get_stats": (C.c_int, [_vp, _u64, C.POINTER(ckpt_stats)]),
-    "ckpt_file_name": (C.c_int, [_vp, C.c_char_p, C.c_size_t]),
+    "ckpt_file_name": (C.c_int, [_vp, _u64, C.c_char_p, C.c_size_t]),
     "ckpt_last_error": (C.c_char_p, []),
     "ckpt_destroy": (C.c_int, [_vp]),
     "proxy_gemm_bf16": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _i32, _vp]),
