@@ -1,0 +1,324 @@
+#!/usr/bin/env python3
+"""Benchmark of the snapshot hot path on one MI355X.
+
+A step is one training iteration of the synthetic proxy: a bf16 GEMM phase of fixed length
+(forward+backward stand-in), the wait for the immutable window's end, the Adam update over the whole
+shard, and, every `ckpt_every` steps, a snapshot request. Everything the checkpoint path does (pack
+kernels, device-to-host copies into the pinned ring, file writes) runs in the library, overlapped
+with the following steps. Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5]
+"""
+import argparse
+import json
+import os
+import shutil
+import statistics
+import sys
+import tempfile
+import time
+
+# More hardware queues than the four HIP uses by default, so that the compute stream, the pack stream
+# and the copy streams each get one (must be set before the HIP runtime starts).
+if int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < 8:
+    os.environ["GPU_MAX_HW_QUEUES"] = "8"
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: Llama-7B-shaped shard, 94 GB)")
+    ap.add_argument("--ckpt-every", type=int, default=0, help="0: the workload's own interval")
+    ap.add_argument("--compute-ms", type=float, default=0.0, help="0: the workload's own forward+backward length")
+    ap.add_argument("--ring-gib", type=float, default=0.0, help="0: the whole data region, at most 64 GiB")
+    ap.add_argument("--staging-gib", type=float, default=0.0, help="0: two super-chunks")
+    ap.add_argument("--chunk-mib", type=int, default=64)
+    ap.add_argument("--superchunk-mib", type=int, default=1024)
+    ap.add_argument("--dma-streams", type=int, default=2)
+    ap.add_argument("--io-threads", type=int, default=12)
+    ap.add_argument("--policy", choices=["d2h", "pack"], default="d2h")
+    ap.add_argument("--io-mode", choices=["auto", "pwrite", "mmap"], default="auto")
+    ap.add_argument("--keep-last", type=int, default=1, help="checkpoint files kept; older ones are recycled in place (0: keep all)")
+    ap.add_argument("--prealloc", type=int, default=2, help="spare files pre-allocated at registration")
+    ap.add_argument("--out-dir", default="")
+    ap.add_argument("--baseline-steps", type=int, default=6)
+    ap.add_argument("--oracle-sample-gb", type=float, default=12.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-restore", action="store_true")
+    return ap.parse_args()
+
+
+def measure_link_peak(torch, dev, s, nbytes=1 << 30, reps=10):
+    """Best of `reps` single pinned copies of 1 GiB in each direction (GB/s)."""
+    d = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    h = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+    h.zero_()
+    best = {"d2h": 0.0, "h2d": 0.0}
+    with torch.cuda.stream(s):
+        for name, dst, src in (("d2h", h, d), ("h2d", d, h)):
+            for _ in range(reps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(s)
+                dst.copy_(src, non_blocking=True)
+                e1.record(s)
+                e1.synchronize()
+                best[name] = max(best[name], nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del d, h
+    return best
+
+
+def measure_devcopy(torch, B, dev, s, nbytes=4 << 30, reps=5):
+    """Contiguous aligned copy kernel: the practical HBM ceiling for the pack kernel (GB/s read+write)."""
+    a = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    b = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    a.zero_()
+    best = 0.0
+    with torch.cuda.stream(s):
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(s)
+            B.proxy_devcopy(b.data_ptr(), a.data_ptr(), nbytes, s.cuda_stream)
+            e1.record(s)
+            e1.synchronize()
+            best = max(best, 2 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del a, b
+    return best
+
+
+def cpu_baseline(torch, shard, sample_bytes, out_dir):
+    """The oracle as it stands: blocking per-tensor read-back into pageable memory, then the plain C
+    serializer writing the same format to the same sink. One host thread."""
+    from oracle import oracle
+    ks, total = [], 0
+    for k, t in enumerate(shard.spec.tensors):
+        ks.append(k)
+        total += t.nbytes
+        if total >= sample_bytes:
+            break
+    path = os.path.join(out_dir, "oracle_sample.dsl")
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    host = [shard.readback(k) for k in ks]
+    tensors = [(shard.spec.tensors[k].name, shard.spec.tensors[k].dtype, shard.spec.tensors[k].shape, h) for k, h in zip(ks, host)]
+    oracle.serialize_file(tensors, 0, path)
+    dt = time.perf_counter() - t0
+    os.unlink(path)
+    return {"value": round(total / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "first %d tensors (%.2f GB) of the workload: blocking read-back + serialize to the same sink, %.1f s; box has %d cores"
+                      % (len(ks), total / 1e9, dt, os.cpu_count())}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; --gpus %d is not supported (each box has one MI355X and the "
+              "snapshot path of a shard needs no exchange between GPUs)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2406_10707_amd import binding as B
+    from paper_2406_10707_amd import harness, shards
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    spec = shards.make_shard(args.config)
+    every = args.ckpt_every or spec.ckpt_every
+    compute_ms = args.compute_ms or spec.compute_ms
+    base = args.out_dir or ("/dev/shm" if os.path.isdir("/dev/shm") else None)
+    out_dir = tempfile.mkdtemp(prefix="dsllm_bench_", dir=base)
+    try:
+        run(args, torch, B, harness, spec, every, compute_ms, out_dir, dev)
+    finally:
+        shutil.rmtree(out_dir, ignore_errors=True)
+
+
+def run(args, torch, B, harness, spec, every, compute_ms, out_dir, dev):
+    stream = harness.make_compute_stream(dev)
+    link = measure_link_peak(torch, dev, stream)
+    devcopy_gbps = measure_devcopy(torch, B, dev, stream)
+
+    shard = harness.DeviceShard(spec, dev)
+    shard.fill_device(stream)
+    stream.synchronize()
+    gemm = harness.GemmProxy(8192, dev)
+    launches, gemm_ms_per_launch = gemm.calibrate(compute_ms, stream)
+
+    policy = B.CKPT_WINDOW_PACK if args.policy == "pack" else B.CKPT_WINDOW_D2H
+    chunk = args.chunk_mib << 20
+    # the paper pre-allocates a host cache large enough for the shard; capped so that cache + one file fit the box
+    ring_bytes = int(args.ring_gib * (1 << 30)) or min(64 << 30, -(-(spec.payload_bytes + 4096 * len(spec.tensors)) // chunk) * chunk)
+    args.ring_gib = round(ring_bytes / (1 << 30), 2)
+    cfg = B.make_config(out_dir=out_dir, host_ring_bytes=ring_bytes, dma_chunk_bytes=args.chunk_mib << 20,
+                        pack_superchunk_bytes=args.superchunk_mib << 20, dev_staging_bytes=int(args.staging_gib * (1 << 30)),
+                        n_dma_streams=args.dma_streams, n_io_threads=args.io_threads, window_policy=policy,
+                        io_mode={"auto": B.CKPT_IO_AUTO, "pwrite": B.CKPT_IO_PWRITE, "mmap": B.CKPT_IO_MMAP}[args.io_mode],
+                        keep_last=args.keep_last, prealloc_files=args.prealloc if args.keep_last else 0)
+    t0 = time.perf_counter()
+    ck = B.Checkpointer(cfg)
+    ck.register_tensors(shard.descs())
+    init_s = time.perf_counter() - t0
+    lay = ck.layout()
+
+    def iteration(step, with_ckpt, marks):
+        """One step on `stream`; marks gets (start, after-gemm, end) events."""
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record(stream)
+        gemm.run(launches, stream)
+        e[1].record(stream)
+        if with_ckpt:
+            ck.wait_immutable_window_end(stream.cuda_stream)
+        shard.update(step, stream)
+        if with_ckpt and step % every == 0:
+            ck.snapshot_async(step, stream.cuda_stream)
+            requested.append(step)
+        e[2].record(stream)
+        marks.append(e)
+
+    requested, live_files = [], []
+
+    def reap(block=False):
+        """Unlink committed checkpoint files except the newest (the sink may be tmpfs, i.e. host memory).
+        With keep_last > 0 the library retires old files itself."""
+        if args.keep_last:
+            return
+        for it in live_files[:-1]:
+            if block:
+                ck.flush(it)
+            if ck.stats(it)["committed"]:
+                os.unlink(ck.file_name(it))
+                live_files.remove(it)
+
+    with torch.cuda.stream(stream):
+        # ---- baseline: same steps, checkpointing off
+        marks = []
+        for i in range(2 + args.baseline_steps):
+            iteration(1000000 + i, False, marks)
+        stream.synchronize()
+        base_iter_ms = statistics.median(m[0].elapsed_time(m[2]) for m in marks[2:])
+        base_gemm_ms = statistics.median(m[0].elapsed_time(m[1]) for m in marks[2:])
+
+        # ---- warm-up with checkpointing (untimed)
+        step = 0
+        wmarks = []
+        for _ in range(args.warmup):
+            step += 1
+            n_before = len(requested)
+            iteration(step, True, wmarks)
+            if len(requested) > n_before:
+                live_files.append(requested[-1])
+            reap()
+        torch.cuda.synchronize()
+        first_timed = step + 1
+
+        # ---- timed region: exactly K steps
+        marks = []
+        t_start = time.perf_counter()
+        for _ in range(args.steps):
+            step += 1
+            n_before = len(requested)
+            iteration(step, True, marks)
+            if len(requested) > n_before:
+                live_files.append(requested[-1])
+            reap()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    # ---- drain (the paper counts pending flushes in end-to-end time; reported, not part of the K steps)
+    t0 = time.perf_counter()
+    ck.flush()
+    drain_s = time.perf_counter() - t0
+    reap(block=True)
+
+    # snapshots whose copies ran inside the timed region: requested at the end of steps first_timed-1 .. last-1
+    in_region = [it for it in requested if first_timed - 1 <= it < step]
+    stats = [ck.stats(it) for it in in_region]
+    all_stats = [ck.stats(it) for it in requested]
+    iter_ms = [m[0].elapsed_time(m[2]) for m in marks]
+    gemm_ms = [m[0].elapsed_time(m[1]) for m in marks]
+    stall_total_ms = sum(iter_ms) - base_iter_ms * len(iter_ms)
+    S = lay["data_bytes"]
+
+    def gbps(nbytes, ms):
+        return nbytes / (ms * 1e-3) / 1e9 if ms and ms > 0 else None
+
+    snap_gbps = gbps(S * len(stats), sum(s["request_to_d2h_end_ms"] for s in stats)) if stats else None
+    link_gbps = gbps(S * len(stats), sum(s["d2h_span_ms"] for s in stats)) if stats else None
+    pack_launches = sum(s["pack_launches"] for s in stats)
+    pack_ms = sum(s["pack_ms_sum"] for s in stats)
+    # algorithmic bytes of the pack kernel: every payload byte read once, every data-region byte written once
+    pack_bytes_per_snapshot = lay["payload_bytes"] + lay["data_bytes"]
+    pack_gbps = gbps(pack_bytes_per_snapshot * len(stats), pack_ms) if stats else None
+    # D2H busy steps: the GEMM phases that overlapped copies
+    busy = [g for i, g in enumerate(gemm_ms) if any(0 < (first_timed + i) - it <= 2 for it in requested)]
+    floor_ms = max(0.0, S / (link["d2h"] * 1e9) * 1e3 - base_gemm_ms)
+
+    result = {
+        "metric": "snapshot GB/s per GPU (fraction of host-link peak) + training stall ms/iter",
+        "value": round(snap_gbps, 3) if snap_gbps else None,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": spec.name, "payload_bytes": lay["payload_bytes"], "n_tensors": lay["n_tensors"],
+                   "ckpt_every": every, "compute_ms": compute_ms, "window_policy": args.policy,
+                   "ring_gib": args.ring_gib, "dma_chunk_mib": args.chunk_mib, "pack_superchunk_mib": args.superchunk_mib,
+                   "staging_gib": args.staging_gib or 2 * args.superchunk_mib / 1024, "dma_streams": args.dma_streams,
+                   "io_threads": args.io_threads, "hw_queues": int(os.environ["GPU_MAX_HW_QUEUES"]), "io_mode": args.io_mode, "keep_last": args.keep_last, "prealloc_files": args.prealloc, "sink": out_dir.rsplit("/", 1)[0]},
+        "roofline": {"bound": "hbm", "kernel": "pack_kernel", "achieved": round(pack_gbps, 1) if pack_gbps else None,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(pack_gbps / HBM_PEAK_GBPS, 4) if pack_gbps else None,
+                     "traffic": None, "launches": pack_launches,
+                     "avg_launch_ms": round(pack_ms / pack_launches, 4) if pack_launches else None,
+                     "bytes_per_launch": round(pack_bytes_per_snapshot / (pack_launches / max(1, len(stats)))) if pack_launches else None,
+                     "devcopy_ceiling_gbps": round(devcopy_gbps, 1)},
+        "snapshot": {"snapshots_in_timed_region": len(stats), "link_peak_d2h_gbps": round(link["d2h"], 2),
+                     "link_peak_h2d_gbps": round(link["h2d"], 2),
+                     "d2h_gbps": round(link_gbps, 2) if link_gbps else None,
+                     "d2h_frac_of_link_peak": round(link_gbps / link["d2h"], 4) if link_gbps else None,
+                     "snapshot_gbps_frac_of_link_peak": round(snap_gbps / link["d2h"], 4) if snap_gbps else None,
+                     "host_snapshot_call_ms": round(max(s["host_snapshot_call_ms"] for s in all_stats), 3) if all_stats else None,
+                     "host_backpressure_ms": round(max(s["host_backpressure_ms"] for s in all_stats), 1) if all_stats else None,
+                     "flush_gbps": round(statistics.median(S / (s["host_flush_span_ms"] * 1e-3) / 1e9 for s in all_stats), 2) if all_stats else None,
+                     "drain_s": round(drain_s, 2), "init_s": round(init_s, 2)},
+        "stall": {"baseline_ms_per_step": round(base_iter_ms, 3), "ms_per_step": round(statistics.mean(iter_ms), 3),
+                  "stall_ms_per_step": round(stall_total_ms / len(iter_ms), 3),
+                  "stall_pct": round(100.0 * stall_total_ms / (base_iter_ms * len(iter_ms)), 3),
+                  "stall_ms_per_snapshot": round(stall_total_ms / max(1, len(stats)), 2),
+                  "floor_ms_per_snapshot": round(floor_ms, 2),
+                  "gemm_ms_baseline": round(base_gemm_ms, 3),
+                  "gemm_ms_while_copying": round(statistics.median(busy), 3) if busy else None,
+                  "gemm_slowdown_pct": round(100.0 * (statistics.median(busy) / base_gemm_ms - 1), 3) if busy else None,
+                  "gemm_tflops": round(gemm.flops_per_launch / (gemm_ms_per_launch * 1e-3) / 1e12, 1)},
+    }
+
+    if not args.no_restore and requested:
+        last = requested[-1]
+        shard_probe = [0, len(shard.bufs) // 2, len(shard.bufs) - 1]
+        want = {k: shard.readback(k) for k in shard_probe}
+        for k in shard_probe:
+            shard.bufs[k].fill_(0xA5)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ck.restore(ck.file_name(last), stream.cuda_stream)
+        stream.synchronize()
+        dt = time.perf_counter() - t0
+        # the newest file is the state after the last step only if that step took a snapshot
+        ok = all((shard.readback(k) == want[k]).all() for k in shard_probe) if last == step else None
+        result["restore"] = {"gbps": round(S / dt / 1e9, 2), "seconds": round(dt, 2), "probe_tensors_bit_exact": ok if ok is None else bool(ok)}
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(torch, shard, int(args.oracle_sample_gb * 1e9), out_dir)
+    ck.destroy()
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -61,22 +61,35 @@ typedef struct {
  * or its tail) */
 typedef enum { CKPT_WINDOW_D2H = 0, CKPT_WINDOW_PACK = 1 } ckpt_window_policy;
 
+/* how the I/O threads put a ring slot into the file: pwrite (serialised per file by the kernel for
+ * buffered writes, but the only way with O_DIRECT), or stores into a shared mapping of the file
+ * (parallel across threads; the choice for tmpfs and page-cache sinks). AUTO = mmap unless o_direct. */
+typedef enum { CKPT_IO_AUTO = 0, CKPT_IO_PWRITE = 1, CKPT_IO_MMAP = 2 } ckpt_io_mode;
+
 /* Zero in a size/count field selects the default given in the comment. */
 typedef struct {
     int32_t device;                 /* HIP device ordinal */
     const char *out_dir;            /* directory of the checkpoint files; must exist */
     uint64_t host_ring_bytes;       /* pinned host ring; the paper's one knob. default 8 GiB; rounded down to
                                        whole DMA chunks, at least 2 chunks */
-    uint64_t dma_chunk_bytes;       /* one device-to-host copy and one ring slot. default 64 MiB; multiple of 64 KiB */
+    uint64_t dma_chunk_bytes;       /* one device-to-host copy and one ring slot. default 64 MiB; multiple of 32 KiB */
     uint64_t pack_superchunk_bytes; /* bytes one pack launch produces. default 1 GiB; multiple of dma_chunk_bytes */
     uint64_t dev_staging_bytes;     /* device staging; default 2 super-chunks; rounded down to whole super-chunks, at least 2
                                        (or the whole data region when that is smaller) */
     int32_t n_dma_streams;          /* default 2, at most 8 */
     int32_t n_io_threads;           /* host threads that write (and, on restore, read) ring slots. default 4, at most 64 */
     int32_t window_policy;          /* ckpt_window_policy */
-    int32_t o_direct;               /* 1: open files with O_DIRECT (all offsets and sizes are 4 KiB multiples) */
-    int32_t fsync_on_commit;        /* 1: fsync before the rename that commits a file */
-    int32_t reserved[7];            /* must be zero */
+    int32_t o_direct;               /* 1: open files with O_DIRECT (all offsets and sizes are 4 KiB multiples); data then
+                                       passes through a 4 MiB bounce buffer per I/O thread, because the kernel does not
+                                       accept the pinned ring's pages for direct I/O */
+    int32_t fsync_on_commit;        /* 1: fsync (and msync) before the rename that commits a file */
+    int32_t io_mode;                /* ckpt_io_mode */
+    int32_t keep_last;              /* 0: every checkpoint file stays. K > 0: once a snapshot is committed only the K
+                                       newest files keep their names; older ones are retired to hidden spare files whose
+                                       pages the next snapshots overwrite in place (no page allocation on the write path,
+                                       as with the host cache). K valid files plus one being written exist at a time. */
+    int32_t prealloc_files;         /* spare files created, with all pages allocated, at registration (needs keep_last > 0) */
+    int32_t reserved[4];            /* must be zero */
 } ckpt_config;
 
 /* Sizes that follow from a tensor list and a configuration. */
@@ -117,6 +130,7 @@ typedef struct {
     double host_request_to_commit_ms; /* host: request -> file renamed */
     double host_backpressure_ms;      /* host: time the submit thread spent waiting for a free ring slot */
     double host_snapshot_call_ms;     /* host: time the caller spent inside ckpt_snapshot_async */
+    double host_flush_span_ms;        /* host: first chunk on the host -> file renamed (the flush proper) */
 } ckpt_stats;
 
 #define CKPT_ITER_ALL UINT64_MAX

@@ -53,6 +53,15 @@ int proxy_mutate_words(void *dev_words, uint64_t n_words, uint64_t step, void *s
  * copy whose bandwidth is the practical ceiling for the pack kernel. */
 int proxy_devcopy(void *dev_dst, const void *dev_src, uint64_t nbytes, void *stream);
 
+/* A plain non-blocking HIP stream of default priority (hipStreamCreateWithFlags), returned as void*.
+ * The harness takes its compute stream from here instead of a framework's stream pool: every HIP
+ * stream is mapped onto one of a few hardware queues, and work of two streams that share a queue
+ * runs in submission order, so the compute stream must not share a hardware queue with the
+ * library's pack and copy streams. Creating the few streams that are really used, one after the
+ * other, gives each a queue of its own. */
+int proxy_stream_create(void **stream_out);
+int proxy_stream_destroy(void *stream);
+
 #ifdef __cplusplus
 }
 #endif

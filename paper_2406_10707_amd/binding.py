@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libdsllm_ckpt.so")
 CKPT_OK, CKPT_EINVAL, CKPT_ENOMEM, CKPT_EIO, CKPT_EHIP, CKPT_ESTATE, CKPT_EFORMAT, CKPT_EMISMATCH = 0, -1, -2, -3, -4, -5, -6, -7
 CKPT_BF16, CKPT_F32, CKPT_F16, CKPT_U8, CKPT_I32, CKPT_I64 = 1, 2, 3, 4, 5, 6
 CKPT_WINDOW_D2H, CKPT_WINDOW_PACK = 0, 1
+CKPT_IO_AUTO, CKPT_IO_PWRITE, CKPT_IO_MMAP = 0, 1, 2
 CKPT_ITER_ALL = 0xFFFFFFFFFFFFFFFF
 _STATUS_NAMES = {0: "CKPT_OK", -1: "CKPT_EINVAL", -2: "CKPT_ENOMEM", -3: "CKPT_EIO", -4: "CKPT_EHIP", -5: "CKPT_ESTATE",
                  -6: "CKPT_EFORMAT", -7: "CKPT_EMISMATCH"}
@@ -32,7 +33,8 @@ class ckpt_config(C.Structure):
     _fields_ = [("device", C.c_int32), ("out_dir", C.c_char_p), ("host_ring_bytes", C.c_uint64),
                 ("dma_chunk_bytes", C.c_uint64), ("pack_superchunk_bytes", C.c_uint64), ("dev_staging_bytes", C.c_uint64),
                 ("n_dma_streams", C.c_int32), ("n_io_threads", C.c_int32), ("window_policy", C.c_int32),
-                ("o_direct", C.c_int32), ("fsync_on_commit", C.c_int32), ("reserved", C.c_int32 * 7)]
+                ("o_direct", C.c_int32), ("fsync_on_commit", C.c_int32), ("io_mode", C.c_int32), ("keep_last", C.c_int32),
+                ("prealloc_files", C.c_int32), ("reserved", C.c_int32 * 4)]
 
 
 class ckpt_layout(C.Structure):
@@ -50,7 +52,8 @@ class ckpt_stats(C.Structure):
                 ("d2h_done", C.c_int32), ("committed", C.c_int32), ("pack_launches", C.c_int32), ("reserved0", C.c_int32),
                 ("pack_ms_sum", C.c_double), ("request_to_d2h_end_ms", C.c_double), ("d2h_span_ms", C.c_double),
                 ("request_to_pack_end_ms", C.c_double), ("host_submit_ms", C.c_double), ("host_request_to_commit_ms", C.c_double),
-                ("host_backpressure_ms", C.c_double), ("host_snapshot_call_ms", C.c_double)]
+                ("host_backpressure_ms", C.c_double), ("host_snapshot_call_ms", C.c_double),
+                ("host_flush_span_ms", C.c_double)]
 
 
 class CkptError(RuntimeError):
@@ -92,6 +95,8 @@ _SIGS = {
     "proxy_fill_words": (C.c_int, [_vp, _u64, _u64, _vp]),
     "proxy_mutate_words": (C.c_int, [_vp, _u64, _u64, _vp]),
     "proxy_devcopy": (C.c_int, [_vp, _vp, _u64, _vp]),
+    "proxy_stream_create": (C.c_int, [C.POINTER(_vp)]),
+    "proxy_stream_destroy": (C.c_int, [_vp]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(lib, _name)      # raises if the library does not export the symbol
@@ -111,7 +116,8 @@ def _struct_dict(s):
 
 
 def make_config(out_dir="", device=0, host_ring_bytes=0, dma_chunk_bytes=0, pack_superchunk_bytes=0, dev_staging_bytes=0,
-                n_dma_streams=0, n_io_threads=0, window_policy=CKPT_WINDOW_D2H, o_direct=0, fsync_on_commit=0):
+                n_dma_streams=0, n_io_threads=0, window_policy=CKPT_WINDOW_D2H, o_direct=0, fsync_on_commit=0,
+                io_mode=CKPT_IO_AUTO, keep_last=0, prealloc_files=0):
     cfg = ckpt_config()
     cfg.device = device
     cfg.out_dir = os.fsencode(out_dir) if out_dir else None
@@ -124,6 +130,9 @@ def make_config(out_dir="", device=0, host_ring_bytes=0, dma_chunk_bytes=0, pack
     cfg.window_policy = window_policy
     cfg.o_direct = o_direct
     cfg.fsync_on_commit = fsync_on_commit
+    cfg.io_mode = io_mode
+    cfg.keep_last = keep_last
+    cfg.prealloc_files = prealloc_files
     return cfg
 
 
@@ -269,3 +278,13 @@ def proxy_mutate_words(w, n_words, step, stream):
 
 def proxy_devcopy(dst, src, nbytes, stream):
     _proxy(lib.proxy_devcopy(dst, src, nbytes, stream), "proxy_devcopy")
+
+
+def proxy_stream_create():
+    out = _vp()
+    _proxy(lib.proxy_stream_create(C.byref(out)), "proxy_stream_create")
+    return out.value
+
+
+def proxy_stream_destroy(stream):
+    _proxy(lib.proxy_stream_destroy(stream), "proxy_stream_destroy")

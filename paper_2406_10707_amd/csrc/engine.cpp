@@ -23,7 +23,9 @@
 
 #include <errno.h>
 #include <fcntl.h>
+#include <sys/mman.h>
 #include <sys/stat.h>
+#include <sys/statvfs.h>
 #include <unistd.h>
 
 #include "plan.hpp"
@@ -44,14 +46,31 @@ struct ckpt_plan { Plan plan; };
 
 namespace {
 
+// An open checkpoint file. With retention (keep_last > 0) files, descriptors and mappings live on
+// after the commit: a retired file is renamed to a hidden spare name and a later snapshot writes
+// into the same pages through the same mapping, so the steady-state flush is plain memcpy.
+struct FileSlot {
+    std::string path;
+    int fd = -1;
+    uint8_t *map = nullptr;           // whole-file shared mapping when the sink is written through mmap
+    uint64_t map_bytes = 0;
+    void close_all() {
+        if (map) munmap(map, map_bytes);
+        if (fd >= 0) ::close(fd);
+        map = nullptr; fd = -1;
+    }
+};
+
 struct Snap {
     uint64_t iter = 0;
     int fd = -1;
+    uint8_t *map = nullptr;
     std::string tmp_path, final_path;
     std::atomic<uint64_t> chunks_left{0};
     hipEvent_t ev_boundary = nullptr;
     bool submitted = false, d2h_done = false, committed = false, window_closed = false;
-    Clock::time_point t_request, t_submitted, t_committed;
+    Clock::time_point t_request, t_submitted, t_committed, t_first_chunk;
+    bool have_first_chunk = false;
     double call_ms = 0, backpressure_ms = 0;
     double pack_ms_sum = -1, req_to_d2h_end_ms = -1, d2h_span_ms = -1, req_to_pack_end_ms = -1;
 };
@@ -107,6 +126,11 @@ struct ckpt_ctx {
     int async_code = 0;
     std::string async_err;
     bool restoring = false;
+    // retention: committed iterations in commit order, and retired files whose pages are reused
+    std::deque<uint64_t> committed_iters;
+    std::vector<FileSlot> spares;
+    std::map<uint64_t, FileSlot> kept;     // committed files that still carry their names
+    uint64_t spare_seq = 0;
 
     void latch(int code, const std::string &msg) {
         std::lock_guard<std::mutex> lk(mu);
@@ -172,8 +196,36 @@ static void finish_d2h_stats(ckpt_ctx *c, Snap *s) {
     c->cv_state.notify_all();
 }
 
+// O_DIRECT cannot take its data from the pinned ring (the kernel refuses device-mapped pages as a
+// direct-I/O source or target: EFAULT), so direct I/O goes through a small aligned bounce buffer
+// owned by the I/O thread.
+constexpr uint64_t kBounceBytes = 4ull << 20;
+
+static bool direct_write(int fd, uint8_t *bounce, const uint8_t *src, uint64_t n, uint64_t off, std::string *err) {
+    while (n) {
+        uint64_t m = n < kBounceBytes ? n : kBounceBytes;
+        memcpy(bounce, src, m);
+        if (!pwrite_all(fd, bounce, m, off, err)) return false;
+        src += m; off += m; n -= m;
+    }
+    return true;
+}
+
+static bool direct_read(int fd, uint8_t *bounce, uint8_t *dst, uint64_t n, uint64_t off, std::string *err) {
+    while (n) {
+        uint64_t m = n < kBounceBytes ? n : kBounceBytes;
+        if (!pread_all(fd, bounce, m, off, err)) return false;
+        memcpy(dst, bounce, m);
+        dst += m; off += m; n -= m;
+    }
+    return true;
+}
+
 static void io_thread_main(ckpt_ctx *c) {
     (void)hipSetDevice(c->device);
+    uint8_t *bounce = nullptr;
+    if (c->cfg.o_direct && posix_memalign(reinterpret_cast<void **>(&bounce), 4096, kBounceBytes) != 0) bounce = nullptr;
+    struct BounceFree { uint8_t *&p; ~BounceFree() { free(p); } } bounce_free{bounce};
     for (;;) {
         IoJob job;
         {
@@ -186,7 +238,8 @@ static void io_thread_main(ckpt_ctx *c) {
         uint8_t *slot_ptr = c->ring + job.slot * c->cfg.dma_chunk_bytes;
         std::string err;
         if (job.kind == IoJob::READ) {
-            bool ok = pread_all(job.fd, slot_ptr, job.nbytes, job.file_off, &err);
+            bool ok = c->cfg.o_direct ? (bounce ? direct_read(job.fd, bounce, slot_ptr, job.nbytes, job.file_off, &err) : (err = "no bounce buffer", false))
+                                      : pread_all(job.fd, slot_ptr, job.nbytes, job.file_off, &err);
             if (!ok) c->latch(CKPT_EIO, err);
             std::lock_guard<std::mutex> lk(c->mu);
             c->slot_state[job.slot] = SLOT_READ_DONE;
@@ -197,6 +250,11 @@ static void io_thread_main(ckpt_ctx *c) {
         Snap *s = job.snap.get();
         hipError_t he = hipEventSynchronize(c->ev_slot[job.slot]);
         if (he != hipSuccess) c->latch(CKPT_EHIP, std::string("copy event: ") + hipGetErrorString(he));
+        if (job.file_off == c->plan.header_bytes) {
+            std::lock_guard<std::mutex> lk(c->mu);
+            s->t_first_chunk = Clock::now();
+            s->have_first_chunk = true;
+        }
         if (job.last) {
             for (size_t k = 0; k < c->dma.size(); k++) {
                 he = hipEventSynchronize(c->ev_job_tail[k]);
@@ -204,7 +262,12 @@ static void io_thread_main(ckpt_ctx *c) {
             }
             finish_d2h_stats(c, s);
         }
-        if (s->fd >= 0 && !pwrite_all(s->fd, slot_ptr, job.nbytes, job.file_off, &err)) c->latch(CKPT_EIO, s->tmp_path + ": " + err);
+        if (s->map) memcpy(s->map + job.file_off, slot_ptr, job.nbytes);   // page-cache/tmpfs sink: parallel across threads
+        else if (s->fd >= 0) {
+            bool ok = c->cfg.o_direct ? (bounce ? direct_write(s->fd, bounce, slot_ptr, job.nbytes, job.file_off, &err) : (err = "no bounce buffer", false))
+                                      : pwrite_all(s->fd, slot_ptr, job.nbytes, job.file_off, &err);
+            if (!ok) c->latch(CKPT_EIO, s->tmp_path + ": " + err);
+        }
         {
             std::lock_guard<std::mutex> lk(c->mu);
             c->slot_state[job.slot] = SLOT_FREE;
@@ -213,14 +276,42 @@ static void io_thread_main(ckpt_ctx *c) {
         if (s->chunks_left.fetch_sub(1) == 1) {
             // last chunk written: commit
             if (s->fd >= 0) {
+                const bool retain = c->cfg.keep_last > 0;
+                if (s->map && c->cfg.fsync_on_commit && msync(s->map, c->plan.file_bytes(), MS_SYNC) != 0)
+                    c->latch(CKPT_EIO, s->tmp_path + ": msync: " + strerror(errno));
                 if (c->cfg.fsync_on_commit && fsync(s->fd) != 0) c->latch(CKPT_EIO, s->tmp_path + ": fsync: " + strerror(errno));
-                if (close(s->fd) != 0) c->latch(CKPT_EIO, s->tmp_path + ": close: " + strerror(errno));
-                s->fd = -1;
+                FileSlot fs;
+                fs.path = s->final_path; fs.fd = s->fd; fs.map = s->map; fs.map_bytes = c->plan.file_bytes();
+                s->fd = -1; s->map = nullptr;
                 bool had_error;
                 { std::lock_guard<std::mutex> lk(c->mu); had_error = c->async_code != 0; }
                 // a file gets its final name only when whole
-                if (!had_error && rename(s->tmp_path.c_str(), s->final_path.c_str()) != 0)
+                if (!had_error && rename(s->tmp_path.c_str(), s->final_path.c_str()) != 0) {
                     c->latch(CKPT_EIO, s->final_path + ": rename: " + strerror(errno));
+                    had_error = true;
+                }
+                if (retain && !had_error) {
+                    // files older than the newest keep_last become spares, overwritten in place later
+                    std::lock_guard<std::mutex> lk(c->mu);
+                    auto dup = c->kept.find(s->iter);
+                    if (dup != c->kept.end()) { dup->second.close_all(); c->kept.erase(dup); }
+                    c->kept[s->iter] = fs;
+                    c->committed_iters.push_back(s->iter);
+                    while (c->committed_iters.size() > size_t(c->cfg.keep_last)) {
+                        const uint64_t old = c->committed_iters.front();
+                        c->committed_iters.pop_front();
+                        auto it = c->kept.find(old);
+                        if (old == s->iter || it == c->kept.end()) continue;
+                        FileSlot sp = it->second;
+                        c->kept.erase(it);
+                        std::string spare = c->out_dir + "/.spare_" + std::to_string(getpid()) + "_" + std::to_string(c->spare_seq++) + ".dsl";
+                        if (rename(sp.path.c_str(), spare.c_str()) == 0) { sp.path = spare; c->spares.push_back(sp); }
+                        else sp.close_all();   // somebody removed or replaced the file: drop it
+                    }
+                } else {
+                    fs.close_all();
+                    if (had_error) unlink(s->tmp_path.c_str());
+                }
             }
             std::lock_guard<std::mutex> lk(c->mu);
             s->t_committed = Clock::now();
@@ -249,14 +340,46 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
     }
 
     // file and header
-    int flags = O_WRONLY | O_CREAT | O_TRUNC | (c->cfg.o_direct ? O_DIRECT : 0);
-    s->fd = open(s->tmp_path.c_str(), flags, 0644);
-    if (s->fd < 0) c->latch(CKPT_EIO, s->tmp_path + ": open: " + strerror(errno));
-    else {
-        memcpy(c->hdr_buf, p.header.data(), p.header_bytes);
-        for (int i = 0; i < 8; i++) c->hdr_buf[16 + i] = uint8_t(s->iter >> (8 * i));
-        std::string err;
-        if (!pwrite_all(s->fd, c->hdr_buf, p.header_bytes, 0, &err)) c->latch(CKPT_EIO, s->tmp_path + ": " + err);
+    const bool use_mmap = c->cfg.io_mode == CKPT_IO_MMAP;
+    memcpy(c->hdr_buf, p.header.data(), p.header_bytes);
+    for (int i = 0; i < 8; i++) c->hdr_buf[16 + i] = uint8_t(s->iter >> (8 * i));
+    FileSlot reuse;
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        if (!c->spares.empty()) { reuse = c->spares.back(); c->spares.pop_back(); }
+    }
+    std::string ferr;
+    if (reuse.fd >= 0) {
+        // a retired file of this registration: same size, pages allocated, still open (and mapped);
+        // every byte of it is rewritten (header, data and padding), so nothing is truncated
+        s->tmp_path = reuse.path;
+        s->fd = reuse.fd;
+        s->map = reuse.map;
+    } else {
+        int flags = (use_mmap ? O_RDWR : O_WRONLY) | O_CREAT | O_TRUNC | (c->cfg.o_direct ? O_DIRECT : 0);
+        s->fd = open(s->tmp_path.c_str(), flags, 0644);
+        if (s->fd < 0) ferr = std::string("open: ") + strerror(errno);
+        else if (use_mmap) {
+            // stores into a mapping cannot report "no space left" as an error code: check the room first
+            struct statvfs vfs;
+            if (fstatvfs(s->fd, &vfs) == 0 && uint64_t(vfs.f_bavail) * vfs.f_frsize < p.file_bytes()) ferr = "not enough free space for the checkpoint file";
+            else if (ftruncate(s->fd, off_t(p.file_bytes())) != 0) ferr = std::string("ftruncate: ") + strerror(errno);
+            else {
+                void *m = mmap(nullptr, p.file_bytes(), PROT_READ | PROT_WRITE, MAP_SHARED, s->fd, 0);
+                if (m == MAP_FAILED) ferr = std::string("mmap: ") + strerror(errno);
+                else s->map = static_cast<uint8_t *>(m);
+            }
+        }
+    }
+    if (ferr.empty() && s->fd >= 0) {
+        if (s->map) memcpy(s->map, c->hdr_buf, p.header_bytes);
+        else if (!pwrite_all(s->fd, c->hdr_buf, p.header_bytes, 0, &ferr)) {}
+    }
+    if (!ferr.empty()) {
+        c->latch(CKPT_EIO, s->tmp_path + ": " + ferr);
+        if (s->map) munmap(s->map, p.file_bytes());
+        if (s->fd >= 0) close(s->fd);
+        s->map = nullptr; s->fd = -1;
     }
 
     if ((e = hipStreamWaitEvent(c->pack_stream, s->ev_boundary, 0)) != hipSuccess) hip_fail("wait boundary", e);
@@ -470,6 +593,8 @@ int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out) {
     return CKPT_OK;
 }
 
+static bool preallocate_file(const std::string &path, uint64_t bytes, int n_threads, bool map_it, bool o_direct, FileSlot *out, std::string *err);
+
 int ckpt_register_tensors(ckpt_ctx *c, const ckpt_tensor_desc *tensors, size_t n) {
     if (!c) return fail(CKPT_EINVAL, "null context");
     if (c->registered) return fail(CKPT_ESTATE, "tensors already registered in this context");
@@ -522,7 +647,49 @@ int ckpt_register_tensors(ckpt_ctx *c, const ckpt_tensor_desc *tensors, size_t n
     if (posix_memalign(reinterpret_cast<void **>(&c->hdr_buf), 4096, p.header_bytes) != 0) return fail(CKPT_ENOMEM, "header buffer");
     c->plan = std::move(p);
     c->registered = true;
+    for (int i = 0; i < c->cfg.prealloc_files; i++) {
+        std::string spare = c->out_dir + "/.spare_" + std::to_string(getpid()) + "_" + std::to_string(c->spare_seq++) + ".dsl";
+        FileSlot fs;
+        if (!preallocate_file(spare, c->plan.file_bytes(), std::min(c->cfg.n_io_threads, 8), c->cfg.io_mode == CKPT_IO_MMAP, c->cfg.o_direct, &fs, &err))
+            return fail(CKPT_EIO, err);
+        c->spares.push_back(fs);
+    }
     return CKPT_OK;
+}
+
+// Creates a file of `bytes` bytes with all its pages allocated (zero-filled), several threads writing.
+static bool preallocate_file(const std::string &path, uint64_t bytes, int n_threads, bool map_it, bool o_direct, FileSlot *out, std::string *err) {
+    int fd = open(path.c_str(), O_RDWR | O_CREAT | O_TRUNC, 0644);
+    if (fd < 0) { *err = path + ": open: " + strerror(errno); return false; }
+    const uint64_t piece = 16ull << 20;
+    std::vector<uint8_t> zeros(piece, 0);
+    std::atomic<uint64_t> next{0};
+    std::atomic<bool> ok{true};
+    std::mutex emu;
+    std::vector<std::thread> th;
+    for (int t = 0; t < n_threads; t++)
+        th.emplace_back([&] {
+            for (;;) {
+                uint64_t off = next.fetch_add(piece);
+                if (off >= bytes || !ok) return;
+                std::string e;
+                if (!pwrite_all(fd, zeros.data(), std::min(piece, bytes - off), off, &e)) { std::lock_guard<std::mutex> lk(emu); *err = path + ": " + e; ok = false; }
+            }
+        });
+    for (auto &t : th) t.join();
+    close(fd);
+    if (!ok) { unlink(path.c_str()); return false; }
+    // reopen the way the flush will use it; with a mapping, fault every page in now
+    out->path = path;
+    out->fd = open(path.c_str(), (map_it ? O_RDWR : O_WRONLY) | (o_direct ? O_DIRECT : 0));
+    if (out->fd < 0) { *err = path + ": open: " + strerror(errno); unlink(path.c_str()); return false; }
+    if (map_it) {
+        void *m = mmap(nullptr, bytes, PROT_READ | PROT_WRITE, MAP_SHARED | MAP_POPULATE, out->fd, 0);
+        if (m == MAP_FAILED) { *err = path + ": mmap: " + strerror(errno); close(out->fd); unlink(path.c_str()); return false; }
+        out->map = static_cast<uint8_t *>(m);
+        out->map_bytes = bytes;
+    }
+    return true;
 }
 
 static int take_async_error(ckpt_ctx *c) {
@@ -650,6 +817,7 @@ int ckpt_get_stats(ckpt_ctx *c, uint64_t iter, ckpt_stats *o) {
     o->host_request_to_commit_ms = s.committed ? ms_between(s.t_request, s.t_committed) : -1;
     o->host_backpressure_ms = s.submitted ? s.backpressure_ms : -1;
     o->host_snapshot_call_ms = s.call_ms;
+    o->host_flush_span_ms = (s.committed && s.have_first_chunk) ? ms_between(s.t_first_chunk, s.t_committed) : -1;
     return CKPT_OK;
 }
 
@@ -816,6 +984,8 @@ int ckpt_destroy(ckpt_ctx *c) {
     if (c->staging) (void)hipFree(c->staging);
     if (c->dev_tiles) (void)hipFree(c->dev_tiles);
     if (c->ring) (void)hipHostFree(c->ring);
+    for (auto &sp : c->spares) { sp.close_all(); unlink(sp.path.c_str()); }
+    for (auto &kv : c->kept) kv.second.close_all();
     free(c->hdr_buf);
     delete c;
     return rc;

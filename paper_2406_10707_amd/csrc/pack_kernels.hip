@@ -1,8 +1,10 @@
 // Pack and scatter kernels for gfx950: pure byte movement between scattered tensors and the
 // contiguous, 4 KiB-aligned staging image of the checkpoint's data region. HBM-bound.
 //
-// One wavefront (64 lanes) walks one tile of the descriptor table: up to 64 KiB of destination,
-// 16 bytes per lane per step, 1 KiB per wavefront step, several steps in flight. The staging side is
+// One wavefront (64 lanes) walks one tile of the descriptor table: up to 32 KiB of destination,
+// 16 bytes per lane per step, 1 KiB per wavefront step, 16 steps (aligned source) or 8 (misaligned
+// source, which needs two registers sets) in flight; a sweep of tile sizes, unroll depths and block
+// sizes on MI355X put this shape at the top for a plain copy. The staging side is
 // always 16-byte aligned. The tensor side is aligned to its element size only; when it is not
 // 16-byte aligned each lane reads the two aligned 16-byte words that cover its bytes and
 // byte-shifts them together (v_alignbyte), so every global access is an aligned 128-bit one. An
@@ -19,7 +21,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWavesPerBlock = 4;
 constexpr int kBlock = 64 * kWavesPerBlock;
-constexpr int kUnroll = 8;
+constexpr int kUnroll = 16;        // aligned path: 16 x 16 bytes per lane in flight
+constexpr int kUnrollShift = 8;    // misaligned path: 8 pairs of 16-byte words per lane in flight
 
 __device__ __forceinline__ u32x4 ld16(const u32x4 *p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ void st16(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
@@ -63,12 +66,12 @@ __device__ __forceinline__ u32x4 keep_bytes(u32x4 v, uint32_t keep) {
 template <int W>
 __device__ __forceinline__ void pack_shifted(const u32x4 *src_al, u32x4 *dst, uint32_t n_full, uint32_t b, uint32_t lane) {
     uint32_t i = lane;
-    for (; i + 64 * (kUnroll - 1) < n_full; i += 64 * kUnroll) {
-        u32x4 lo[kUnroll], hi[kUnroll];
+    for (; i + 64 * (kUnrollShift - 1) < n_full; i += 64 * kUnrollShift) {
+        u32x4 lo[kUnrollShift], hi[kUnrollShift];
 #pragma unroll
-        for (int u = 0; u < kUnroll; u++) { lo[u] = ld16(src_al + i + 64 * u); hi[u] = ld16(src_al + i + 64 * u + 1); }
+        for (int u = 0; u < kUnrollShift; u++) { lo[u] = ld16(src_al + i + 64 * u); hi[u] = ld16(src_al + i + 64 * u + 1); }
 #pragma unroll
-        for (int u = 0; u < kUnroll; u++) st16(dst + i + 64 * u, funnel<W>(lo[u], hi[u], b));
+        for (int u = 0; u < kUnrollShift; u++) st16(dst + i + 64 * u, funnel<W>(lo[u], hi[u], b));
     }
     for (; i < n_full; i += 64) st16(dst + i, funnel<W>(ld16(src_al + i), ld16(src_al + i + 1), b));
 }
@@ -140,12 +143,12 @@ template <int W>
 __device__ __forceinline__ void scatter_shifted(const u32x4 *src, u32x4 *dst_al, uint32_t n_words, uint32_t b, uint32_t lane) {
     // dst_al[j] for j = 1..n_words gets bytes [(16-sh) + 16*(j-1), +16) of src = funnel of src[j-1], src[j] at shift 16-sh
     uint32_t i = lane;
-    for (; i + 64 * (kUnroll - 1) < n_words; i += 64 * kUnroll) {
-        u32x4 lo[kUnroll], hi[kUnroll];
+    for (; i + 64 * (kUnrollShift - 1) < n_words; i += 64 * kUnrollShift) {
+        u32x4 lo[kUnrollShift], hi[kUnrollShift];
 #pragma unroll
-        for (int u = 0; u < kUnroll; u++) { lo[u] = ld16(src + i + 64 * u); hi[u] = ld16(src + i + 64 * u + 1); }
+        for (int u = 0; u < kUnrollShift; u++) { lo[u] = ld16(src + i + 64 * u); hi[u] = ld16(src + i + 64 * u + 1); }
 #pragma unroll
-        for (int u = 0; u < kUnroll; u++) st16(dst_al + 1 + i + 64 * u, funnel<W>(lo[u], hi[u], b));
+        for (int u = 0; u < kUnrollShift; u++) st16(dst_al + 1 + i + 64 * u, funnel<W>(lo[u], hi[u], b));
     }
     for (; i < n_words; i += 64) st16(dst_al + 1 + i, funnel<W>(ld16(src + i), ld16(src + i + 1), b));
 }

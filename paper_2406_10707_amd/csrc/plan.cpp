@@ -27,8 +27,16 @@ int resolve_config(const ckpt_config *in, ResolvedConfig *out, std::string *err)
     c.window_policy = in->window_policy;
     c.o_direct = in->o_direct;
     c.fsync_on_commit = in->fsync_on_commit;
+    c.io_mode = in->io_mode;
+    c.keep_last = in->keep_last;
+    c.prealloc_files = in->prealloc_files;
+    if (c.keep_last < 0 || c.prealloc_files < 0 || c.prealloc_files > 16) { *err = "config: keep_last must be >= 0 and prealloc_files 0..16"; return CKPT_EINVAL; }
+    if (c.prealloc_files > 0 && c.keep_last == 0) { *err = "config: prealloc_files needs keep_last > 0"; return CKPT_EINVAL; }
+    if (c.io_mode == CKPT_IO_AUTO) c.io_mode = c.o_direct ? CKPT_IO_PWRITE : CKPT_IO_MMAP;
+    if (c.io_mode != CKPT_IO_PWRITE && c.io_mode != CKPT_IO_MMAP) { *err = "config: unknown io_mode"; return CKPT_EINVAL; }
+    if (c.io_mode == CKPT_IO_MMAP && c.o_direct) { *err = "config: o_direct needs io_mode pwrite"; return CKPT_EINVAL; }
     for (int r : in->reserved) if (r != 0) { *err = "config: reserved fields must be zero"; return CKPT_EINVAL; }
-    if (c.dma_chunk_bytes % kTileBytes != 0) { *err = "config: dma_chunk_bytes must be a multiple of 64 KiB"; return CKPT_EINVAL; }
+    if (c.dma_chunk_bytes % kTileBytes != 0) { *err = "config: dma_chunk_bytes must be a multiple of the 32 KiB tile size"; return CKPT_EINVAL; }
     if (c.pack_superchunk_bytes % c.dma_chunk_bytes != 0) { *err = "config: pack_superchunk_bytes must be a multiple of dma_chunk_bytes"; return CKPT_EINVAL; }
     if (c.pack_superchunk_bytes > (64ull << 30)) { *err = "config: pack_superchunk_bytes above 64 GiB"; return CKPT_EINVAL; }
     if (c.n_dma_streams < 1 || c.n_dma_streams > 8) { *err = "config: n_dma_streams must be 1..8"; return CKPT_EINVAL; }

@@ -11,7 +11,7 @@ namespace dsllm {
 
 constexpr uint64_t kAlign = 4096;        // alignment unit of the file format
 constexpr uint64_t kFixedHeader = 64;
-constexpr uint64_t kTileBytes = 64 * 1024;  // destination bytes one wavefront produces
+constexpr uint64_t kTileBytes = 32 * 1024;  // destination bytes one wavefront produces (measured best: 32 KiB, 16 loads in flight per lane)
 
 struct TensorInfo {
     std::string name;
@@ -24,7 +24,7 @@ struct TensorInfo {
 
 struct ResolvedConfig {
     uint64_t host_ring_bytes, dma_chunk_bytes, pack_superchunk_bytes, dev_staging_bytes;
-    int n_dma_streams, n_io_threads, window_policy, o_direct, fsync_on_commit;
+    int n_dma_streams, n_io_threads, window_policy, o_direct, fsync_on_commit, io_mode, keep_last, prealloc_files;
 };
 
 struct Plan {

@@ -1,6 +1,7 @@
 // Synthetic training proxy kernels for gfx950 (see include/ckpt_proxy.h): bf16 MFMA GEMM,
 // element-wise Adam step, seeded state fill, flat-buffer word fill/mutate, contiguous copy.
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 
 #include "../../include/ckpt_proxy.h"
@@ -103,19 +104,19 @@ __global__ __launch_bounds__(256) void mutate_words_kernel(uint32_t *__restrict_
 }
 
 __global__ __launch_bounds__(256) void devcopy_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src, uint64_t n16) {
-    // each wavefront streams 64 KiB pieces, 8 x 16 bytes per lane in flight, like the pack kernel's aligned path
+    // each wavefront streams 32 KiB pieces, 16 x 16 bytes per lane in flight, like the pack kernel's aligned path
     const uint32_t lane = threadIdx.x & 63;
     const uint64_t wave = uint64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
     const uint64_t n_waves = uint64_t(gridDim.x) * 4;
-    for (uint64_t base = wave * 4096; base < n16; base += n_waves * 4096) {
-        const uint64_t end = base + 4096 < n16 ? base + 4096 : n16;
+    for (uint64_t base = wave * 2048; base < n16; base += n_waves * 2048) {
+        const uint64_t end = base + 2048 < n16 ? base + 2048 : n16;
         uint64_t i = base + lane;
-        for (; i + 64 * 7 < end; i += 64 * 8) {
-            u32x4 t[8];
+        for (; i + 64 * 15 < end; i += 64 * 16) {
+            u32x4 t[16];
 #pragma unroll
-            for (int u = 0; u < 8; u++) t[u] = __builtin_nontemporal_load(src + i + 64 * u);
+            for (int u = 0; u < 16; u++) t[u] = __builtin_nontemporal_load(src + i + 64 * u);
 #pragma unroll
-            for (int u = 0; u < 8; u++) __builtin_nontemporal_store(t[u], dst + i + 64 * u);
+            for (int u = 0; u < 16; u++) __builtin_nontemporal_store(t[u], dst + i + 64 * u);
         }
         for (; i < end; i += 64) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
     }
@@ -249,10 +250,8 @@ int proxy_adam_step(void *p, void *master, void *m, void *v, uint64_t numel, uin
     if (((uint64_t(master) | uint64_t(m) | uint64_t(v)) & 15) || (uint64_t(p) & 7)) return -1;
     AdamArgs a;
     a.lr = lr; a.beta1 = beta1; a.beta2 = beta2; a.eps = eps;
-    double b1t = 1.0, b2t = 1.0;
-    for (uint64_t i = 0; i < step && (b1t > 1e-300 || b2t > 1e-300); i++) { b1t *= beta1; b2t *= beta2; }
-    a.inv_bc1 = float(1.0 / (1.0 - b1t));
-    a.inv_bc2 = float(1.0 / (1.0 - b2t));
+    a.inv_bc1 = float(1.0 / (1.0 - pow(double(beta1), double(step))));
+    a.inv_bc2 = float(1.0 / (1.0 - pow(double(beta2), double(step))));
     hipLaunchKernelGGL(adam_kernel, dim3(blocks_for((numel + 3) / 4, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<uint16_t *>(p), static_cast<float *>(master), static_cast<float *>(m), static_cast<float *>(v), numel,
                        stream_key(seed + step, tensor, 3), a);
@@ -276,12 +275,25 @@ int proxy_mutate_words(void *w, uint64_t n, uint64_t step, void *stream) {
 int proxy_devcopy(void *dst, const void *src, uint64_t nbytes, void *stream) {
     if (!dst || !src || nbytes == 0 || (nbytes & 15) || ((uint64_t(dst) | uint64_t(src)) & 15)) return -1;
     const uint64_t n16 = nbytes >> 4;
-    uint64_t pieces = (n16 + 4095) / 4096;
-    uint64_t blocks = (pieces + 3) / 4;
-    if (blocks > 256 * 64) blocks = 256 * 64;
+    uint64_t pieces = (n16 + 2047) / 2048;
+    uint64_t blocks = (pieces + 3) / 4;           // one piece per wavefront up to 4 GiB, grid-stride beyond
+    if (blocks > (1u << 15)) blocks = 1u << 15;
     hipLaunchKernelGGL(devcopy_kernel, dim3(unsigned(blocks)), dim3(256), 0, static_cast<hipStream_t>(stream), static_cast<u32x4 *>(dst),
                        static_cast<const u32x4 *>(src), n16);
     return hip_rc();
+}
+
+int proxy_stream_create(void **out) {
+    if (!out) return -1;
+    hipStream_t s = nullptr;
+    if (hipStreamCreateWithFlags(&s, hipStreamNonBlocking) != hipSuccess) return -4;
+    *out = s;
+    return 0;
+}
+
+int proxy_stream_destroy(void *stream) {
+    if (!stream) return -1;
+    return hipStreamDestroy(static_cast<hipStream_t>(stream)) == hipSuccess ? 0 : -4;
 }
 
 }  // extern "C"

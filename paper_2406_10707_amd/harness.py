@@ -9,6 +9,15 @@ from . import binding as B
 from . import shards
 
 
+def make_compute_stream(device="cuda:0"):
+    """A torch stream object around a stream created by the library (proxy_stream_create), so that it
+    does not come from PyTorch's pool of 32+ streams, which would spread over all hardware queues and
+    end up sharing one with the checkpoint library's own streams."""
+    torch.cuda.set_device(device)
+    torch.cuda.current_stream().synchronize()      # HIP is initialised and the null stream has its queue
+    return torch.cuda.ExternalStream(B.proxy_stream_create(), device=device)
+
+
 class DeviceShard:
     """The tensors of a ShardSpec in device memory.
 

@@ -48,7 +48,7 @@ int main(int argc, char **argv) {
         switch (rnd() % 6) {
             case 0: nb = 1 + rnd() % 40; break;                      // smaller than two words
             case 1: nb = 4096 - 16 + rnd() % 33; break;              // around one alignment unit
-            case 2: nb = 65536 - 32 + rnd() % 65; break;             // around one tile
+            case 2: nb = 32768 * (1 + rnd() % 2) - 32 + rnd() % 65; break;   // around one or two tiles
             case 3: nb = 65536 * (1 + rnd() % 3) + rnd() % 5000; break;
             case 4: nb = 16 * (1 + rnd() % 600); break;              // whole words
             default: nb = 1 + rnd() % 200000; break;

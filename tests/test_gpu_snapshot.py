@@ -64,6 +64,60 @@ def test_tiny_shard_file_equals_oracle(config, policy, tmp_path):
     ck.destroy()
 
 
+@pytest.mark.parametrize("mode", ["pwrite", "o_direct", "mmap+fsync"])
+def test_sink_modes_write_the_same_file(mode, tmp_path):
+    _say(f"sink mode {mode}")
+    spec = shards.make_shard(5, tiny=True)
+    shard = harness.DeviceShard(spec, DEV)
+    shard.upload_host_values()
+    stream = torch.cuda.Stream()
+    kw = dict(pwrite=dict(io_mode=B.CKPT_IO_PWRITE), o_direct=dict(o_direct=1, fsync_on_commit=1),
+              **{"mmap+fsync": dict(io_mode=B.CKPT_IO_MMAP, fsync_on_commit=1)})[mode]
+    ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), n_io_threads=3, n_dma_streams=1, **SMALL, **kw))
+    ck.register_tensors(shard.descs())
+    for it in (1, 2):
+        ck.snapshot_async(it, stream.cuda_stream)
+        ck.flush(it)
+    host = [shards.host_values(spec, k) for k in range(len(spec.tensors))]
+    for it in (1, 2):
+        assert open(ck.file_name(it), "rb").read() == oracle.serialize_bytes(shard.oracle_tensors(host), it)
+    shard.poison()
+    assert ck.restore(ck.file_name(2), stream.cuda_stream) == 2
+    stream.synchronize()
+    assert all(np.array_equal(g, h) for g, h in zip(shard.readback_all(), host))
+    ck.destroy()
+
+
+@pytest.mark.parametrize("io_mode", [B.CKPT_IO_MMAP, B.CKPT_IO_PWRITE])
+def test_retention_recycles_files_in_place(io_mode, tmp_path):
+    """keep_last=2 with one pre-allocated spare: only the two newest files keep their names, retired
+    files are overwritten in place, and every byte of a recycled file is rewritten (the spare starts
+    as zeros, later spares hold an older iteration's bytes)."""
+    _say(f"retention io_mode {io_mode}")
+    spec = shards.make_shard(5, tiny=True)
+    shard = harness.DeviceShard(spec, DEV)
+    shard.upload_host_values()
+    stream = torch.cuda.Stream()
+    ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), keep_last=2, prealloc_files=1, io_mode=io_mode, **SMALL))
+    ck.register_tensors(shard.descs())
+    assert len([f for f in os.listdir(tmp_path) if f.startswith(".spare_")]) == 1
+    want = {}
+    for it in range(1, 7):
+        shard.update(it, stream)
+        ck.snapshot_async(it, stream.cuda_stream)
+        ck.wait_immutable_window_end(stream.cuda_stream, host_block=True)
+        want[it] = oracle.serialize_bytes(shard.oracle_tensors(shard.readback_all()), it)
+        ck.flush(it)
+        names = sorted(f for f in os.listdir(tmp_path) if not f.startswith("."))
+        assert names == [os.path.basename(ck.file_name(j)) for j in range(max(1, it - 1), it + 1)], names
+        assert open(ck.file_name(it), "rb").read() == want[it]
+        if it > 1:
+            assert open(ck.file_name(it - 1), "rb").read() == want[it - 1]
+    assert ck.stats(1)["committed"] == 1          # measurements of retired snapshots stay available
+    ck.destroy()
+    assert not [f for f in os.listdir(tmp_path) if f.startswith(".spare_")]
+
+
 @pytest.mark.parametrize("config", [1, 5])
 def test_every_iteration_with_mutation(config, tmp_path):
     """Snapshot every iteration while the update keeps mutating everything, with nothing but stream
