@@ -38,7 +38,7 @@ def parse_args():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: Llama-7B-shaped shard, 94 GB)")
     ap.add_argument("--ckpt-every", type=int, default=0, help="0: the workload's own interval")
     ap.add_argument("--compute-ms", type=float, default=0.0, help="0: the workload's own forward+backward length")
-    ap.add_argument("--ring-gib", type=float, default=0.0, help="0: the whole data region, at most 64 GiB")
+    ap.add_argument("--ring-gib", type=float, default=0.0, help="0: the whole data region, at most 48 GiB")
     ap.add_argument("--staging-gib", type=float, default=0.0, help="0: two super-chunks")
     ap.add_argument("--chunk-mib", type=int, default=64)
     ap.add_argument("--superchunk-mib", type=int, default=1024)
@@ -53,6 +53,7 @@ def parse_args():
     ap.add_argument("--oracle-sample-gb", type=float, default=12.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-restore", action="store_true")
+    ap.add_argument("--dump", default="", help="write per-step timings and per-snapshot measurements to this JSON file")
     return ap.parse_args()
 
 
@@ -153,7 +154,7 @@ def run(args, torch, B, harness, spec, every, compute_ms, out_dir, dev):
     policy = B.CKPT_WINDOW_PACK if args.policy == "pack" else B.CKPT_WINDOW_D2H
     chunk = args.chunk_mib << 20
     # the paper pre-allocates a host cache large enough for the shard; capped so that cache + one file fit the box
-    ring_bytes = int(args.ring_gib * (1 << 30)) or min(64 << 30, -(-(spec.payload_bytes + 4096 * len(spec.tensors)) // chunk) * chunk)
+    ring_bytes = int(args.ring_gib * (1 << 30)) or min(48 << 30, -(-(spec.payload_bytes + 4096 * len(spec.tensors)) // chunk) * chunk)
     args.ring_gib = round(ring_bytes / (1 << 30), 2)
     cfg = B.make_config(out_dir=out_dir, host_ring_bytes=ring_bytes, dma_chunk_bytes=args.chunk_mib << 20,
                         pack_superchunk_bytes=args.superchunk_mib << 20, dev_staging_bytes=int(args.staging_gib * (1 << 30)),
@@ -298,6 +299,11 @@ def run(args, torch, B, harness, spec, every, compute_ms, out_dir, dev):
                   "gemm_slowdown_pct": round(100.0 * (statistics.median(busy) / base_gemm_ms - 1), 3) if busy else None,
                   "gemm_tflops": round(gemm.flops_per_launch / (gemm_ms_per_launch * 1e-3) / 1e12, 1)},
     }
+
+    if args.dump:
+        with open(args.dump, "w") as f:
+            json.dump({"first_timed_step": first_timed, "iter_ms": iter_ms, "gemm_ms": gemm_ms, "requested": requested,
+                       "snapshots": all_stats, "baseline_iter_ms": base_iter_ms, "baseline_gemm_ms": base_gemm_ms}, f, indent=1)
 
     if not args.no_restore and requested:
         last = requested[-1]

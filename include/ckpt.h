@@ -131,6 +131,8 @@ typedef struct {
     double host_backpressure_ms;      /* host: time the submit thread spent waiting for a free ring slot */
     double host_snapshot_call_ms;     /* host: time the caller spent inside ckpt_snapshot_async */
     double host_flush_span_ms;        /* host: first chunk on the host -> file renamed (the flush proper) */
+    double host_io_wait_ms_sum;       /* host: summed over I/O threads, time waiting for chunks' copy events */
+    double host_io_copy_ms_sum;       /* host: summed over I/O threads, time writing ring slots to the file */
 } ckpt_stats;
 
 #define CKPT_ITER_ALL UINT64_MAX

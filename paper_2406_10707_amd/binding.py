@@ -53,7 +53,7 @@ class ckpt_stats(C.Structure):
                 ("pack_ms_sum", C.c_double), ("request_to_d2h_end_ms", C.c_double), ("d2h_span_ms", C.c_double),
                 ("request_to_pack_end_ms", C.c_double), ("host_submit_ms", C.c_double), ("host_request_to_commit_ms", C.c_double),
                 ("host_backpressure_ms", C.c_double), ("host_snapshot_call_ms", C.c_double),
-                ("host_flush_span_ms", C.c_double)]
+                ("host_flush_span_ms", C.c_double), ("host_io_wait_ms_sum", C.c_double), ("host_io_copy_ms_sum", C.c_double)]
 
 
 class CkptError(RuntimeError):

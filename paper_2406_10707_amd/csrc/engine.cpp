@@ -42,6 +42,12 @@ static thread_local std::string g_last_error;
 static int fail(int code, const std::string &msg) { g_last_error = msg; return code; }
 static double ms_between(Clock::time_point a, Clock::time_point b) { return std::chrono::duration<double, std::milli>(b - a).count(); }
 
+// Progress lines on stderr when DSLLM_CKPT_TRACE is set in the environment (set-up stages only).
+static void trace(const char *what) {
+    static const bool on = getenv("DSLLM_CKPT_TRACE") != nullptr;
+    if (on) { fprintf(stderr, "[dsllm_ckpt] %s\n", what); fflush(stderr); }
+}
+
 struct ckpt_plan { Plan plan; };
 
 namespace {
@@ -72,6 +78,7 @@ struct Snap {
     Clock::time_point t_request, t_submitted, t_committed, t_first_chunk;
     bool have_first_chunk = false;
     double call_ms = 0, backpressure_ms = 0;
+    std::atomic<uint64_t> io_wait_us{0}, io_copy_us{0};   // summed over the I/O threads
     double pack_ms_sum = -1, req_to_d2h_end_ms = -1, d2h_span_ms = -1, req_to_pack_end_ms = -1;
 };
 
@@ -248,7 +255,10 @@ static void io_thread_main(ckpt_ctx *c) {
         }
         // WRITE: the chunk's copy must have landed in the slot first
         Snap *s = job.snap.get();
+        auto tw0 = Clock::now();
         hipError_t he = hipEventSynchronize(c->ev_slot[job.slot]);
+        auto tw1 = Clock::now();
+        s->io_wait_us += uint64_t(ms_between(tw0, tw1) * 1000.0);
         if (he != hipSuccess) c->latch(CKPT_EHIP, std::string("copy event: ") + hipGetErrorString(he));
         if (job.file_off == c->plan.header_bytes) {
             std::lock_guard<std::mutex> lk(c->mu);
@@ -273,6 +283,7 @@ static void io_thread_main(ckpt_ctx *c) {
             c->slot_state[job.slot] = SLOT_FREE;
             c->cv_state.notify_all();
         }
+        s->io_copy_us += uint64_t(ms_between(tw1, Clock::now()) * 1000.0);
         if (s->chunks_left.fetch_sub(1) == 1) {
             // last chunk written: commit
             if (s->fd >= 0) {
@@ -552,9 +563,35 @@ int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out) {
     c->device = cfg->device;
     c->out_dir = cfg->out_dir;
     c->n_slots = rc.host_ring_bytes / rc.dma_chunk_bytes;
+    trace("init: creating streams and events");
+    c->slot_state.assign(c->n_slots, SLOT_FREE);
+    hipError_t e = hipSuccess;
+    auto cleanup_fail = [&](int code, const std::string &m) { trace(("init: failed: " + m).c_str()); ckpt_destroy(c.release()); return fail(code, m); };
+    if ((e = hipStreamCreateWithFlags(&c->pack_stream, hipStreamNonBlocking)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
+    for (int k = 0; k < rc.n_dma_streams; k++) {
+        hipStream_t s;
+        if ((e = hipStreamCreateWithFlags(&s, hipStreamNonBlocking)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
+        c->dma.push_back(s);
+    }
+    trace("init: streams created");
+    for (uint64_t i = 0; i < c->n_slots; i++) {
+        hipEvent_t ev;
+        if ((e = hipEventCreateWithFlags(&ev, hipEventBlockingSync)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
+        c->ev_slot.push_back(ev);
+    }
+    trace("init: slot events created");
+    for (int k = 0; k < rc.n_dma_streams; k++) {
+        hipEvent_t ev;
+        if ((e = hipEventCreateWithFlags(&ev, hipEventBlockingSync)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
+        c->ev_job_tail.push_back(ev);
+    }
+    if ((e = hipEventCreate(&c->ev_first_copy)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
+    if ((e = hipEventCreate(&c->ev_user)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
     void *ring = nullptr;
-    hipError_t e = hipHostMalloc(&ring, rc.host_ring_bytes, hipHostMallocDefault);
-    if (e != hipSuccess) return fail(CKPT_ENOMEM, std::string("hipHostMalloc(ring): ") + hipGetErrorString(e));
+    trace("init: allocating the pinned ring");
+    e = hipHostMalloc(&ring, rc.host_ring_bytes, hipHostMallocDefault);
+    trace("init: ring allocated, touching pages");
+    if (e != hipSuccess) return cleanup_fail(CKPT_ENOMEM, std::string("hipHostMalloc(ring): ") + hipGetErrorString(e));
     c->ring = static_cast<uint8_t *>(ring);
     {   // touch every page now, in parallel, so no snapshot pays for first-touch page faults
         int nt = std::max(1, std::min(rc.n_io_threads, 16));
@@ -567,29 +604,12 @@ int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out) {
             });
         for (auto &t : th) t.join();
     }
-    c->slot_state.assign(c->n_slots, SLOT_FREE);
-    auto cleanup_fail = [&](int code, const std::string &m) { ckpt_destroy(c.release()); return fail(code, m); };
-    if ((e = hipStreamCreateWithFlags(&c->pack_stream, hipStreamNonBlocking)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
-    for (int k = 0; k < rc.n_dma_streams; k++) {
-        hipStream_t s;
-        if ((e = hipStreamCreateWithFlags(&s, hipStreamNonBlocking)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
-        c->dma.push_back(s);
-    }
-    for (uint64_t i = 0; i < c->n_slots; i++) {
-        hipEvent_t ev;
-        if ((e = hipEventCreateWithFlags(&ev, hipEventBlockingSync)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
-        c->ev_slot.push_back(ev);
-    }
-    for (int k = 0; k < rc.n_dma_streams; k++) {
-        hipEvent_t ev;
-        if ((e = hipEventCreateWithFlags(&ev, hipEventBlockingSync)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
-        c->ev_job_tail.push_back(ev);
-    }
-    if ((e = hipEventCreate(&c->ev_first_copy)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
-    if ((e = hipEventCreate(&c->ev_user)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
+    trace("init: pages touched");
+    trace("init: starting threads");
     c->submit_thread = std::thread(submit_thread_main, c.get());
     for (int i = 0; i < rc.n_io_threads; i++) c->io_threads.emplace_back(io_thread_main, c.get());
     *out = c.release();
+    trace("init: done");
     return CKPT_OK;
 }
 
@@ -817,6 +837,8 @@ int ckpt_get_stats(ckpt_ctx *c, uint64_t iter, ckpt_stats *o) {
     o->host_request_to_commit_ms = s.committed ? ms_between(s.t_request, s.t_committed) : -1;
     o->host_backpressure_ms = s.submitted ? s.backpressure_ms : -1;
     o->host_snapshot_call_ms = s.call_ms;
+    o->host_io_wait_ms_sum = s.io_wait_us.load() / 1000.0;
+    o->host_io_copy_ms_sum = s.io_copy_us.load() / 1000.0;
     o->host_flush_span_ms = (s.committed && s.have_first_chunk) ? ms_between(s.t_first_chunk, s.t_committed) : -1;
     return CKPT_OK;
 }
