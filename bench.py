@@ -38,7 +38,7 @@ def parse_args():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: Llama-7B-shaped shard, 94 GB)")
     ap.add_argument("--ckpt-every", type=int, default=0, help="0: the workload's own interval")
     ap.add_argument("--compute-ms", type=float, default=0.0, help="0: the workload's own forward+backward length")
-    ap.add_argument("--ring-gib", type=float, default=0.0, help="0: the whole data region, at most 48 GiB")
+    ap.add_argument("--ring-gib", type=float, default=0.0, help="0: the whole data region, at most 16 GiB")
     ap.add_argument("--staging-gib", type=float, default=0.0, help="0: two super-chunks")
     ap.add_argument("--chunk-mib", type=int, default=64)
     ap.add_argument("--superchunk-mib", type=int, default=1024)
@@ -50,51 +50,49 @@ def parse_args():
     ap.add_argument("--prealloc", type=int, default=2, help="spare files pre-allocated at registration")
     ap.add_argument("--out-dir", default="")
     ap.add_argument("--baseline-steps", type=int, default=6)
-    ap.add_argument("--oracle-sample-gb", type=float, default=12.0)
+    ap.add_argument("--oracle-sample-gb", type=float, default=8.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-restore", action="store_true")
     ap.add_argument("--dump", default="", help="write per-step timings and per-snapshot measurements to this JSON file")
     return ap.parse_args()
 
 
-def measure_link_peak(torch, dev, s, nbytes=1 << 30, reps=10):
+def measure_link_peak(B, harness, s, nbytes=1 << 30, reps=10):
     """Best of `reps` single pinned copies of 1 GiB in each direction (GB/s)."""
-    d = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-    h = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
-    h.zero_()
+    d = harness.DevBuf(nbytes)
+    h = B.proxy_host_alloc_pinned(nbytes)
     best = {"d2h": 0.0, "h2d": 0.0}
-    with torch.cuda.stream(s):
-        for name, dst, src in (("d2h", h, d), ("h2d", d, h)):
-            for _ in range(reps):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record(s)
-                dst.copy_(src, non_blocking=True)
-                e1.record(s)
-                e1.synchronize()
-                best[name] = max(best[name], nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
-    del d, h
-    return best
-
-
-def measure_devcopy(torch, B, dev, s, nbytes=4 << 30, reps=5):
-    """Contiguous aligned copy kernel: the practical HBM ceiling for the pack kernel (GB/s read+write)."""
-    a = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-    b = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-    a.zero_()
-    best = 0.0
-    with torch.cuda.stream(s):
+    for name, to_host in (("d2h", True), ("h2d", False)):
         for _ in range(reps):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0, e1 = harness.Event(), harness.Event()
             e0.record(s)
-            B.proxy_devcopy(b.data_ptr(), a.data_ptr(), nbytes, s.cuda_stream)
+            B.proxy_copy_pinned_async(h if to_host else d.ptr, d.ptr if to_host else h, nbytes, to_host, s.handle)
             e1.record(s)
             e1.synchronize()
-            best = max(best, 2 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
-    del a, b
+            best[name] = max(best[name], nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    B.proxy_host_free_pinned(h)
+    d.free()
     return best
 
 
-def cpu_baseline(torch, shard, sample_bytes, out_dir):
+def measure_devcopy(B, harness, s, nbytes=4 << 30, reps=5):
+    """Contiguous aligned copy kernel: the practical HBM ceiling for the pack kernel (GB/s read+write)."""
+    a, b = harness.DevBuf(nbytes), harness.DevBuf(nbytes)
+    B.proxy_device_fill_async(a.ptr, 1, nbytes, s.handle)
+    best = 0.0
+    for _ in range(reps):
+        e0, e1 = harness.Event(), harness.Event()
+        e0.record(s)
+        B.proxy_devcopy(b.ptr, a.ptr, nbytes, s.handle)
+        e1.record(s)
+        e1.synchronize()
+        best = max(best, 2 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    a.free()
+    b.free()
+    return best
+
+
+def cpu_baseline(harness, shard, sample_bytes, out_dir):
     """The oracle as it stands: blocking per-tensor read-back into pageable memory, then the plain C
     serializer writing the same format to the same sink. One host thread."""
     from oracle import oracle
@@ -105,7 +103,7 @@ def cpu_baseline(torch, shard, sample_bytes, out_dir):
         if total >= sample_bytes:
             break
     path = os.path.join(out_dir, "oracle_sample.dsl")
-    torch.cuda.synchronize()
+    harness.synchronize()
     t0 = time.perf_counter()
     host = [shard.readback(k) for k in ks]
     tensors = [(shard.spec.tensors[k].name, shard.spec.tensors[k].dtype, shard.spec.tensors[k].shape, h) for k, h in zip(ks, host)]
@@ -123,38 +121,36 @@ def main():
         print("bench.py: this build measures one GPU; --gpus %d is not supported (each box has one MI355X and the "
               "snapshot path of a shard needs no exchange between GPUs)" % args.gpus, file=sys.stderr)
         sys.exit(2)
-    import torch
     from paper_2406_10707_amd import binding as B
     from paper_2406_10707_amd import harness, shards
 
-    dev = "cuda:0"
-    torch.cuda.set_device(0)
     spec = shards.make_shard(args.config)
     every = args.ckpt_every or spec.ckpt_every
     compute_ms = args.compute_ms or spec.compute_ms
     base = args.out_dir or ("/dev/shm" if os.path.isdir("/dev/shm") else None)
     out_dir = tempfile.mkdtemp(prefix="dsllm_bench_", dir=base)
     try:
-        run(args, torch, B, harness, spec, every, compute_ms, out_dir, dev)
+        run(args, B, harness, spec, every, compute_ms, out_dir)
     finally:
         shutil.rmtree(out_dir, ignore_errors=True)
 
 
-def run(args, torch, B, harness, spec, every, compute_ms, out_dir, dev):
-    stream = harness.make_compute_stream(dev)
-    link = measure_link_peak(torch, dev, stream)
-    devcopy_gbps = measure_devcopy(torch, B, dev, stream)
+def run(args, B, harness, spec, every, compute_ms, out_dir):
+    info = B.proxy_device_info()
+    stream = harness.make_compute_stream()
+    link = measure_link_peak(B, harness, stream)
+    devcopy_gbps = measure_devcopy(B, harness, stream)
 
-    shard = harness.DeviceShard(spec, dev)
+    shard = harness.DeviceShard(spec)
     shard.fill_device(stream)
     stream.synchronize()
-    gemm = harness.GemmProxy(8192, dev)
+    gemm = harness.GemmProxy(8192)
     launches, gemm_ms_per_launch = gemm.calibrate(compute_ms, stream)
 
     policy = B.CKPT_WINDOW_PACK if args.policy == "pack" else B.CKPT_WINDOW_D2H
     chunk = args.chunk_mib << 20
     # the paper pre-allocates a host cache large enough for the shard; capped so that cache + one file fit the box
-    ring_bytes = int(args.ring_gib * (1 << 30)) or min(48 << 30, -(-(spec.payload_bytes + 4096 * len(spec.tensors)) // chunk) * chunk)
+    ring_bytes = int(args.ring_gib * (1 << 30)) or min(16 << 30, -(-(spec.payload_bytes + 4096 * len(spec.tensors)) // chunk) * chunk)
     args.ring_gib = round(ring_bytes / (1 << 30), 2)
     cfg = B.make_config(out_dir=out_dir, host_ring_bytes=ring_bytes, dma_chunk_bytes=args.chunk_mib << 20,
                         pack_superchunk_bytes=args.superchunk_mib << 20, dev_staging_bytes=int(args.staging_gib * (1 << 30)),
@@ -169,7 +165,7 @@ def run(args, torch, B, harness, spec, every, compute_ms, out_dir, dev):
 
     def iteration(step, with_ckpt, marks):
         """One step on `stream`; marks gets (start, after-gemm, end) events."""
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e = [harness.Event() for _ in range(3)]
         e[0].record(stream)
         gemm.run(launches, stream)
         e[1].record(stream)
@@ -196,40 +192,39 @@ def run(args, torch, B, harness, spec, every, compute_ms, out_dir, dev):
                 os.unlink(ck.file_name(it))
                 live_files.remove(it)
 
-    with torch.cuda.stream(stream):
-        # ---- baseline: same steps, checkpointing off
-        marks = []
-        for i in range(2 + args.baseline_steps):
-            iteration(1000000 + i, False, marks)
-        stream.synchronize()
-        base_iter_ms = statistics.median(m[0].elapsed_time(m[2]) for m in marks[2:])
-        base_gemm_ms = statistics.median(m[0].elapsed_time(m[1]) for m in marks[2:])
+    # ---- baseline: same steps, checkpointing off
+    marks = []
+    for i in range(2 + args.baseline_steps):
+        iteration(1000000 + i, False, marks)
+    stream.synchronize()
+    base_iter_ms = statistics.median(m[0].elapsed_time(m[2]) for m in marks[2:])
+    base_gemm_ms = statistics.median(m[0].elapsed_time(m[1]) for m in marks[2:])
 
-        # ---- warm-up with checkpointing (untimed)
-        step = 0
-        wmarks = []
-        for _ in range(args.warmup):
-            step += 1
-            n_before = len(requested)
-            iteration(step, True, wmarks)
-            if len(requested) > n_before:
-                live_files.append(requested[-1])
-            reap()
-        torch.cuda.synchronize()
-        first_timed = step + 1
+    # ---- warm-up with checkpointing (untimed)
+    step = 0
+    wmarks = []
+    for _ in range(args.warmup):
+        step += 1
+        n_before = len(requested)
+        iteration(step, True, wmarks)
+        if len(requested) > n_before:
+            live_files.append(requested[-1])
+        reap()
+    harness.synchronize()
+    first_timed = step + 1
 
-        # ---- timed region: exactly K steps
-        marks = []
-        t_start = time.perf_counter()
-        for _ in range(args.steps):
-            step += 1
-            n_before = len(requested)
-            iteration(step, True, marks)
-            if len(requested) > n_before:
-                live_files.append(requested[-1])
-            reap()
-        torch.cuda.synchronize()
-        elapsed = time.perf_counter() - t_start
+    # ---- timed region: exactly K steps
+    marks = []
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step += 1
+        n_before = len(requested)
+        iteration(step, True, marks)
+        if len(requested) > n_before:
+            live_files.append(requested[-1])
+        reap()
+    harness.synchronize()
+    elapsed = time.perf_counter() - t_start
     ms_per_step = elapsed * 1e3 / args.steps
 
     # ---- drain (the paper counts pending flushes in end-to-end time; reported, not part of the K steps)
@@ -273,7 +268,8 @@ def run(args, torch, B, harness, spec, every, compute_ms, out_dir, dev):
                    "ckpt_every": every, "compute_ms": compute_ms, "window_policy": args.policy,
                    "ring_gib": args.ring_gib, "dma_chunk_mib": args.chunk_mib, "pack_superchunk_mib": args.superchunk_mib,
                    "staging_gib": args.staging_gib or 2 * args.superchunk_mib / 1024, "dma_streams": args.dma_streams,
-                   "io_threads": args.io_threads, "hw_queues": int(os.environ["GPU_MAX_HW_QUEUES"]), "io_mode": args.io_mode, "keep_last": args.keep_last, "prealloc_files": args.prealloc, "sink": out_dir.rsplit("/", 1)[0]},
+                   "io_threads": args.io_threads, "hw_queues": int(os.environ["GPU_MAX_HW_QUEUES"]), "device": info["name"],
+                   "hip_runtime": info["hip_runtime_version"], "io_mode": args.io_mode, "keep_last": args.keep_last, "prealloc_files": args.prealloc, "sink": out_dir.rsplit("/", 1)[0]},
         "roofline": {"bound": "hbm", "kernel": "pack_kernel", "achieved": round(pack_gbps, 1) if pack_gbps else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(pack_gbps / HBM_PEAK_GBPS, 4) if pack_gbps else None,
                      "traffic": None, "launches": pack_launches,
@@ -307,11 +303,11 @@ def run(args, torch, B, harness, spec, every, compute_ms, out_dir, dev):
 
     if not args.no_restore and requested:
         last = requested[-1]
-        shard_probe = [0, len(shard.bufs) // 2, len(shard.bufs) - 1]
+        shard_probe = [0, len(shard.ptrs) // 2, len(shard.ptrs) - 1]
         want = {k: shard.readback(k) for k in shard_probe}
         for k in shard_probe:
-            shard.bufs[k].fill_(0xA5)
-        torch.cuda.synchronize()
+            B.proxy_device_fill_async(shard.ptrs[k], 0xA5, shard.spec.tensors[k].nbytes, stream.handle)
+        harness.synchronize()
         t0 = time.perf_counter()
         ck.restore(ck.file_name(last), stream.cuda_stream)
         stream.synchronize()
@@ -321,7 +317,7 @@ def run(args, torch, B, harness, spec, every, compute_ms, out_dir, dev):
         result["restore"] = {"gbps": round(S / dt / 1e9, 2), "seconds": round(dt, 2), "probe_tensors_bit_exact": ok if ok is None else bool(ok)}
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(torch, shard, int(args.oracle_sample_gb * 1e9), out_dir)
+        result["cpu_baseline"] = cpu_baseline(harness, shard, int(args.oracle_sample_gb * 1e9), out_dir)
     ck.destroy()
     print(json.dumps(result), flush=True)
 

@@ -53,6 +53,28 @@ int proxy_mutate_words(void *dev_words, uint64_t n_words, uint64_t step, void *s
  * copy whose bandwidth is the practical ceiling for the pack kernel. */
 int proxy_devcopy(void *dev_dst, const void *dev_src, uint64_t nbytes, void *stream);
 
+/* ---- device memory, copies, events: thin wrappers so that a harness needs no other GPU package ----
+ * All return 0 on success, -1 on a bad argument, -4 on a HIP error. Copies marked blocking return
+ * when the bytes have arrived; host pointers of the blocking copies may be pageable. */
+int proxy_device_alloc(uint64_t nbytes, void **dev_out);              /* hipMalloc */
+int proxy_device_free(void *dev);
+int proxy_host_alloc_pinned(uint64_t nbytes, void **host_out);        /* hipHostMalloc, pages touched */
+int proxy_host_free_pinned(void *host);
+int proxy_copy_h2d(void *dev_dst, const void *host_src, uint64_t nbytes);                 /* blocking */
+int proxy_copy_d2h(void *host_dst, const void *dev_src, uint64_t nbytes);                 /* blocking */
+int proxy_copy_d2d_async(void *dev_dst, const void *dev_src, uint64_t nbytes, void *stream);
+int proxy_copy_pinned_async(void *dst, const void *src, uint64_t nbytes, int32_t to_host, void *stream);
+int proxy_device_fill_async(void *dev, int32_t byte, uint64_t nbytes, void *stream);      /* hipMemsetAsync */
+int proxy_stream_synchronize(void *stream);
+int proxy_device_synchronize(void);
+int proxy_event_create(void **event_out);                             /* timing enabled */
+int proxy_event_destroy(void *event);
+int proxy_event_record(void *event, void *stream);
+int proxy_event_synchronize(void *event);
+int proxy_event_elapsed_ms(void *start, void *stop, float *ms_out);
+int proxy_device_info(char *name_buf, uint64_t name_cap, int32_t *cu_count, uint64_t *total_mem, uint64_t *free_mem,
+                      int32_t *runtime_version);
+
 /* A plain non-blocking HIP stream of default priority (hipStreamCreateWithFlags), returned as void*.
  * The harness takes its compute stream from here instead of a framework's stream pool: every HIP
  * stream is mapped onto one of a few hardware queues, and work of two streams that share a queue

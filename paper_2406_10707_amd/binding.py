@@ -5,12 +5,10 @@ import ctypes as C
 import os
 
 # The library must use the same HIP runtime as whoever owns the device memory and the streams it is
-# handed. PyTorch ships a runtime of its own, so when PyTorch is in the process it is loaded first and
-# libdsllm_ckpt.so then binds to that already-loaded libamdhip64 instead of bringing a second one.
-try:
-    import torch  # noqa: F401
-except ImportError:  # a pure C caller links the system runtime; nothing to align with
-    torch = None
+# handed; one process must never hold two HIP runtimes. libdsllm_ckpt.so binds to whichever
+# libamdhip64 is already loaded, else to the system one (/opt/rocm). A caller that also uses PyTorch,
+# which ships a runtime of its own, must import torch BEFORE this module. The harness, tests and
+# benchmark of this repository do not use PyTorch at all and so run on the system runtime.
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libdsllm_ckpt.so")
@@ -95,6 +93,23 @@ _SIGS = {
     "proxy_fill_words": (C.c_int, [_vp, _u64, _u64, _vp]),
     "proxy_mutate_words": (C.c_int, [_vp, _u64, _u64, _vp]),
     "proxy_devcopy": (C.c_int, [_vp, _vp, _u64, _vp]),
+    "proxy_device_alloc": (C.c_int, [_u64, C.POINTER(_vp)]),
+    "proxy_device_free": (C.c_int, [_vp]),
+    "proxy_host_alloc_pinned": (C.c_int, [_u64, C.POINTER(_vp)]),
+    "proxy_host_free_pinned": (C.c_int, [_vp]),
+    "proxy_copy_h2d": (C.c_int, [_vp, _vp, _u64]),
+    "proxy_copy_d2h": (C.c_int, [_vp, _vp, _u64]),
+    "proxy_copy_d2d_async": (C.c_int, [_vp, _vp, _u64, _vp]),
+    "proxy_copy_pinned_async": (C.c_int, [_vp, _vp, _u64, _i32, _vp]),
+    "proxy_device_fill_async": (C.c_int, [_vp, _i32, _u64, _vp]),
+    "proxy_stream_synchronize": (C.c_int, [_vp]),
+    "proxy_device_synchronize": (C.c_int, []),
+    "proxy_event_create": (C.c_int, [C.POINTER(_vp)]),
+    "proxy_event_destroy": (C.c_int, [_vp]),
+    "proxy_event_record": (C.c_int, [_vp, _vp]),
+    "proxy_event_synchronize": (C.c_int, [_vp]),
+    "proxy_event_elapsed_ms": (C.c_int, [_vp, _vp, C.POINTER(C.c_float)]),
+    "proxy_device_info": (C.c_int, [C.c_char_p, _u64, C.POINTER(_i32), C.POINTER(_u64), C.POINTER(_u64), C.POINTER(_i32)]),
     "proxy_stream_create": (C.c_int, [C.POINTER(_vp)]),
     "proxy_stream_destroy": (C.c_int, [_vp]),
 }
@@ -288,3 +303,84 @@ def proxy_stream_create():
 
 def proxy_stream_destroy(stream):
     _proxy(lib.proxy_stream_destroy(stream), "proxy_stream_destroy")
+
+
+def proxy_device_alloc(nbytes):
+    out = _vp()
+    _proxy(lib.proxy_device_alloc(nbytes, C.byref(out)), "proxy_device_alloc(%d)" % nbytes)
+    return out.value
+
+
+def proxy_device_free(ptr):
+    _proxy(lib.proxy_device_free(ptr), "proxy_device_free")
+
+
+def proxy_host_alloc_pinned(nbytes):
+    out = _vp()
+    _proxy(lib.proxy_host_alloc_pinned(nbytes, C.byref(out)), "proxy_host_alloc_pinned(%d)" % nbytes)
+    return out.value
+
+
+def proxy_host_free_pinned(ptr):
+    _proxy(lib.proxy_host_free_pinned(ptr), "proxy_host_free_pinned")
+
+
+def proxy_copy_h2d(dev, host, nbytes):
+    _proxy(lib.proxy_copy_h2d(dev, host, nbytes), "proxy_copy_h2d")
+
+
+def proxy_copy_d2h(host, dev, nbytes):
+    _proxy(lib.proxy_copy_d2h(host, dev, nbytes), "proxy_copy_d2h")
+
+
+def proxy_copy_d2d_async(dst, src, nbytes, stream):
+    _proxy(lib.proxy_copy_d2d_async(dst, src, nbytes, stream), "proxy_copy_d2d_async")
+
+
+def proxy_copy_pinned_async(dst, src, nbytes, to_host, stream):
+    _proxy(lib.proxy_copy_pinned_async(dst, src, nbytes, 1 if to_host else 0, stream), "proxy_copy_pinned_async")
+
+
+def proxy_device_fill_async(dev, byte, nbytes, stream):
+    _proxy(lib.proxy_device_fill_async(dev, byte, nbytes, stream), "proxy_device_fill_async")
+
+
+def proxy_stream_synchronize(stream):
+    _proxy(lib.proxy_stream_synchronize(stream), "proxy_stream_synchronize")
+
+
+def proxy_device_synchronize():
+    _proxy(lib.proxy_device_synchronize(), "proxy_device_synchronize")
+
+
+def proxy_event_create():
+    out = _vp()
+    _proxy(lib.proxy_event_create(C.byref(out)), "proxy_event_create")
+    return out.value
+
+
+def proxy_event_destroy(ev):
+    _proxy(lib.proxy_event_destroy(ev), "proxy_event_destroy")
+
+
+def proxy_event_record(ev, stream):
+    _proxy(lib.proxy_event_record(ev, stream), "proxy_event_record")
+
+
+def proxy_event_synchronize(ev):
+    _proxy(lib.proxy_event_synchronize(ev), "proxy_event_synchronize")
+
+
+def proxy_event_elapsed_ms(start, stop):
+    ms = C.c_float(0)
+    _proxy(lib.proxy_event_elapsed_ms(start, stop, C.byref(ms)), "proxy_event_elapsed_ms")
+    return ms.value
+
+
+def proxy_device_info():
+    name = C.create_string_buffer(256)
+    cus, ver = _i32(0), _i32(0)
+    total, free = _u64(0), _u64(0)
+    _proxy(lib.proxy_device_info(name, 256, C.byref(cus), C.byref(total), C.byref(free), C.byref(ver)), "proxy_device_info")
+    return {"name": name.value.decode(), "compute_units": cus.value, "total_mem": total.value, "free_mem": free.value,
+            "hip_runtime_version": ver.value}

@@ -347,7 +347,9 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
     if (c->prev_job) {
         for (size_t k = 0; k < nk; k++) if ((e = hipEventSynchronize(c->ev_job_tail[k])) != hipSuccess) hip_fail("tail sync", e);
         std::unique_lock<std::mutex> lk(c->mu);
-        c->cv_state.wait(lk, [&] { return c->prev_job->d2h_done; });
+        // with retention the previous commit is also what retires an older file into the spare pool this
+        // snapshot is about to draw from: wait for it (it follows the last copy by one chunk write)
+        c->cv_state.wait(lk, [&] { return c->prev_job->d2h_done && (c->cfg.keep_last == 0 || c->prev_job->committed); });
     }
 
     // file and header

@@ -2,6 +2,7 @@
 // element-wise Adam step, seeded state fill, flat-buffer word fill/mutate, contiguous copy.
 #include <hip/hip_runtime.h>
 #include <math.h>
+#include <stdio.h>
 #include <stdint.h>
 
 #include "../../include/ckpt_proxy.h"
@@ -281,6 +282,66 @@ int proxy_devcopy(void *dst, const void *src, uint64_t nbytes, void *stream) {
     hipLaunchKernelGGL(devcopy_kernel, dim3(unsigned(blocks)), dim3(256), 0, static_cast<hipStream_t>(stream), static_cast<u32x4 *>(dst),
                        static_cast<const u32x4 *>(src), n16);
     return hip_rc();
+}
+
+#define PROXY_TRY(expr) do { if ((expr) != hipSuccess) { (void)hipGetLastError(); return -4; } } while (0)
+
+int proxy_device_alloc(uint64_t nbytes, void **out) {
+    if (!out || nbytes == 0) return -1;
+    PROXY_TRY(hipMalloc(out, nbytes));
+    return 0;
+}
+int proxy_device_free(void *dev) { if (!dev) return -1; PROXY_TRY(hipFree(dev)); return 0; }
+int proxy_host_alloc_pinned(uint64_t nbytes, void **out) {
+    if (!out || nbytes == 0) return -1;
+    PROXY_TRY(hipHostMalloc(out, nbytes, hipHostMallocDefault));
+    for (uint64_t o = 0; o < nbytes; o += 4096) static_cast<volatile char *>(*out)[o] = 0;
+    return 0;
+}
+int proxy_host_free_pinned(void *host) { if (!host) return -1; PROXY_TRY(hipHostFree(host)); return 0; }
+int proxy_copy_h2d(void *dst, const void *src, uint64_t n) { if (!dst || !src) return -1; if (n) PROXY_TRY(hipMemcpy(dst, src, n, hipMemcpyHostToDevice)); return 0; }
+int proxy_copy_d2h(void *dst, const void *src, uint64_t n) { if (!dst || !src) return -1; if (n) PROXY_TRY(hipMemcpy(dst, src, n, hipMemcpyDeviceToHost)); return 0; }
+int proxy_copy_d2d_async(void *dst, const void *src, uint64_t n, void *stream) {
+    if (!dst || !src) return -1;
+    if (n) PROXY_TRY(hipMemcpyAsync(dst, src, n, hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)));
+    return 0;
+}
+int proxy_copy_pinned_async(void *dst, const void *src, uint64_t n, int32_t to_host, void *stream) {
+    if (!dst || !src) return -1;
+    if (n) PROXY_TRY(hipMemcpyAsync(dst, src, n, to_host ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice, static_cast<hipStream_t>(stream)));
+    return 0;
+}
+int proxy_device_fill_async(void *dev, int32_t byte, uint64_t n, void *stream) {
+    if (!dev) return -1;
+    if (n) PROXY_TRY(hipMemsetAsync(dev, byte, n, static_cast<hipStream_t>(stream)));
+    return 0;
+}
+int proxy_stream_synchronize(void *stream) { PROXY_TRY(hipStreamSynchronize(static_cast<hipStream_t>(stream))); return 0; }
+int proxy_device_synchronize(void) { PROXY_TRY(hipDeviceSynchronize()); return 0; }
+int proxy_event_create(void **out) { if (!out) return -1; hipEvent_t e; PROXY_TRY(hipEventCreate(&e)); *out = e; return 0; }
+int proxy_event_destroy(void *e) { if (!e) return -1; PROXY_TRY(hipEventDestroy(static_cast<hipEvent_t>(e))); return 0; }
+int proxy_event_record(void *e, void *stream) { if (!e) return -1; PROXY_TRY(hipEventRecord(static_cast<hipEvent_t>(e), static_cast<hipStream_t>(stream))); return 0; }
+int proxy_event_synchronize(void *e) { if (!e) return -1; PROXY_TRY(hipEventSynchronize(static_cast<hipEvent_t>(e))); return 0; }
+int proxy_event_elapsed_ms(void *a, void *b, float *ms) {
+    if (!a || !b || !ms) return -1;
+    PROXY_TRY(hipEventElapsedTime(ms, static_cast<hipEvent_t>(a), static_cast<hipEvent_t>(b)));
+    return 0;
+}
+int proxy_device_info(char *name, uint64_t cap, int32_t *cus, uint64_t *total, uint64_t *free_, int32_t *ver) {
+    int dev = 0;
+    PROXY_TRY(hipGetDevice(&dev));
+    hipDeviceProp_t p;
+    PROXY_TRY(hipGetDeviceProperties(&p, dev));
+    if (name && cap) { snprintf(name, cap, "%s (%s)", p.name, p.gcnArchName); }
+    if (cus) *cus = p.multiProcessorCount;
+    size_t f = 0, t = 0;
+    PROXY_TRY(hipMemGetInfo(&f, &t));
+    if (total) *total = t;
+    if (free_) *free_ = f;
+    int v = 0;
+    PROXY_TRY(hipRuntimeGetVersion(&v));
+    if (ver) *ver = v;
+    return 0;
 }
 
 int proxy_stream_create(void **out) {

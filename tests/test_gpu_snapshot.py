@@ -7,7 +7,6 @@ import tempfile
 
 import numpy as np
 import pytest
-import torch
 
 from oracle import oracle
 from paper_2406_10707_amd import binding as B
@@ -15,7 +14,6 @@ from paper_2406_10707_amd import harness, shards
 from tests import format_reader as fr
 
 pytestmark = pytest.mark.gpu
-DEV = "cuda:0"
 
 
 def _say(msg):
@@ -41,9 +39,9 @@ def test_tiny_shard_file_equals_oracle(config, policy, tmp_path):
     than the shard (streaming flush and back-pressure are on the path)."""
     _say(f"tiny config {config} policy {policy}")
     spec = shards.make_shard(config, tiny=True)
-    shard = harness.DeviceShard(spec, DEV)
+    shard = harness.DeviceShard(spec)
     shard.upload_host_values()
-    stream = torch.cuda.Stream()
+    stream = harness.Stream()
     ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), window_policy=policy, **SMALL))
     ck.register_tensors(shard.descs())
     lay = ck.layout()
@@ -68,9 +66,9 @@ def test_tiny_shard_file_equals_oracle(config, policy, tmp_path):
 def test_sink_modes_write_the_same_file(mode, tmp_path):
     _say(f"sink mode {mode}")
     spec = shards.make_shard(5, tiny=True)
-    shard = harness.DeviceShard(spec, DEV)
+    shard = harness.DeviceShard(spec)
     shard.upload_host_values()
-    stream = torch.cuda.Stream()
+    stream = harness.Stream()
     kw = dict(pwrite=dict(io_mode=B.CKPT_IO_PWRITE), o_direct=dict(o_direct=1, fsync_on_commit=1),
               **{"mmap+fsync": dict(io_mode=B.CKPT_IO_MMAP, fsync_on_commit=1)})[mode]
     ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), n_io_threads=3, n_dma_streams=1, **SMALL, **kw))
@@ -95,9 +93,9 @@ def test_retention_recycles_files_in_place(io_mode, tmp_path):
     as zeros, later spares hold an older iteration's bytes)."""
     _say(f"retention io_mode {io_mode}")
     spec = shards.make_shard(5, tiny=True)
-    shard = harness.DeviceShard(spec, DEV)
+    shard = harness.DeviceShard(spec)
     shard.upload_host_values()
-    stream = torch.cuda.Stream()
+    stream = harness.Stream()
     ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), keep_last=2, prealloc_files=1, io_mode=io_mode, **SMALL))
     ck.register_tensors(shard.descs())
     assert len([f for f in os.listdir(tmp_path) if f.startswith(".spare_")]) == 1
@@ -125,25 +123,24 @@ def test_every_iteration_with_mutation(config, tmp_path):
     iteration i is a device-side clone taken right after update i on the compute stream."""
     _say(f"every-iteration config {config}")
     spec = shards.make_shard(config, tiny=True)
-    shard = harness.DeviceShard(spec, DEV)
+    shard = harness.DeviceShard(spec)
     shard.upload_host_values()
-    gemm = harness.GemmProxy(1024, DEV)
-    stream = torch.cuda.Stream()
+    gemm = harness.GemmProxy(1024)
+    stream = harness.Stream()
     ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), **SMALL))
     ck.register_tensors(shard.descs())
     clones = {}
-    with torch.cuda.stream(stream):
-        for it in range(1, 7):
-            gemm.run(4, stream)                                  # forward/backward stand-in
-            ck.wait_immutable_window_end(stream.cuda_stream)     # before the update
-            shard.update(it, stream)
-            clones[it] = shard.clone_all()
-            ck.snapshot_async(it, stream.cuda_stream)
+    for it in range(1, 7):
+        gemm.run(4, stream)                                  # forward/backward stand-in
+        ck.wait_immutable_window_end(stream.cuda_stream)     # before the update
+        shard.update(it, stream)
+        clones[it] = shard.clone_all(stream)
+        ck.snapshot_async(it, stream.cuda_stream)
     ck.flush()
     stream.synchronize()
     files = {}
     for it in range(1, 7):
-        host = [c.cpu().numpy() for c in clones[it]]
+        host = [c.download() for c in clones[it]]
         assert oracle.compare_file(shard.oracle_tensors(host), it, ck.file_name(it)) is None, f"iteration {it}"
         files[it] = open(ck.file_name(it), "rb").read()
     assert len(set(files.values())) == 6          # the update really changed the state every time
@@ -155,20 +152,20 @@ def test_update_inside_the_window_is_detected(big_dir):
     the state at the boundary. Shows the parity check can see a late copy."""
     _say("negative control")
     spec = shards.make_shard(1)          # 1.7 GB: copies take tens of milliseconds
-    shard = harness.DeviceShard(spec, DEV)
-    stream = torch.cuda.Stream()
+    shard = harness.DeviceShard(spec)
+    stream = harness.Stream()
     shard.fill_device(stream)
+    stream.synchronize()
     ck = B.Checkpointer(B.make_config(out_dir=big_dir, dma_chunk_bytes=16 << 20, pack_superchunk_bytes=64 << 20,
                                       host_ring_bytes=2 << 30))
     ck.register_tensors(shard.descs())
-    with torch.cuda.stream(stream):
-        clones = shard.clone_all()
-        ck.snapshot_async(1, stream.cuda_stream)
-        shard.update(1, stream)                                  # too early, on purpose
-        ck.wait_immutable_window_end(stream.cuda_stream)
+    clones = shard.clone_all(stream)
+    ck.snapshot_async(1, stream.cuda_stream)
+    shard.update(1, stream)                                  # too early, on purpose
+    ck.wait_immutable_window_end(stream.cuda_stream)
     ck.flush(1)
     stream.synchronize()
-    host = [c.cpu().numpy() for c in clones]
+    host = [c.download() for c in clones]
     assert oracle.compare_file(shard.oracle_tensors(host), 1, ck.file_name(1)) is not None
     ck.destroy()
 
@@ -177,9 +174,9 @@ def test_update_inside_the_window_is_detected(big_dir):
 def test_restore_and_resnapshot_round_trip(config, tmp_path):
     _say(f"restore config {config}")
     spec = shards.make_shard(config, tiny=True)
-    shard = harness.DeviceShard(spec, DEV)
+    shard = harness.DeviceShard(spec)
     shard.upload_host_values()
-    stream = torch.cuda.Stream()
+    stream = harness.Stream()
     ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), **SMALL))
     ck.register_tensors(shard.descs())
     ck.snapshot_async(10, stream.cuda_stream)
@@ -196,7 +193,7 @@ def test_restore_and_resnapshot_round_trip(config, tmp_path):
         for t in spec.tensors:
             used[t.buffer][t.offset:t.offset + t.nbytes] = True
         for f, u in zip(shard.flat, used):
-            assert np.all(f.cpu().numpy()[~u] == 0xA5)
+            assert np.all(f.download()[~u] == 0xA5)
     # the oracle's restore agrees (file -> host arrays)
     blank = [np.zeros(t.nbytes, dtype=np.uint8) for t in spec.tensors]
     assert oracle.restore_file(ck.file_name(10), shard.oracle_tensors(blank)) == 10
@@ -212,9 +209,9 @@ def test_restore_and_resnapshot_round_trip(config, tmp_path):
 def test_restore_rejects_bad_files(tmp_path):
     _say("restore errors")
     spec = shards.make_shard(1, tiny=True)
-    shard = harness.DeviceShard(spec, DEV)
+    shard = harness.DeviceShard(spec)
     shard.upload_host_values()
-    stream = torch.cuda.Stream()
+    stream = harness.Stream()
     ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), **SMALL))
     ck.register_tensors(shard.descs())
     ck.snapshot_async(1, stream.cuda_stream)
@@ -238,7 +235,7 @@ def test_restore_rejects_bad_files(tmp_path):
     assert e.value.code == B.CKPT_EIO
     # a file of another registration
     other = shards.make_shard(2, tiny=True)
-    oshard = harness.DeviceShard(other, DEV)
+    oshard = harness.DeviceShard(other)
     oshard.upload_host_values()
     ck2 = B.Checkpointer(B.make_config(out_dir=str(tmp_path / "."), **SMALL))
     ck2.register_tensors(oshard.descs())
@@ -265,9 +262,9 @@ def test_call_order_and_argument_errors(tmp_path):
         B.Checkpointer(B.make_config(out_dir=str(tmp_path), device=99))
     assert e.value.code == B.CKPT_EINVAL
     spec = shards.make_shard(1, tiny=True)
-    shard = harness.DeviceShard(spec, DEV)
+    shard = harness.DeviceShard(spec)
     shard.upload_host_values()
-    stream = torch.cuda.Stream()
+    stream = harness.Stream()
     ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), **SMALL))
     with pytest.raises(B.CkptError) as e:
         ck.snapshot_async(1, stream.cuda_stream)
@@ -300,9 +297,9 @@ def test_io_error_is_latched_and_reported(tmp_path):
     back from ckpt_flush, the context stays usable."""
     _say("io error")
     spec = shards.make_shard(1, tiny=True)
-    shard = harness.DeviceShard(spec, DEV)
+    shard = harness.DeviceShard(spec)
     shard.upload_host_values()
-    stream = torch.cuda.Stream()
+    stream = harness.Stream()
     out = tmp_path / "out"
     out.mkdir()
     ck = B.Checkpointer(B.make_config(out_dir=str(out), **SMALL))
@@ -325,11 +322,11 @@ def test_default_stream_and_default_config(big_dir):
     super-chunks): config 1 at full size, whole file compared by the oracle's streaming comparison."""
     _say("config 1 full size, default config")
     spec = shards.make_shard(1)
-    shard = harness.DeviceShard(spec, DEV)
-    shard.fill_device(torch.cuda.default_stream())
+    shard = harness.DeviceShard(spec)
+    shard.fill_device(harness.NullStream())
     ck = B.Checkpointer(B.make_config(out_dir=big_dir))
     ck.register_tensors(shard.descs())
-    shard.update(1, torch.cuda.default_stream())
+    shard.update(1, harness.NullStream())
     ck.snapshot_async(1, 0)
     ck.wait_immutable_window_end(0, host_block=True)
     host = shard.readback_all()
