@@ -192,13 +192,17 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                 os.unlink(ck.file_name(it))
                 live_files.remove(it)
 
-    # ---- baseline: same steps, checkpointing off
-    marks = []
-    for i in range(2 + args.baseline_steps):
-        iteration(1000000 + i, False, marks)
-    stream.synchronize()
-    base_iter_ms = statistics.median(m[0].elapsed_time(m[2]) for m in marks[2:])
-    base_gemm_ms = statistics.median(m[0].elapsed_time(m[1]) for m in marks[2:])
+    # ---- baseline: same steps, checkpointing off; measured before and after the checkpointed run and
+    # averaged, because GEMM speed drifts by a few per cent with the card's temperature
+    def baseline_phase(n):
+        marks = []
+        for i in range(2 + n):
+            iteration(1000000 + i, False, marks)
+        stream.synchronize()
+        return (statistics.median(m[0].elapsed_time(m[2]) for m in marks[2:]),
+                statistics.median(m[0].elapsed_time(m[1]) for m in marks[2:]))
+
+    base_before = baseline_phase(args.baseline_steps)
 
     # ---- warm-up with checkpointing (untimed)
     step = 0
@@ -232,6 +236,9 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     ck.flush()
     drain_s = time.perf_counter() - t0
     reap(block=True)
+    base_after = baseline_phase(args.baseline_steps)
+    base_iter_ms = 0.5 * (base_before[0] + base_after[0])
+    base_gemm_ms = 0.5 * (base_before[1] + base_after[1])
 
     # snapshots whose copies ran inside the timed region: requested at the end of steps first_timed-1 .. last-1
     in_region = [it for it in requested if first_timed - 1 <= it < step]
@@ -290,7 +297,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                   "stall_pct": round(100.0 * stall_total_ms / (base_iter_ms * len(iter_ms)), 3),
                   "stall_ms_per_snapshot": round(stall_total_ms / max(1, len(stats)), 2),
                   "floor_ms_per_snapshot": round(floor_ms, 2),
-                  "gemm_ms_baseline": round(base_gemm_ms, 3),
+                  "gemm_ms_baseline": round(base_gemm_ms, 3), "baseline_before_after_ms": [round(base_before[0], 2), round(base_after[0], 2)],
                   "gemm_ms_while_copying": round(statistics.median(busy), 3) if busy else None,
                   "gemm_slowdown_pct": round(100.0 * (statistics.median(busy) / base_gemm_ms - 1), 3) if busy else None,
                   "gemm_tflops": round(gemm.flops_per_launch / (gemm_ms_per_launch * 1e-3) / 1e12, 1)},

@@ -2,9 +2,9 @@
 // contiguous, 4 KiB-aligned staging image of the checkpoint's data region. HBM-bound.
 //
 // One wavefront (64 lanes) walks one tile of the descriptor table: up to 32 KiB of destination,
-// 16 bytes per lane per step, 1 KiB per wavefront step, 16 steps (aligned source) or 8 (misaligned
-// source, which needs two registers sets) in flight; a sweep of tile sizes, unroll depths and block
-// sizes on MI355X put this shape at the top for a plain copy. The staging side is
+// 16 bytes per lane per step, 1 KiB per wavefront step, 8 steps in flight (which keeps the kernel at
+// 64 VGPRs, 8 wavefronts per SIMD); sweeps of tile size, unroll depth and block size on MI355X put
+// this shape at the top for the table-driven kernel (a plain copy without a table is about 5% faster). The staging side is
 // always 16-byte aligned. The tensor side is aligned to its element size only; when it is not
 // 16-byte aligned each lane reads the two aligned 16-byte words that cover its bytes and
 // byte-shifts them together (v_alignbyte), so every global access is an aligned 128-bit one. An
@@ -19,10 +19,20 @@ namespace dsllm {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kWavesPerBlock = 4;
+// tuning constants (overridable at compile time for sweeps)
+#ifndef DSLLM_PACK_WAVES_PER_BLOCK
+#define DSLLM_PACK_WAVES_PER_BLOCK 4
+#endif
+#ifndef DSLLM_PACK_UNROLL
+#define DSLLM_PACK_UNROLL 8
+#endif
+#ifndef DSLLM_PACK_UNROLL_SHIFT
+#define DSLLM_PACK_UNROLL_SHIFT 8
+#endif
+constexpr int kWavesPerBlock = DSLLM_PACK_WAVES_PER_BLOCK;
 constexpr int kBlock = 64 * kWavesPerBlock;
-constexpr int kUnroll = 16;        // aligned path: 16 x 16 bytes per lane in flight
-constexpr int kUnrollShift = 8;    // misaligned path: 8 pairs of 16-byte words per lane in flight
+constexpr int kUnroll = DSLLM_PACK_UNROLL;             // aligned path: 16-byte words per lane in flight
+constexpr int kUnrollShift = DSLLM_PACK_UNROLL_SHIFT;  // misaligned path: pairs of 16-byte words per lane in flight
 
 __device__ __forceinline__ u32x4 ld16(const u32x4 *p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ void st16(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
