@@ -115,6 +115,18 @@ def cpu_baseline(harness, shard, sample_bytes, out_dir):
                       % (len(ks), total / 1e9, dt, os.cpu_count())}
 
 
+def traffic_ratio():
+    """HBM traffic of the pack kernel over its algorithmic bytes, as measured with rocprofv3 counters
+    (profiles/pack_kernel_hbm_traffic_gpt2small.txt); None when the summary is not there."""
+    try:
+        for line in open(os.path.join(ROOT, "profiles", "pack_kernel_hbm_traffic_gpt2small.txt")):
+            if line.strip().startswith("traffic_over_algorithmic:"):
+                return float(line.split(":")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -236,6 +248,22 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     ck.flush()
     drain_s = time.perf_counter() - t0
     reap(block=True)
+    restore_result = None
+    if not args.no_restore and requested:
+        last = requested[-1]
+        shard_probe = [0, len(shard.ptrs) // 2, len(shard.ptrs) - 1]
+        want = {k: shard.readback(k) for k in shard_probe}
+        for k in shard_probe:
+            B.proxy_device_fill_async(shard.ptrs[k], 0xA5, shard.spec.tensors[k].nbytes, stream.handle)
+        harness.synchronize()
+        t0 = time.perf_counter()
+        ck.restore(ck.file_name(last), stream.cuda_stream)
+        stream.synchronize()
+        dt = time.perf_counter() - t0
+        # the newest file is the state after the last step only if that step took a snapshot
+        ok = all((shard.readback(k) == want[k]).all() for k in shard_probe) if last == step else None
+        restore_result = {"gbps": round(lay["data_bytes"] / dt / 1e9, 2), "seconds": round(dt, 2), "probe_tensors_bit_exact": ok if ok is None else bool(ok)}
+
     base_after = baseline_phase(args.baseline_steps)
     base_iter_ms = 0.5 * (base_before[0] + base_after[0])
     base_gemm_ms = 0.5 * (base_before[1] + base_after[1])
@@ -279,7 +307,8 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                    "hip_runtime": info["hip_runtime_version"], "io_mode": args.io_mode, "keep_last": args.keep_last, "prealloc_files": args.prealloc, "sink": out_dir.rsplit("/", 1)[0]},
         "roofline": {"bound": "hbm", "kernel": "pack_kernel", "achieved": round(pack_gbps, 1) if pack_gbps else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(pack_gbps / HBM_PEAK_GBPS, 4) if pack_gbps else None,
-                     "traffic": None, "launches": pack_launches,
+                     "traffic": None, "traffic_source": "rocprofv3 FETCH_SIZE+WRITE_SIZE ratio from profiles/ x algorithmic bytes per launch",
+                     "launches": pack_launches,
                      "avg_launch_ms": round(pack_ms / pack_launches, 4) if pack_launches else None,
                      "bytes_per_launch": round(pack_bytes_per_snapshot / (pack_launches / max(1, len(stats)))) if pack_launches else None,
                      "devcopy_ceiling_gbps": round(devcopy_gbps, 1)},
@@ -308,21 +337,11 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
             json.dump({"first_timed_step": first_timed, "iter_ms": iter_ms, "gemm_ms": gemm_ms, "requested": requested,
                        "snapshots": all_stats, "baseline_iter_ms": base_iter_ms, "baseline_gemm_ms": base_gemm_ms}, f, indent=1)
 
-    if not args.no_restore and requested:
-        last = requested[-1]
-        shard_probe = [0, len(shard.ptrs) // 2, len(shard.ptrs) - 1]
-        want = {k: shard.readback(k) for k in shard_probe}
-        for k in shard_probe:
-            B.proxy_device_fill_async(shard.ptrs[k], 0xA5, shard.spec.tensors[k].nbytes, stream.handle)
-        harness.synchronize()
-        t0 = time.perf_counter()
-        ck.restore(ck.file_name(last), stream.cuda_stream)
-        stream.synchronize()
-        dt = time.perf_counter() - t0
-        # the newest file is the state after the last step only if that step took a snapshot
-        ok = all((shard.readback(k) == want[k]).all() for k in shard_probe) if last == step else None
-        result["restore"] = {"gbps": round(S / dt / 1e9, 2), "seconds": round(dt, 2), "probe_tensors_bit_exact": ok if ok is None else bool(ok)}
-
+    ratio = traffic_ratio()
+    if ratio and pack_launches:
+        result["roofline"]["traffic"] = round(ratio * result["roofline"]["bytes_per_launch"])
+    if restore_result:
+        result["restore"] = restore_result
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(harness, shard, int(args.oracle_sample_gb * 1e9), out_dir)
     ck.destroy()
