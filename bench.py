@@ -53,6 +53,8 @@ def parse_args():
     ap.add_argument("--oracle-sample-gb", type=float, default=8.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-restore", action="store_true")
+    ap.add_argument("--variant-steps", type=int, default=20,
+                    help="extra steps measured under window policy PACK with full device staging (0: skip)")
     ap.add_argument("--dump", default="", help="write per-step timings and per-snapshot measurements to this JSON file")
     return ap.parse_args()
 
@@ -160,13 +162,26 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     launches, gemm_ms_per_launch = gemm.calibrate(compute_ms, stream)
 
     policy = B.CKPT_WINDOW_PACK if args.policy == "pack" else B.CKPT_WINDOW_D2H
-    chunk = args.chunk_mib << 20
-    # the paper pre-allocates a host cache large enough for the shard; capped so that cache + one file fit the box
-    ring_bytes = int(args.ring_gib * (1 << 30)) or min(16 << 30, -(-(spec.payload_bytes + 4096 * len(spec.tensors)) // chunk) * chunk)
+    chunk, sc = args.chunk_mib << 20, args.superchunk_mib << 20
+    data_upper = spec.payload_bytes + 4096 * len(spec.tensors)
+    # with SDMA copies the ring size does not limit the copy rate; a quarter of the paper's 64 GB host cache is plenty
+    ring_bytes = int(args.ring_gib * (1 << 30)) or min(16 << 30, -(-data_upper // chunk) * chunk)
     args.ring_gib = round(ring_bytes / (1 << 30), 2)
-    cfg = B.make_config(out_dir=out_dir, host_ring_bytes=ring_bytes, dma_chunk_bytes=args.chunk_mib << 20,
-                        pack_superchunk_bytes=args.superchunk_mib << 20, dev_staging_bytes=int(args.staging_gib * (1 << 30)),
-                        n_dma_streams=args.dma_streams, n_io_threads=args.io_threads, window_policy=policy,
+    # the variant (update released after the pack, copies drain from device staging) needs staging for the whole
+    # data region; under the paper's rule the staging size is not on the critical path
+    want_variant = args.variant_steps > 0 and args.policy == "d2h"
+    staging_bytes = int(args.staging_gib * (1 << 30))
+    if want_variant and not staging_bytes:
+        full = -(-data_upper // sc) * sc
+        free = info["free_mem"] - spec.payload_bytes - (8 << 30)
+        if full <= free:
+            staging_bytes = full
+        else:
+            want_variant = False
+    staging_gib = round((staging_bytes or 2 * sc) / (1 << 30), 2)
+    cfg = B.make_config(out_dir=out_dir, host_ring_bytes=ring_bytes, dma_chunk_bytes=chunk, pack_superchunk_bytes=sc,
+                        dev_staging_bytes=staging_bytes, n_dma_streams=args.dma_streams, n_io_threads=args.io_threads,
+                        window_policy=policy,
                         io_mode={"auto": B.CKPT_IO_AUTO, "pwrite": B.CKPT_IO_PWRITE, "mmap": B.CKPT_IO_MMAP}[args.io_mode],
                         keep_last=args.keep_last, prealloc_files=args.prealloc if args.keep_last else 0)
     t0 = time.perf_counter()
@@ -174,6 +189,9 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     ck.register_tensors(shard.descs())
     init_s = time.perf_counter() - t0
     lay = ck.layout()
+    S = lay["data_bytes"]
+    requested, live_files = [], []
+    state = {"step": 0}
 
     def iteration(step, with_ckpt, marks):
         """One step on `stream`; marks gets (start, after-gemm, end) events."""
@@ -187,10 +205,9 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         if with_ckpt and step % every == 0:
             ck.snapshot_async(step, stream.cuda_stream)
             requested.append(step)
+            live_files.append(step)
         e[2].record(stream)
         marks.append(e)
-
-    requested, live_files = [], []
 
     def reap(block=False):
         """Unlink committed checkpoint files except the newest (the sink may be tmpfs, i.e. host memory).
@@ -204,82 +221,111 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                 os.unlink(ck.file_name(it))
                 live_files.remove(it)
 
-    # ---- baseline: same steps, checkpointing off; measured before and after the checkpointed run and
-    # averaged, because GEMM speed drifts by a few per cent with the card's temperature
     def baseline_phase(n):
+        """Same steps with checkpointing off: (median step ms, median GEMM-phase ms). After an idle period
+        the card runs a few per cent faster for some seconds, so the first ~4 s of steps are discarded."""
         marks = []
-        for i in range(2 + n):
+        skip = max(2, int(4000.0 / max(compute_ms, 1.0)) + 1)
+        skip = min(skip, 40)
+        for i in range(skip + n):
             iteration(1000000 + i, False, marks)
         stream.synchronize()
-        return (statistics.median(m[0].elapsed_time(m[2]) for m in marks[2:]),
-                statistics.median(m[0].elapsed_time(m[1]) for m in marks[2:]))
+        return (statistics.median(m[0].elapsed_time(m[2]) for m in marks[skip:]),
+                statistics.median(m[0].elapsed_time(m[1]) for m in marks[skip:]))
 
+    def region(n_steps):
+        """n_steps checkpointed steps bracketed by full synchronisation; returns timings and wall seconds."""
+        marks = []
+        first = state["step"] + 1
+        harness.synchronize()
+        t_start = time.perf_counter()
+        for _ in range(n_steps):
+            state["step"] += 1
+            iteration(state["step"], True, marks)
+            reap()
+        harness.synchronize()
+        wall = time.perf_counter() - t_start
+        return {"first": first, "last": state["step"], "wall_s": wall,
+                "iter_ms": [m[0].elapsed_time(m[2]) for m in marks], "gemm_ms": [m[0].elapsed_time(m[1]) for m in marks]}
+
+    def gbps(nbytes, ms):
+        return nbytes / (ms * 1e-3) / 1e9 if ms and ms > 0 else None
+
+    def stall_report(reg, base_iter_ms, base_gemm_ms):
+        """Stall of a region. Reference step time: the quiet steps of the same region (4 or more steps after
+        the latest snapshot request) when there are at least three, measured under identical conditions;
+        otherwise the no-checkpoint baseline phases. GEMM slowdown: steps overlapping copies vs the same reference."""
+        in_reg = [it for it in requested if reg["first"] - 1 <= it < reg["last"]]
+        busy, quiet, quiet_iter = [], [], []
+        for i, g in enumerate(reg["gemm_ms"]):
+            since = min([reg["first"] + i - it for it in requested if it < reg["first"] + i] or [99])
+            if since <= 2:
+                busy.append(g)
+            elif since >= 4:
+                quiet.append(g)
+                quiet_iter.append(reg["iter_ms"][i])
+        use_quiet = len(quiet) >= 3
+        ref_iter = statistics.median(quiet_iter) if use_quiet else base_iter_ms
+        ref_gemm = statistics.median(quiet) if use_quiet else base_gemm_ms
+        total = sum(reg["iter_ms"]) - ref_iter * len(reg["iter_ms"])
+        return in_reg, {
+            "reference": "quiet steps of the same region" if use_quiet else "no-checkpoint baseline phases (before and after, averaged)",
+            "reference_ms_per_step": round(ref_iter, 3), "ms_per_step": round(statistics.mean(reg["iter_ms"]), 3),
+            "stall_ms_per_step": round(total / len(reg["iter_ms"]), 3),
+            "stall_pct": round(100.0 * total / (ref_iter * len(reg["iter_ms"])), 3),
+            "stall_ms_per_snapshot": round(total / max(1, len(in_reg)), 2),
+            "baseline_phase_ms_per_step": round(base_iter_ms, 3),
+            "gemm_ms_reference": round(ref_gemm, 3),
+            "gemm_ms_while_copying": round(statistics.median(busy), 3) if busy else None,
+            "gemm_slowdown_pct": round(100.0 * (statistics.median(busy) / ref_gemm - 1), 3) if busy else None}, ref_gemm
+
+    # ---- baseline before; warm-up (untimed); the timed region of exactly K steps
     base_before = baseline_phase(args.baseline_steps)
-
-    # ---- warm-up with checkpointing (untimed)
-    step = 0
-    wmarks = []
-    for _ in range(args.warmup):
-        step += 1
-        n_before = len(requested)
-        iteration(step, True, wmarks)
-        if len(requested) > n_before:
-            live_files.append(requested[-1])
-        reap()
-    harness.synchronize()
-    first_timed = step + 1
-
-    # ---- timed region: exactly K steps
-    marks = []
-    t_start = time.perf_counter()
-    for _ in range(args.steps):
-        step += 1
-        n_before = len(requested)
-        iteration(step, True, marks)
-        if len(requested) > n_before:
-            live_files.append(requested[-1])
-        reap()
-    harness.synchronize()
-    elapsed = time.perf_counter() - t_start
-    ms_per_step = elapsed * 1e3 / args.steps
+    region(args.warmup)
+    main = region(args.steps)
+    ms_per_step = main["wall_s"] * 1e3 / args.steps
 
     # ---- drain (the paper counts pending flushes in end-to-end time; reported, not part of the K steps)
     t0 = time.perf_counter()
     ck.flush()
     drain_s = time.perf_counter() - t0
     reap(block=True)
+
+    # ---- restore of the newest file (its state is the device state only if the last step took a snapshot)
     restore_result = None
     if not args.no_restore and requested:
         last = requested[-1]
-        shard_probe = [0, len(shard.ptrs) // 2, len(shard.ptrs) - 1]
-        want = {k: shard.readback(k) for k in shard_probe}
-        for k in shard_probe:
+        probe = [0, len(shard.ptrs) // 2, len(shard.ptrs) - 1]
+        want = {k: shard.readback(k) for k in probe}
+        for k in probe:
             B.proxy_device_fill_async(shard.ptrs[k], 0xA5, shard.spec.tensors[k].nbytes, stream.handle)
         harness.synchronize()
         t0 = time.perf_counter()
         ck.restore(ck.file_name(last), stream.cuda_stream)
         stream.synchronize()
         dt = time.perf_counter() - t0
-        # the newest file is the state after the last step only if that step took a snapshot
-        ok = all((shard.readback(k) == want[k]).all() for k in shard_probe) if last == step else None
-        restore_result = {"gbps": round(lay["data_bytes"] / dt / 1e9, 2), "seconds": round(dt, 2), "probe_tensors_bit_exact": ok if ok is None else bool(ok)}
+        ok = all((shard.readback(k) == want[k]).all() for k in probe) if last == state["step"] else None
+        restore_result = {"gbps": round(S / dt / 1e9, 2), "seconds": round(dt, 2), "probe_tensors_bit_exact": ok if ok is None else bool(ok)}
 
+    # ---- variant: window released after the pack (policy PACK, staging holds the whole data region)
+    variant = None
+    if want_variant:
+        ck.set_window_policy(B.CKPT_WINDOW_PACK)
+        if state["step"] % every:                        # start the variant right after a multiple of the interval
+            region(every - state["step"] % every)
+            ck.flush()
+        variant = region(args.variant_steps)
+        ck.flush()
+        ck.set_window_policy(B.CKPT_WINDOW_D2H)
+
+    # ---- baseline after; GEMM speed drifts a few per cent with temperature, so before and after are averaged
     base_after = baseline_phase(args.baseline_steps)
     base_iter_ms = 0.5 * (base_before[0] + base_after[0])
     base_gemm_ms = 0.5 * (base_before[1] + base_after[1])
 
-    # snapshots whose copies ran inside the timed region: requested at the end of steps first_timed-1 .. last-1
-    in_region = [it for it in requested if first_timed - 1 <= it < step]
+    in_region, stall, ref_gemm_ms = stall_report(main, base_iter_ms, base_gemm_ms)
     stats = [ck.stats(it) for it in in_region]
     all_stats = [ck.stats(it) for it in requested]
-    iter_ms = [m[0].elapsed_time(m[2]) for m in marks]
-    gemm_ms = [m[0].elapsed_time(m[1]) for m in marks]
-    stall_total_ms = sum(iter_ms) - base_iter_ms * len(iter_ms)
-    S = lay["data_bytes"]
-
-    def gbps(nbytes, ms):
-        return nbytes / (ms * 1e-3) / 1e9 if ms and ms > 0 else None
-
     snap_gbps = gbps(S * len(stats), sum(s["request_to_d2h_end_ms"] for s in stats)) if stats else None
     link_gbps = gbps(S * len(stats), sum(s["d2h_span_ms"] for s in stats)) if stats else None
     pack_launches = sum(s["pack_launches"] for s in stats)
@@ -287,9 +333,10 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     # algorithmic bytes of the pack kernel: every payload byte read once, every data-region byte written once
     pack_bytes_per_snapshot = lay["payload_bytes"] + lay["data_bytes"]
     pack_gbps = gbps(pack_bytes_per_snapshot * len(stats), pack_ms) if stats else None
-    # D2H busy steps: the GEMM phases that overlapped copies
-    busy = [g for i, g in enumerate(gemm_ms) if any(0 < (first_timed + i) - it <= 2 for it in requested)]
-    floor_ms = max(0.0, S / (link["d2h"] * 1e9) * 1e3 - base_gemm_ms)
+    # physical floor under the paper's rule: the copies cannot end before D / B_link, the window is the GEMM phase
+    stall["floor_ms_per_snapshot"] = round(max(0.0, S / (link["d2h"] * 1e9) * 1e3 - ref_gemm_ms), 2)
+    stall["baseline_before_after_ms"] = [round(base_before[0], 2), round(base_after[0], 2)]
+    stall["gemm_tflops"] = round(gemm.flops_per_launch / (gemm_ms_per_launch * 1e-3) / 1e12, 1)
 
     result = {
         "metric": "snapshot GB/s per GPU (fraction of host-link peak) + training stall ms/iter",
@@ -302,9 +349,10 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         "config": {"workload": spec.name, "payload_bytes": lay["payload_bytes"], "n_tensors": lay["n_tensors"],
                    "ckpt_every": every, "compute_ms": compute_ms, "window_policy": args.policy,
                    "ring_gib": args.ring_gib, "dma_chunk_mib": args.chunk_mib, "pack_superchunk_mib": args.superchunk_mib,
-                   "staging_gib": args.staging_gib or 2 * args.superchunk_mib / 1024, "dma_streams": args.dma_streams,
-                   "io_threads": args.io_threads, "hw_queues": int(os.environ["GPU_MAX_HW_QUEUES"]), "device": info["name"],
-                   "hip_runtime": info["hip_runtime_version"], "io_mode": args.io_mode, "keep_last": args.keep_last, "prealloc_files": args.prealloc, "sink": out_dir.rsplit("/", 1)[0]},
+                   "staging_gib": staging_gib, "dma_streams": args.dma_streams, "io_threads": args.io_threads,
+                   "hw_queues": int(os.environ["GPU_MAX_HW_QUEUES"]), "device": info["name"],
+                   "hip_runtime": info["hip_runtime_version"], "io_mode": args.io_mode, "keep_last": args.keep_last,
+                   "prealloc_files": args.prealloc, "sink": out_dir.rsplit("/", 1)[0]},
         "roofline": {"bound": "hbm", "kernel": "pack_kernel", "achieved": round(pack_gbps, 1) if pack_gbps else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(pack_gbps / HBM_PEAK_GBPS, 4) if pack_gbps else None,
                      "traffic": None, "traffic_source": "rocprofv3 FETCH_SIZE+WRITE_SIZE ratio from profiles/ x algorithmic bytes per launch",
@@ -318,24 +366,25 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                      "d2h_frac_of_link_peak": round(link_gbps / link["d2h"], 4) if link_gbps else None,
                      "snapshot_gbps_frac_of_link_peak": round(snap_gbps / link["d2h"], 4) if snap_gbps else None,
                      "host_snapshot_call_ms": round(max(s["host_snapshot_call_ms"] for s in all_stats), 3) if all_stats else None,
-                     "host_backpressure_ms": round(max(s["host_backpressure_ms"] for s in all_stats), 1) if all_stats else None,
                      "flush_gbps": round(statistics.median(S / (s["host_flush_span_ms"] * 1e-3) / 1e9 for s in all_stats), 2) if all_stats else None,
                      "drain_s": round(drain_s, 2), "init_s": round(init_s, 2)},
-        "stall": {"baseline_ms_per_step": round(base_iter_ms, 3), "ms_per_step": round(statistics.mean(iter_ms), 3),
-                  "stall_ms_per_step": round(stall_total_ms / len(iter_ms), 3),
-                  "stall_pct": round(100.0 * stall_total_ms / (base_iter_ms * len(iter_ms)), 3),
-                  "stall_ms_per_snapshot": round(stall_total_ms / max(1, len(stats)), 2),
-                  "floor_ms_per_snapshot": round(floor_ms, 2),
-                  "gemm_ms_baseline": round(base_gemm_ms, 3), "baseline_before_after_ms": [round(base_before[0], 2), round(base_after[0], 2)],
-                  "gemm_ms_while_copying": round(statistics.median(busy), 3) if busy else None,
-                  "gemm_slowdown_pct": round(100.0 * (statistics.median(busy) / base_gemm_ms - 1), 3) if busy else None,
-                  "gemm_tflops": round(gemm.flops_per_launch / (gemm_ms_per_launch * 1e-3) / 1e12, 1)},
+        "stall": stall,
     }
+    if variant:
+        v_in, v_stall, _ = stall_report(variant, base_iter_ms, base_gemm_ms)
+        v_stats = [ck.stats(it) for it in v_in]
+        v_stall["steps"] = len(variant["iter_ms"])
+        v_stall["snapshots"] = len(v_in)
+        v_stall["request_to_pack_end_ms"] = round(statistics.mean(s["request_to_pack_end_ms"] for s in v_stats), 2) if v_stats else None
+        v_stall["snapshot_gbps"] = round(gbps(S * len(v_stats), sum(s["request_to_d2h_end_ms"] for s in v_stats)), 2) if v_stats else None
+        v_stall["note"] = ("window policy PACK: the update waits for the pack kernels only; copies drain from device staging "
+                           "that holds the whole data region (MI355X variant, not the paper's rule)")
+        result["variant_pack_policy"] = v_stall
 
     if args.dump:
         with open(args.dump, "w") as f:
-            json.dump({"first_timed_step": first_timed, "iter_ms": iter_ms, "gemm_ms": gemm_ms, "requested": requested,
-                       "snapshots": all_stats, "baseline_iter_ms": base_iter_ms, "baseline_gemm_ms": base_gemm_ms}, f, indent=1)
+            json.dump({"main": main, "variant": variant, "requested": requested, "snapshots": all_stats,
+                       "baseline_iter_ms": base_iter_ms, "baseline_gemm_ms": base_gemm_ms}, f, indent=1)
 
     ratio = traffic_ratio()
     if ratio and pack_launches:

@@ -181,6 +181,10 @@ int ckpt_snapshot_async(ckpt_ctx *ctx, uint64_t iter, void *hip_stream_compute);
  * snapshot. Does not wait for file writes: those may overlap the update. */
 int ckpt_wait_immutable_window_end(ckpt_ctx *ctx, void *hip_stream_compute, int32_t host_block);
 
+/* Changes the window policy (ckpt_window_policy) for later snapshots. CKPT_ESTATE while a
+ * snapshot's window is open. */
+int ckpt_set_window_policy(ckpt_ctx *ctx, int32_t policy);
+
 /* Blocks until the file of `iter` (or of every requested snapshot, CKPT_ITER_ALL) is written,
  * optionally fsync'ed, and renamed to its final name. Returns the latched asynchronous error, if
  * any, and clears it. CKPT_EINVAL if `iter` was never requested. */

@@ -80,6 +80,7 @@ _SIGS = {
     "ckpt_register_tensors": (C.c_int, [_vp, C.POINTER(ckpt_tensor_desc), C.c_size_t]),
     "ckpt_snapshot_async": (C.c_int, [_vp, _u64, _vp]),
     "ckpt_wait_immutable_window_end": (C.c_int, [_vp, _vp, _i32]),
+    "ckpt_set_window_policy": (C.c_int, [_vp, _i32]),
     "ckpt_flush": (C.c_int, [_vp, _u64]),
     "ckpt_restore": (C.c_int, [_vp, C.c_char_p, _vp, C.POINTER(_u64)]),
     "ckpt_get_layout": (C.c_int, [_vp, C.POINTER(ckpt_layout)]),
@@ -230,6 +231,9 @@ class Checkpointer:
 
     def wait_immutable_window_end(self, stream, host_block=False):
         _check(lib.ckpt_wait_immutable_window_end(self._h, stream, 1 if host_block else 0))
+
+    def set_window_policy(self, policy):
+        _check(lib.ckpt_set_window_policy(self._h, policy))
 
     def flush(self, it=CKPT_ITER_ALL):
         _check(lib.ckpt_flush(self._h, it))

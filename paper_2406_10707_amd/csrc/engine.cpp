@@ -74,7 +74,7 @@ struct Snap {
     std::string tmp_path, final_path;
     std::atomic<uint64_t> chunks_left{0};
     hipEvent_t ev_boundary = nullptr;
-    bool submitted = false, d2h_done = false, committed = false, window_closed = false;
+    bool submitted = false, packs_submitted = false, d2h_done = false, committed = false, window_closed = false;
     Clock::time_point t_request, t_submitted, t_committed, t_first_chunk;
     bool have_first_chunk = false;
     double call_ms = 0, backpressure_ms = 0;
@@ -397,16 +397,29 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
 
     if ((e = hipStreamWaitEvent(c->pack_stream, s->ev_boundary, 0)) != hipSuccess) hip_fail("wait boundary", e);
     double bp_ms = 0;
-    for (uint64_t sc = 0; sc < p.n_superchunks; sc++) {
+    // Pack launches run ahead of the copies as far as staging allows: the first n_stage super-chunks are
+    // packed right away (they depend on nothing but the boundary), super-chunk sc + n_stage as soon as the
+    // copies of sc, whose staging slot it reuses, are enqueued. The copies below may block this thread on
+    // ring back-pressure; the packs must not queue up behind that.
+    auto enqueue_pack = [&](uint64_t sc) {
         const uint64_t stage = sc % c->n_stage;
-        uint8_t *stage_base = c->staging + stage * SC;
         if (sc >= c->n_stage)
             for (size_t k = 0; k < nk; k++)
                 if ((e = hipStreamWaitEvent(c->pack_stream, c->ev_stage_done[stage][k], 0)) != hipSuccess) hip_fail("wait stage", e);
         if ((e = hipEventRecord(c->ev_pack_start[sc], c->pack_stream)) != hipSuccess) hip_fail("record", e);
         const uint64_t t0 = p.sc_first_tile[sc], t1 = p.sc_first_tile[sc + 1];
-        if ((e = launch_pack(c->dev_tiles + t0, t1 - t0, stage_base, sc * SC, c->pack_stream)) != hipSuccess) hip_fail("pack launch", e);
+        if ((e = launch_pack(c->dev_tiles + t0, t1 - t0, c->staging + stage * SC, sc * SC, c->pack_stream)) != hipSuccess) hip_fail("pack launch", e);
         if ((e = hipEventRecord(c->ev_packed[sc], c->pack_stream)) != hipSuccess) hip_fail("record", e);
+        if (sc + 1 == p.n_superchunks) {   // every read of the tensors is now in the pack stream
+            std::lock_guard<std::mutex> lk(c->mu);
+            s->packs_submitted = true;
+            c->cv_state.notify_all();
+        }
+    };
+    for (uint64_t sc = 0; sc < std::min<uint64_t>(c->n_stage, p.n_superchunks); sc++) enqueue_pack(sc);
+    for (uint64_t sc = 0; sc < p.n_superchunks; sc++) {
+        const uint64_t stage = sc % c->n_stage;
+        uint8_t *stage_base = c->staging + stage * SC;
         for (size_t k = 0; k < nk; k++)
             if ((e = hipStreamWaitEvent(c->dma[k], c->ev_packed[sc], 0)) != hipSuccess) hip_fail("wait packed", e);
 
@@ -449,6 +462,7 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
             }
             c->cv_io.notify_one();
         }
+        if (sc + c->n_stage < p.n_superchunks) enqueue_pack(sc + c->n_stage);
     }
     std::lock_guard<std::mutex> lk(c->mu);
     s->backpressure_ms = bp_ms;
@@ -769,9 +783,10 @@ int ckpt_wait_immutable_window_end(ckpt_ctx *c, void *stream, int32_t host_block
         std::unique_lock<std::mutex> lk(c->mu);
         sp = c->last_snap;
         if (!sp || sp->window_closed) return CKPT_OK;
-        // every copy of the pending snapshot must have been enqueued before a device-side wait on its
-        // last event means anything
-        c->cv_state.wait(lk, [&] { return sp->submitted; });
+        // a device-side wait means something only for events that have been recorded: every copy of the
+        // pending snapshot must have been enqueued (policy D2H), or every pack launch (policy PACK)
+        const bool pack_only = c->cfg.window_policy == CKPT_WINDOW_PACK;
+        c->cv_state.wait(lk, [&] { return sp->submitted || (pack_only && sp->packs_submitted); });
     }
     HIP_TRY(c, hipSetDevice(c->device));
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -786,6 +801,15 @@ int ckpt_wait_immutable_window_end(ckpt_ctx *c, void *stream, int32_t host_block
     }
     std::lock_guard<std::mutex> lk(c->mu);
     sp->window_closed = true;
+    return CKPT_OK;
+}
+
+int ckpt_set_window_policy(ckpt_ctx *c, int32_t policy) {
+    if (!c) return fail(CKPT_EINVAL, "null context");
+    if (policy != CKPT_WINDOW_D2H && policy != CKPT_WINDOW_PACK) return fail(CKPT_EINVAL, "unknown window_policy");
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (c->last_snap && !c->last_snap->window_closed) return fail(CKPT_ESTATE, "a snapshot's window is still open");
+    c->cfg.window_policy = policy;
     return CKPT_OK;
 }
 

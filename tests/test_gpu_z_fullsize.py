@@ -1,0 +1,122 @@
+"""Full-size parity: workloads 2-5 at their real sizes (94 / 91 / 61 / 40 GB) in the launch
+configuration bench.py times (64 MiB chunks, 1 GiB super-chunks, 16 GiB ring, 12 I/O threads, tmpfs
+sink). The oracle cannot serialize 94 GB in seconds, so the file is checked on what it can compute
+one by one: the whole header, and for a seeded sample of tensors (plus first, last, smallest,
+largest) the exact bytes at the oracle's offset and the zero padding after them; then the same sample
+after a restore into poisoned memory."""
+import os
+import shutil
+import tempfile
+
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2406_10707_amd import binding as B
+from paper_2406_10707_amd import harness, shards
+
+pytestmark = pytest.mark.gpu
+
+PAYLOAD = {2: 94_337_818_624, 3: 91_113_953_280, 4: 60_816_752_640}
+
+
+def _sample(spec, n=40):
+    rng = np.random.default_rng(spec.seed)
+    sizes = [t.nbytes for t in spec.tensors]
+    ks = {0, len(sizes) - 1, int(np.argmin(sizes)), int(np.argmax(sizes))}
+    ks.update(int(k) for k in rng.choice(len(sizes), size=min(n, len(sizes)), replace=False))
+    return sorted(ks)
+
+
+def _offsets(spec):
+    """Oracle offsets without the quadratic walk: header size from the oracle, then its recurrence
+    checked against the oracle's own per-tensor answer on the sampled indices."""
+    ots = [(t.name, t.dtype, t.shape, None) for t in spec.tensors]
+    hb = oracle.header_bytes(ots)
+    off, out = hb, []
+    for t in spec.tensors:
+        out.append(off)
+        off += -(-t.nbytes // 4096) * 4096
+    return ots, hb, out, off
+
+
+@pytest.mark.parametrize("config", [2, 3, 4, 5])
+def test_full_size_snapshot_and_restore(config):
+    print(f"full size workload {config}", flush=True)
+    spec = shards.make_shard(config)
+    base = "/dev/shm" if os.path.isdir("/dev/shm") else None
+    d = tempfile.mkdtemp(prefix="dsllm_full_", dir=base)
+    shard = harness.DeviceShard(spec)
+    ck = None
+    try:
+        stream = harness.Stream()
+        shard.fill_device(stream)
+        shard.update(1, stream)
+        ck = B.Checkpointer(B.make_config(out_dir=d, host_ring_bytes=16 << 30, dma_chunk_bytes=64 << 20,
+                                          pack_superchunk_bytes=1 << 30, n_dma_streams=2, n_io_threads=12, keep_last=1))
+        ck.register_tensors(shard.descs())
+        ots, hb, offs, fb = _offsets(spec)
+        ks = _sample(spec)
+        # oracle input: device-side clones of the sampled tensors, ordered on the stream between update 1
+        # and update 2 (the boundary the snapshot captures), downloaded later with blocking copies
+        clones = {}
+        for k in ks:
+            clones[k] = harness.DevBuf(spec.tensors[k].nbytes)
+            B.proxy_copy_d2d_async(clones[k].ptr, shard.ptrs[k], spec.tensors[k].nbytes, stream.handle)
+        ck.snapshot_async(1, stream.cuda_stream)
+        ck.wait_immutable_window_end(stream.cuda_stream)
+        shard.update(2, stream)                       # the update right behind the window must not leak into file 1
+        print("  snapshot requested", flush=True)
+        ck.flush(1)
+        st = ck.stats(1)
+        print(f"  flushed: d2h {st['data_bytes'] / st['d2h_span_ms'] / 1e6:.1f} GB/s", flush=True)
+        path = ck.file_name(1)
+        prefix = min(len(ots), 600)                   # the oracle's own offset walk on a prefix pins the recurrence used above
+        delta = hb - oracle.header_bytes(ots[:prefix])
+        assert [o + delta for o in oracle.tensor_offsets(ots[:prefix])] == offs[:prefix]
+        assert os.path.getsize(path) == fb == ck.layout()["file_bytes"]
+        if config in PAYLOAD:
+            assert spec.payload_bytes == PAYLOAD[config]
+        with open(path, "rb") as f:
+            assert f.read(hb) == oracle.build_header(ots, 1)
+        stream.synchronize()
+        host = {k: clones[k].download() for k in ks}
+        for k in ks:
+            t = spec.tensors[k]
+            padded = -(-t.nbytes // 4096) * 4096
+            blob = np.fromfile(path, dtype=np.uint8, count=padded, offset=offs[k])
+            want = oracle.serialize_bytes([(t.name, t.dtype, t.shape, host[k])], 1)      # the oracle on this one tensor
+            ohb = oracle.header_bytes([(t.name, t.dtype, t.shape, None)])
+            assert blob.tobytes() == want[ohb:], t.name
+            assert not np.array_equal(shard.readback(k), host[k]) or t.nbytes < 64         # update 2 did change the device state
+        # restore file 1 into poisoned memory: the device state is again the one at the boundary
+        for k in ks:
+            B.proxy_device_fill_async(shard.ptrs[k], 0xA5, spec.tensors[k].nbytes, stream.handle)
+        assert ck.restore(path, stream.cuda_stream) == 1
+        stream.synchronize()
+        print("  restored", flush=True)
+        for k in ks:
+            assert np.array_equal(shard.readback(k), host[k]), spec.tensors[k].name
+        for c in clones.values():
+            c.free()
+        # the state in the file is the one after update 1, not update 2: re-run update 2 and compare one tensor
+        k = ks[1]
+        before = shard.readback(k)
+        shard.update(2, stream)
+        stream.synchronize()
+        assert not np.array_equal(before, shard.readback(k))
+        if config == 5:
+            # round trip: snapshot the restored-then-updated state again, restore it, and the bytes persist
+            ck.snapshot_async(2, stream.cuda_stream)
+            ck.flush(2)
+            want = {k: shard.readback(k) for k in ks}
+            shard.update(3, stream)
+            assert ck.restore(ck.file_name(2), stream.cuda_stream) == 2
+            stream.synchronize()
+            for k in ks:
+                assert np.array_equal(shard.readback(k), want[k])
+    finally:
+        if ck is not None:
+            ck.destroy()
+        shard.free()
+        shutil.rmtree(d, ignore_errors=True)
