@@ -251,11 +251,14 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     def gbps(nbytes, ms):
         return nbytes / (ms * 1e-3) / 1e9 if ms and ms > 0 else None
 
-    def stall_report(reg, base_iter_ms, base_gemm_ms):
+    def stall_report(reg, base_iter_ms, base_gemm_ms, drained_before=False):
         """Stall of a region. Reference step time: the quiet steps of the same region (4 or more steps after
         the latest snapshot request) when there are at least three, measured under identical conditions;
         otherwise the no-checkpoint baseline phases. GEMM slowdown: steps overlapping copies vs the same reference."""
-        in_reg = [it for it in requested if reg["first"] - 1 <= it < reg["last"]]
+        # snapshots whose copies run inside the region: requested by the step before it (unless everything was
+        # drained before the region began) up to the step before its last
+        lo = reg["first"] if drained_before else reg["first"] - 1
+        in_reg = [it for it in requested if lo <= it < reg["last"]]
         busy, quiet, quiet_iter = [], [], []
         for i, g in enumerate(reg["gemm_ms"]):
             since = min([reg["first"] + i - it for it in requested if it < reg["first"] + i] or [99])
@@ -371,7 +374,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         "stall": stall,
     }
     if variant:
-        v_in, v_stall, _ = stall_report(variant, base_iter_ms, base_gemm_ms)
+        v_in, v_stall, _ = stall_report(variant, base_iter_ms, base_gemm_ms, drained_before=True)
         v_stats = [ck.stats(it) for it in v_in]
         v_stall["steps"] = len(variant["iter_ms"])
         v_stall["snapshots"] = len(v_in)
@@ -386,6 +389,13 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
             json.dump({"main": main, "variant": variant, "requested": requested, "snapshots": all_stats,
                        "baseline_iter_ms": base_iter_ms, "baseline_gemm_ms": base_gemm_ms}, f, indent=1)
 
+    # the same kernel without a GEMM competing for the CUs: the snapshot requested by the last timed step
+    # (its pack launches run while the host waits for the device at the end of the region)
+    tail = [st for st in all_stats if st["iter"] == main["last"] and st["pack_ms_sum"] > 0]
+    if tail:
+        iso = gbps(pack_bytes_per_snapshot, tail[0]["pack_ms_sum"])
+        result["roofline"]["no_gemm_running"] = {"achieved": round(iso, 1), "frac": round(iso / HBM_PEAK_GBPS, 4),
+                                                 "avg_launch_ms": round(tail[0]["pack_ms_sum"] / tail[0]["pack_launches"], 4)}
     ratio = traffic_ratio()
     if ratio and pack_launches:
         result["roofline"]["traffic"] = round(ratio * result["roofline"]["bytes_per_launch"])

@@ -397,15 +397,19 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
 
     if ((e = hipStreamWaitEvent(c->pack_stream, s->ev_boundary, 0)) != hipSuccess) hip_fail("wait boundary", e);
     double bp_ms = 0;
-    // Pack launches run ahead of the copies as far as staging allows: the first n_stage super-chunks are
-    // packed right away (they depend on nothing but the boundary), super-chunk sc + n_stage as soon as the
-    // copies of sc, whose staging slot it reuses, are enqueued. The copies below may block this thread on
-    // ring back-pressure; the packs must not queue up behind that.
+    // Pack launches run `ahead` super-chunks in front of the copies: as far as staging allows when the
+    // window closes with the last pack (policy PACK: get the reads of the tensors over with), two
+    // otherwise (under the paper's rule nothing is gained by packing earlier, and a burst of pack
+    // kernels would only compete with the forward pass). Pack sc waits, on the device, for the copies of
+    // super-chunk sc - ahead, which also frees its staging slot (ahead <= n_stage, copies are in order).
+    // The copies further down may block this thread on ring back-pressure; pack launches are
+    // therefore enqueued before the copies they do not depend on.
+    const uint64_t ahead = c->cfg.window_policy == CKPT_WINDOW_PACK ? c->n_stage : std::min<uint64_t>(c->n_stage, 2);
     auto enqueue_pack = [&](uint64_t sc) {
         const uint64_t stage = sc % c->n_stage;
-        if (sc >= c->n_stage)
+        if (sc >= ahead)
             for (size_t k = 0; k < nk; k++)
-                if ((e = hipStreamWaitEvent(c->pack_stream, c->ev_stage_done[stage][k], 0)) != hipSuccess) hip_fail("wait stage", e);
+                if ((e = hipStreamWaitEvent(c->pack_stream, c->ev_stage_done[(sc - ahead) % c->n_stage][k], 0)) != hipSuccess) hip_fail("wait stage", e);
         if ((e = hipEventRecord(c->ev_pack_start[sc], c->pack_stream)) != hipSuccess) hip_fail("record", e);
         const uint64_t t0 = p.sc_first_tile[sc], t1 = p.sc_first_tile[sc + 1];
         if ((e = launch_pack(c->dev_tiles + t0, t1 - t0, c->staging + stage * SC, sc * SC, c->pack_stream)) != hipSuccess) hip_fail("pack launch", e);
@@ -416,7 +420,7 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
             c->cv_state.notify_all();
         }
     };
-    for (uint64_t sc = 0; sc < std::min<uint64_t>(c->n_stage, p.n_superchunks); sc++) enqueue_pack(sc);
+    for (uint64_t sc = 0; sc < std::min<uint64_t>(ahead, p.n_superchunks); sc++) enqueue_pack(sc);
     for (uint64_t sc = 0; sc < p.n_superchunks; sc++) {
         const uint64_t stage = sc % c->n_stage;
         uint8_t *stage_base = c->staging + stage * SC;
@@ -462,7 +466,7 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
             }
             c->cv_io.notify_one();
         }
-        if (sc + c->n_stage < p.n_superchunks) enqueue_pack(sc + c->n_stage);
+        if (sc + ahead < p.n_superchunks) enqueue_pack(sc + ahead);
     }
     std::lock_guard<std::mutex> lk(c->mu);
     s->backpressure_ms = bp_ms;
