@@ -334,3 +334,43 @@ def test_default_stream_and_default_config(big_dir):
     assert os.path.getsize(ck.file_name(1)) == ck.layout()["file_bytes"] == 1_742_157_312 + 600_576 + ck.layout()["header_bytes"]
     assert oracle.compare_file(shard.oracle_tensors(host), 1, ck.file_name(1)) is None
     ck.destroy()
+
+
+def test_edge_sizes_and_a_tensor_beyond_4_gib(big_dir):
+    """Sizes around every internal boundary (16 B word, 4 KiB unit, 32 KiB tile), a one-byte tensor, a
+    scalar, and one tensor larger than 4 GiB (offsets and tile counts beyond 32 bits), all carved at odd
+    offsets out of one flat buffer. Whole file compared by the oracle's streaming comparison."""
+    _say("edge sizes")
+    sizes = [1, 2, 15, 16, 17, 4095, 4096, 4097, 32767, 32768, 32769, 65535, (4 << 30) + 4097 + 3]
+    tensors, off = [], 3
+    for i, n in enumerate(sizes):
+        tensors.append(shards.TensorSpec(f"edge{i}_{n}", shards.U8, (n,), buffer=0, offset=off, role="raw"))
+        off += n + (i % 7) + 1
+    tensors.append(shards.TensorSpec("scalar", shards.I64, (), buffer=0, offset=(off + 7) // 8 * 8, role="raw"))
+    off = tensors[-1].offset + 8
+    spec = shards.ShardSpec("edges", 99, tensors, flat_buffers=[(off + 255) // 256 * 256])
+    shard = harness.DeviceShard(spec)
+    stream = harness.Stream()
+    shard.fill_device(stream)                      # seeded words over the whole flat buffer
+    stream.synchronize()
+    ck = B.Checkpointer(B.make_config(out_dir=big_dir, host_ring_bytes=1 << 30, dma_chunk_bytes=32 << 20,
+                                      pack_superchunk_bytes=512 << 20, n_io_threads=8))
+    ck.register_tensors(shard.descs())
+    lay = ck.layout()
+    assert lay["n_superchunks"] >= 9 and lay["data_bytes"] > (4 << 30)
+    ck.snapshot_async(7, stream.cuda_stream)
+    ck.wait_immutable_window_end(stream.cuda_stream)
+    host = shard.readback_all()
+    ck.flush(7)
+    assert oracle.compare_file(shard.oracle_tensors(host), 7, ck.file_name(7)) is None
+    whole = shard.flat[0].download()
+    shard.poison(0x5A)
+    assert ck.restore(ck.file_name(7), stream.cuda_stream) == 7
+    stream.synchronize()
+    after = shard.flat[0].download()
+    used = np.zeros(spec.flat_buffers[0], dtype=bool)
+    for t in tensors:
+        used[t.offset:t.offset + t.nbytes] = True
+    assert np.array_equal(after[used], whole[used]) and np.all(after[~used] == 0x5A)
+    ck.destroy()
+    shard.free()
