@@ -1,0 +1,174 @@
+// The whole snapshot engine on the CPU, against the model runtime of hip/hip_runtime.h in this
+// folder, meant to be built with -fsanitize=thread: caller thread, submit thread, I/O threads and one
+// thread per stream all run for real, so ThreadSanitizer sees every pair of accesses that the
+// engine's event graph fails to order (the update writing tensors a pack kernel still reads, a copy
+// reading staging before the pack wrote it, a ring slot reused before it was written out, ...).
+// The files are compared with images built here by plain memcpy.
+#include <cstdio>
+#include <cstdlib>
+#include <string>
+#include <vector>
+
+#include <sys/stat.h>
+#include <unistd.h>
+
+#include "../../include/ckpt.h"
+#include "hip/hip_runtime.h"
+
+thread_local dim3 threadIdx, blockIdx, blockDim, gridDim;
+
+static uint64_t rng_state;
+static uint64_t rnd() {
+    rng_state += 0x9E3779B97F4A7C15ull;
+    uint64_t z = rng_state;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+#define REQUIRE(cond)                                                                        \
+    do {                                                                                     \
+        if (!(cond)) { printf("FAILED %s line %d: %s (%s)\n", #cond, __LINE__, ckpt_last_error(), what.c_str()); return 1; } \
+    } while (0)
+
+struct Tensor { uint8_t *base; uint64_t lead, nbytes; std::string name; int64_t shape; };
+
+static std::vector<uint8_t> read_file(const std::string &p) {
+    std::vector<uint8_t> out;
+    FILE *f = fopen(p.c_str(), "rb");
+    if (!f) return out;
+    fseek(f, 0, SEEK_END);
+    long n = ftell(f);
+    fseek(f, 0, SEEK_SET);
+    out.resize(n);
+    if (n && fread(out.data(), 1, n, f) != size_t(n)) out.clear();
+    fclose(f);
+    return out;
+}
+
+static int scenario(const std::string &dir, int policy, int keep_last, int io_mode, uint64_t ring_bytes, uint64_t staging_bytes, int n_tensors) {
+    std::string what = "policy " + std::to_string(policy) + " keep_last " + std::to_string(keep_last) + " io_mode " + std::to_string(io_mode);
+    std::vector<Tensor> ts;
+    for (int k = 0; k < n_tensors; k++) {
+        Tensor t;
+        t.lead = k < 16 ? k : rnd() % 16;
+        switch (rnd() % 4) {
+            case 0: t.nbytes = 1 + rnd() % 100; break;
+            case 1: t.nbytes = 4096 - 8 + rnd() % 17; break;
+            case 2: t.nbytes = 32768 * (1 + rnd() % 3) - 20 + rnd() % 41; break;
+            default: t.nbytes = 1 + rnd() % 150000; break;
+        }
+        t.base = static_cast<uint8_t *>(aligned_alloc(16, (t.lead + t.nbytes + 15) / 16 * 16));
+        for (uint64_t i = 0; i < t.lead + t.nbytes; i++) t.base[i] = uint8_t(rnd());
+        t.name = "t" + std::to_string(k);
+        t.shape = int64_t(t.nbytes);
+        ts.push_back(t);
+    }
+    std::vector<ckpt_tensor_desc> descs;
+    for (auto &t : ts) {
+        ckpt_tensor_desc d{};
+        d.name = t.name.c_str(); d.dtype = CKPT_U8; d.ndim = 1; d.shape = &t.shape; d.dev_ptr = t.base + t.lead; d.nbytes = t.nbytes;
+        descs.push_back(d);
+    }
+    ckpt_config cfg{};
+    cfg.device = 0;
+    cfg.out_dir = dir.c_str();
+    cfg.host_ring_bytes = ring_bytes;
+    cfg.dma_chunk_bytes = 64 << 10;
+    cfg.pack_superchunk_bytes = 256 << 10;
+    cfg.dev_staging_bytes = staging_bytes;
+    cfg.n_dma_streams = 2;
+    cfg.n_io_threads = 3;
+    cfg.window_policy = policy;
+    cfg.io_mode = io_mode;
+    cfg.keep_last = keep_last;
+    cfg.prealloc_files = keep_last ? 1 : 0;
+    ckpt_ctx *ctx = nullptr;
+    REQUIRE(ckpt_init(&cfg, &ctx) == CKPT_OK);
+    REQUIRE(ckpt_register_tensors(ctx, descs.data(), descs.size()) == CKPT_OK);
+    ckpt_layout lay;
+    REQUIRE(ckpt_get_layout(ctx, &lay) == CKPT_OK);
+    ckpt_plan *plan = nullptr;
+    REQUIRE(ckpt_plan_create(descs.data(), descs.size(), &cfg, &plan) == CKPT_OK);
+    std::vector<uint64_t> offs(descs.size());
+    REQUIRE(ckpt_plan_offsets(plan, offs.data(), offs.size()) == CKPT_OK);
+
+    hipStream_t compute;
+    hipStreamCreateWithFlags(&compute, hipStreamNonBlocking);
+    const int iters = 6;
+    std::vector<std::vector<uint8_t>> expect(iters + 1);
+    for (int it = 1; it <= iters; it++) {
+        // forward/backward stand-in: reads every tensor (must be allowed to overlap the snapshot)
+        emu_submit(compute, [&ts] { volatile uint64_t sum = 0; for (auto &t : ts) for (uint64_t i = 0; i < t.nbytes; i += 64) sum = sum + t.base[t.lead + i]; });
+        REQUIRE(ckpt_wait_immutable_window_end(ctx, compute, 0) == CKPT_OK);
+        // update: mutates every byte, then the expected image of this boundary is taken, in stream order
+        emu_submit(compute, [&ts, it] { for (auto &t : ts) for (uint64_t i = 0; i < t.nbytes; i++) t.base[t.lead + i] = uint8_t(t.base[t.lead + i] * 31 + it); });
+        std::vector<uint8_t> *img = &expect[it];
+        emu_submit(compute, [&ts, &offs, &lay, plan, img, it] {
+            img->assign(lay.file_bytes, 0);
+            ckpt_plan_header(plan, uint64_t(it), img->data(), lay.header_bytes);
+            for (size_t k = 0; k < ts.size(); k++) memcpy(img->data() + offs[k], ts[k].base + ts[k].lead, ts[k].nbytes);
+        });
+        REQUIRE(ckpt_snapshot_async(ctx, uint64_t(it), compute) == CKPT_OK);
+    }
+    REQUIRE(ckpt_flush(ctx, CKPT_ITER_ALL) == CKPT_OK);
+    hipStreamSynchronize(compute);
+    char name[4096];
+    for (int it = 1; it <= iters; it++) {
+        REQUIRE(ckpt_file_name(ctx, uint64_t(it), name, sizeof name) == CKPT_OK);
+        std::vector<uint8_t> got = read_file(name);
+        const bool should_exist = keep_last == 0 || it > iters - keep_last;
+        if (!should_exist) { REQUIRE(got.empty()); continue; }
+        what = "iteration " + std::to_string(it);
+        REQUIRE(got == expect[it]);
+        ckpt_stats st;
+        REQUIRE(ckpt_get_stats(ctx, uint64_t(it), &st) == CKPT_OK && st.committed == 1 && st.d2h_done == 1);
+    }
+    // restore the newest file into poisoned tensors; bytes around the tensors must stay untouched
+    for (auto &t : ts) memset(t.base, 0xA5, (t.lead + t.nbytes + 15) / 16 * 16);
+    uint64_t got_iter = 0;
+    REQUIRE(ckpt_file_name(ctx, uint64_t(iters), name, sizeof name) == CKPT_OK);
+    REQUIRE(ckpt_restore(ctx, name, compute, &got_iter) == CKPT_OK && got_iter == uint64_t(iters));
+    hipStreamSynchronize(compute);
+    for (size_t k = 0; k < ts.size(); k++) {
+        what = "restore tensor " + std::to_string(k);
+        REQUIRE(memcmp(ts[k].base + ts[k].lead, expect[iters].data() + offs[k], ts[k].nbytes) == 0);
+        for (uint64_t i = 0; i < ts[k].lead; i++) REQUIRE(ts[k].base[i] == 0xA5);
+        for (uint64_t i = ts[k].lead + ts[k].nbytes; i < (ts[k].lead + ts[k].nbytes + 15) / 16 * 16; i++) REQUIRE(ts[k].base[i] == 0xA5);
+    }
+    // errors: a file of the wrong size, then the directory disappears under a snapshot
+    what = "error paths";
+    std::string bad = dir + "/bad.dsl";
+    { FILE *f = fopen(bad.c_str(), "wb"); fwrite(expect[iters].data(), 1, expect[iters].size() - 4096, f); fclose(f); }
+    REQUIRE(ckpt_restore(ctx, bad.c_str(), compute, nullptr) == CKPT_EFORMAT);
+    REQUIRE(ckpt_snapshot_async(ctx, 100, compute) == CKPT_OK);
+    REQUIRE(ckpt_snapshot_async(ctx, 101, compute) == CKPT_ESTATE);       // window of 100 not closed
+    REQUIRE(ckpt_flush(ctx, 100) == CKPT_OK);
+    REQUIRE(ckpt_flush(ctx, 555) == CKPT_EINVAL);
+    hipStreamSynchronize(compute);
+    REQUIRE(ckpt_destroy(ctx) == CKPT_OK);
+    ckpt_plan_destroy(plan);
+    hipStreamDestroy(compute);
+    for (auto &t : ts) free(t.base);
+    printf("ok %s: %d tensors, %llu data bytes, %llu super-chunks, %llu chunks\n",
+           ("policy " + std::to_string(policy) + " keep_last " + std::to_string(keep_last) + " io_mode " + std::to_string(io_mode)).c_str(),
+           n_tensors, (unsigned long long)lay.data_bytes, (unsigned long long)lay.n_superchunks, (unsigned long long)lay.n_chunks);
+    return 0;
+}
+
+int main(int argc, char **argv) {
+    if (argc < 2) { printf("usage: emu_engine <scratch dir> [seed]\n"); return 2; }
+    rng_state = argc > 2 ? strtoull(argv[2], 0, 10) : 1;
+    std::string root = argv[1];
+    int n = 0;
+    auto sub = [&] { std::string d = root + "/s" + std::to_string(n++); mkdir(d.c_str(), 0755); return d; };
+    // ring of 4 slots (much smaller than the data), staging of 2 super-chunks: the paper's rule
+    if (scenario(sub(), CKPT_WINDOW_D2H, 0, CKPT_IO_PWRITE, 256 << 10, 0, 60)) return 1;
+    // retention with recycled, mapped files
+    if (scenario(sub(), CKPT_WINDOW_D2H, 2, CKPT_IO_MMAP, 256 << 10, 0, 60)) return 1;
+    // update released after the pack; staging holds everything
+    if (scenario(sub(), CKPT_WINDOW_PACK, 1, CKPT_IO_MMAP, 512 << 10, 64 << 20, 60)) return 1;
+    // update released after the pack with only two staging slots (packs depend on copies)
+    if (scenario(sub(), CKPT_WINDOW_PACK, 0, CKPT_IO_PWRITE, 128 << 10, 0, 40)) return 1;
+    return 0;
+}

@@ -1,6 +1,8 @@
-"""Runs the pack and scatter kernel SOURCE on the CPU, thread by thread, under AddressSanitizer
-(tests/emu): every address the kernels compute is bounds-checked against exactly sized buffers and
-the results are compared with plain memcpy expectations. No GPU involved."""
+"""Runs the library's SOURCE on the CPU (tests/emu). The pack and scatter kernels run thread by thread
+under AddressSanitizer: every address they compute is bounds-checked against exactly sized buffers
+and the results are compared with plain memcpy expectations. The whole engine runs against a model of
+streams and events under ThreadSanitizer: files, restore, retention and error paths are checked, and
+any pair of accesses the engine's event graph leaves unordered is reported as a race. No GPU involved."""
 import os
 import shutil
 import subprocess
@@ -28,3 +30,24 @@ def test_pack_and_scatter_stay_in_bounds_and_move_the_right_bytes(emu, seed, n):
     r = subprocess.run([emu, str(seed), str(n)], capture_output=True, text=True, timeout=300)
     assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-4000:]
     assert r.stdout.startswith("ok seed")
+
+
+@pytest.fixture(scope="module")
+def emu_engine(tmp_path_factory):
+    if not os.path.exists(CLANG):
+        pytest.skip("ROCm clang not present")
+    exe = str(tmp_path_factory.mktemp("emu") / "emu_engine")
+    csrc = os.path.join(ROOT, "paper_2406_10707_amd", "csrc")
+    cmd = [CLANG, "-x", "c++", "-std=c++17", "-O1", "-g", "-fsanitize=thread", "-fno-omit-frame-pointer", "-pthread",
+           "-I", os.path.join(ROOT, "tests", "emu"), "-o", exe, os.path.join(ROOT, "tests", "emu", "emu_engine.cpp"),
+           os.path.join(csrc, "engine.cpp"), os.path.join(csrc, "plan.cpp"), os.path.join(csrc, "pack_kernels.hip")]
+    subprocess.run(cmd, check=True, cwd=os.path.join(ROOT, "tests", "emu"))
+    return exe
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_engine_event_graph_under_thread_sanitizer(emu_engine, seed, tmp_path):
+    r = subprocess.run([emu_engine, str(tmp_path), str(seed)], capture_output=True, text=True, timeout=600)
+    out = r.stdout + r.stderr
+    assert r.returncode == 0 and "ThreadSanitizer" not in out and "FAILED" not in out, out[-6000:]
+    assert out.count("ok policy") == 4
