@@ -43,7 +43,7 @@ def parse_args():
     ap.add_argument("--chunk-mib", type=int, default=64)
     ap.add_argument("--superchunk-mib", type=int, default=1024)
     ap.add_argument("--dma-streams", type=int, default=2)
-    ap.add_argument("--io-threads", type=int, default=12)
+    ap.add_argument("--io-threads", type=int, default=6)
     ap.add_argument("--policy", choices=["d2h", "pack"], default="d2h")
     ap.add_argument("--io-mode", choices=["auto", "pwrite", "mmap"], default="auto")
     ap.add_argument("--keep-last", type=int, default=1, help="checkpoint files kept; older ones are recycled in place (0: keep all)")

@@ -27,15 +27,28 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #define DSLLM_PACK_UNROLL 8
 #endif
 #ifndef DSLLM_PACK_UNROLL_SHIFT
-#define DSLLM_PACK_UNROLL_SHIFT 8
+#define DSLLM_PACK_UNROLL_SHIFT 4
 #endif
 constexpr int kWavesPerBlock = DSLLM_PACK_WAVES_PER_BLOCK;
 constexpr int kBlock = 64 * kWavesPerBlock;
 constexpr int kUnroll = DSLLM_PACK_UNROLL;             // aligned path: 16-byte words per lane in flight
 constexpr int kUnrollShift = DSLLM_PACK_UNROLL_SHIFT;  // misaligned path: pairs of 16-byte words per lane in flight
 
-__device__ __forceinline__ u32x4 ld16(const u32x4 *p) { return __builtin_nontemporal_load(p); }
-__device__ __forceinline__ void st16(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+// Tensor addresses come out of the descriptor table as integers, so the compiler cannot know they
+// are global memory and would use flat loads (which also pass through the LDS address check and
+// count against two wait counters). Casting to the global address space gives global_load/store.
+#if defined(__HIP_DEVICE_COMPILE__)
+#define DSLLM_GLOBAL __attribute__((address_space(1)))
+// Keeps a loaded 16-byte word whole and in registers of its own. Without it the compiler narrows the
+// two loads of the misaligned path to the dwords the shift uses and packs them into overlapping
+// registers, which forces a wait after every pair of loads.
+#define DSLLM_KEEP_WHOLE(v) asm volatile("" : "+v"(v))
+#else
+#define DSLLM_GLOBAL
+#define DSLLM_KEEP_WHOLE(v) (void)0
+#endif
+__device__ __forceinline__ u32x4 ld16(const u32x4 *p) { return __builtin_nontemporal_load((const u32x4 DSLLM_GLOBAL *)p); }
+__device__ __forceinline__ void st16(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, (u32x4 DSLLM_GLOBAL *)p); }
 
 // A value that is the same in every lane of the wavefront, moved to scalar registers. The builtin
 // returns a signed int: each half goes through uint32_t before widening, or the low half would be
@@ -80,6 +93,8 @@ __device__ __forceinline__ void pack_shifted(const u32x4 *src_al, u32x4 *dst, ui
         u32x4 lo[kUnrollShift], hi[kUnrollShift];
 #pragma unroll
         for (int u = 0; u < kUnrollShift; u++) { lo[u] = ld16(src_al + i + 64 * u); hi[u] = ld16(src_al + i + 64 * u + 1); }
+#pragma unroll
+        for (int u = 0; u < kUnrollShift; u++) { DSLLM_KEEP_WHOLE(lo[u]); DSLLM_KEEP_WHOLE(hi[u]); }
 #pragma unroll
         for (int u = 0; u < kUnrollShift; u++) st16(dst + i + 64 * u, funnel<W>(lo[u], hi[u], b));
     }
@@ -157,6 +172,8 @@ __device__ __forceinline__ void scatter_shifted(const u32x4 *src, u32x4 *dst_al,
         u32x4 lo[kUnrollShift], hi[kUnrollShift];
 #pragma unroll
         for (int u = 0; u < kUnrollShift; u++) { lo[u] = ld16(src + i + 64 * u); hi[u] = ld16(src + i + 64 * u + 1); }
+#pragma unroll
+        for (int u = 0; u < kUnrollShift; u++) { DSLLM_KEEP_WHOLE(lo[u]); DSLLM_KEEP_WHOLE(hi[u]); }
 #pragma unroll
         for (int u = 0; u < kUnrollShift; u++) st16(dst_al + 1 + i + 64 * u, funnel<W>(lo[u], hi[u], b));
     }
