@@ -104,9 +104,11 @@ __device__ __forceinline__ void pack_shifted(const u32x4 *src_al, u32x4 *dst, ui
 __global__ __launch_bounds__(kBlock) void pack_kernel(const ckpt_tile *__restrict__ tiles, uint64_t n_tiles,
                                                      uint8_t *__restrict__ slot_base, uint64_t slot_data_off) {
     const uint32_t lane = threadIdx.x & 63;
-    const uint64_t t = uint64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+    // The wavefront's number within the block is made uniform first: the descriptor address is then a
+    // scalar value and the descriptor arrives through scalar loads (read-only path, no vector-memory
+    // round trip before the first data load); measured, this closes the gap to a table-free copy.
+    const uint64_t t = uint64_t(blockIdx.x) * kWavesPerBlock + uniform_u32(threadIdx.x >> 6);
     if (t >= n_tiles) return;
-    // the descriptor is the same for the whole wavefront: keep it in scalar registers
     const ckpt_tile *tp = tiles + t;
     const uint64_t src = uniform_u64(tp->src);
     const uint64_t dst_off = uniform_u64(tp->dst_off);
@@ -183,7 +185,7 @@ __device__ __forceinline__ void scatter_shifted(const u32x4 *src, u32x4 *dst_al,
 __global__ __launch_bounds__(kBlock) void scatter_kernel(const ckpt_tile *__restrict__ tiles, uint64_t n_tiles,
                                                         const uint8_t *__restrict__ slot_base, uint64_t slot_data_off) {
     const uint32_t lane = threadIdx.x & 63;
-    const uint64_t t = uint64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+    const uint64_t t = uint64_t(blockIdx.x) * kWavesPerBlock + uniform_u32(threadIdx.x >> 6);   // uniform: scalar descriptor loads
     if (t >= n_tiles) return;
     const ckpt_tile *tp = tiles + t;
     const uint64_t dstp = uniform_u64(tp->src);
