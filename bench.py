@@ -48,6 +48,9 @@ def parse_args():
     ap.add_argument("--io-mode", choices=["auto", "pwrite", "mmap"], default="auto")
     ap.add_argument("--keep-last", type=int, default=1, help="checkpoint files kept; older ones are recycled in place (0: keep all)")
     ap.add_argument("--prealloc", type=int, default=2, help="spare files pre-allocated at registration")
+    ap.add_argument("--direct-min-mib", type=float, default=0.0,
+                    help="hybrid path: tensors of at least this size are copied by the DMA engines straight out of their own "
+                         "memory, only smaller ones are packed (0: everything is packed)")
     ap.add_argument("--out-dir", default="")
     ap.add_argument("--baseline-steps", type=int, default=6)
     ap.add_argument("--oracle-sample-gb", type=float, default=8.0)
@@ -55,6 +58,9 @@ def parse_args():
     ap.add_argument("--no-restore", action="store_true")
     ap.add_argument("--variant-steps", type=int, default=20,
                     help="extra steps measured under window policy PACK with full device staging (0: skip)")
+    ap.add_argument("--paired-blocks", type=int, default=3,
+                    help="workloads that checkpoint every step: alternate this many blocks of checkpointed and quiet steps "
+                         "after the timed region for a stall figure free of thermal drift (0: off)")
     ap.add_argument("--dump", default="", help="write per-step timings and per-snapshot measurements to this JSON file")
     return ap.parse_args()
 
@@ -169,7 +175,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     args.ring_gib = round(ring_bytes / (1 << 30), 2)
     # the variant (update released after the pack, copies drain from device staging) needs staging for the whole
     # data region; under the paper's rule the staging size is not on the critical path
-    want_variant = args.variant_steps > 0 and args.policy == "d2h"
+    want_variant = args.variant_steps > 0 and args.policy == "d2h" and args.direct_min_mib == 0
     staging_bytes = int(args.staging_gib * (1 << 30))
     if want_variant and not staging_bytes:
         full = -(-data_upper // sc) * sc
@@ -181,7 +187,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     staging_gib = round((staging_bytes or 2 * sc) / (1 << 30), 2)
     cfg = B.make_config(out_dir=out_dir, host_ring_bytes=ring_bytes, dma_chunk_bytes=chunk, pack_superchunk_bytes=sc,
                         dev_staging_bytes=staging_bytes, n_dma_streams=args.dma_streams, n_io_threads=args.io_threads,
-                        window_policy=policy,
+                        window_policy=policy, direct_min_bytes=int(args.direct_min_mib * (1 << 20)),
                         io_mode={"auto": B.CKPT_IO_AUTO, "pwrite": B.CKPT_IO_PWRITE, "mmap": B.CKPT_IO_MMAP}[args.io_mode],
                         keep_last=args.keep_last, prealloc_files=args.prealloc if args.keep_last else 0)
     t0 = time.perf_counter()
@@ -193,7 +199,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     requested, live_files = [], []
     state = {"step": 0}
 
-    def iteration(step, with_ckpt, marks):
+    def iteration(step, with_ckpt, marks, snap=True):
         """One step on `stream`; marks gets (start, after-gemm, end) events."""
         e = [harness.Event() for _ in range(3)]
         e[0].record(stream)
@@ -202,7 +208,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         if with_ckpt:
             ck.wait_immutable_window_end(stream.cuda_stream)
         shard.update(step, stream)
-        if with_ckpt and step % every == 0:
+        if with_ckpt and snap and step % every == 0:
             ck.snapshot_async(step, stream.cuda_stream)
             requested.append(step)
             live_files.append(step)
@@ -247,6 +253,27 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         wall = time.perf_counter() - t_start
         return {"first": first, "last": state["step"], "wall_s": wall,
                 "iter_ms": [m[0].elapsed_time(m[2]) for m in marks], "gemm_ms": [m[0].elapsed_time(m[1]) for m in marks]}
+
+    def alternating_phase(blocks, block_len):
+        """Blocks of checkpointed steps alternate with blocks of steps that request no snapshot, a few seconds
+        each, so both kinds run in the same thermal state of the card (its GEMM speed drifts by a few per cent
+        over tens of seconds, which biases a comparison with a separate no-checkpoint phase). Compared are the
+        steady steps of each kind: checkpointed steps whose predecessor also requested a snapshot, and quiet
+        steps from the third of a block on (the last snapshot's copies are over by then)."""
+        marks, kind = [], []
+        harness.synchronize()
+        for _ in range(blocks):
+            for j in range(2 * block_len):
+                state["step"] += 1
+                iteration(state["step"], True, marks, snap=j < block_len)
+                kind.append(("busy" if j >= 1 else None) if j < block_len else ("quiet" if j - block_len >= 2 else None))
+                reap()
+        harness.synchronize()
+        out = {}
+        for name in ("busy", "quiet"):
+            sel = [m for m, k in zip(marks, kind) if k == name]
+            out[name] = (statistics.median(m[0].elapsed_time(m[2]) for m in sel), statistics.median(m[0].elapsed_time(m[1]) for m in sel), len(sel))
+        return out
 
     def gbps(nbytes, ms):
         return nbytes / (ms * 1e-3) / 1e9 if ms and ms > 0 else None
@@ -310,6 +337,21 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         ok = all((shard.readback(k) == want[k]).all() for k in probe) if last == state["step"] else None
         restore_result = {"gbps": round(S / dt / 1e9, 2), "seconds": round(dt, 2), "probe_tensors_bit_exact": ok if ok is None else bool(ok)}
 
+    # ---- every-iteration workloads have no quiet steps inside the timed region: paired reference
+    paired = None
+    if every == 1 and args.paired_blocks > 0:
+        ck.flush()
+        block_len = max(5, min(20, int(1000.0 / max(compute_ms, 1.0) + 0.999)))
+        alt = alternating_phase(args.paired_blocks, block_len)
+        ck.flush()
+        reap(block=True)
+        paired = {"checkpointed_ms_per_step": round(alt["busy"][0], 3), "quiet_ms_per_step": round(alt["quiet"][0], 3),
+                  "stall_ms_per_step": round(alt["busy"][0] - alt["quiet"][0], 3),
+                  "stall_pct": round(100.0 * (alt["busy"][0] / alt["quiet"][0] - 1), 3),
+                  "gemm_slowdown_pct": round(100.0 * (alt["busy"][1] / alt["quiet"][1] - 1), 3),
+                  "steps_compared": [alt["busy"][2], alt["quiet"][2]], "block_len": block_len,
+                  "note": "blocks of checkpointed and of quiet steps alternate, medians of the steady steps of each kind"}
+
     # ---- variant: window released after the pack (policy PACK, staging holds the whole data region)
     variant = None
     if want_variant:
@@ -334,10 +376,15 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     pack_launches = sum(s["pack_launches"] for s in stats)
     pack_ms = sum(s["pack_ms_sum"] for s in stats)
     # algorithmic bytes of the pack kernel: every payload byte read once, every data-region byte written once
-    pack_bytes_per_snapshot = lay["payload_bytes"] + lay["data_bytes"]
+    # (tensors copied directly on the hybrid path never pass through the kernel)
+    pack_bytes_per_snapshot = lay["payload_bytes"] - lay["direct_bytes"] + lay["data_bytes"] - lay["direct_data_bytes"]
     pack_gbps = gbps(pack_bytes_per_snapshot * len(stats), pack_ms) if stats else None
     # physical floor under the paper's rule: the copies cannot end before D / B_link, the window is the GEMM phase
     stall["floor_ms_per_snapshot"] = round(max(0.0, S / (link["d2h"] * 1e9) * 1e3 - ref_gemm_ms), 2)
+    stall["stall_minus_floor_ms_per_snapshot"] = round(stall["stall_ms_per_snapshot"] - stall["floor_ms_per_snapshot"], 2)
+    if paired:
+        paired["stall_minus_floor_ms_per_step"] = round(paired["stall_ms_per_step"] - stall["floor_ms_per_snapshot"], 2)
+        stall["paired_alternating_blocks"] = paired
     stall["baseline_before_after_ms"] = [round(base_before[0], 2), round(base_after[0], 2)]
     stall["gemm_tflops"] = round(gemm.flops_per_launch / (gemm_ms_per_launch * 1e-3) / 1e12, 1)
 
@@ -355,7 +402,9 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                    "staging_gib": staging_gib, "dma_streams": args.dma_streams, "io_threads": args.io_threads,
                    "hw_queues": int(os.environ["GPU_MAX_HW_QUEUES"]), "device": info["name"],
                    "hip_runtime": info["hip_runtime_version"], "io_mode": args.io_mode, "keep_last": args.keep_last,
-                   "prealloc_files": args.prealloc, "sink": out_dir.rsplit("/", 1)[0]},
+                   "prealloc_files": args.prealloc, "sink": out_dir.rsplit("/", 1)[0],
+                   "direct_min_mib": args.direct_min_mib, "direct_tensors": lay["n_direct_tensors"],
+                   "direct_bytes": lay["direct_bytes"], "copy_segments": lay["n_segments"]},
         "roofline": {"bound": "hbm", "kernel": "pack_kernel", "achieved": round(pack_gbps, 1) if pack_gbps else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(pack_gbps / HBM_PEAK_GBPS, 4) if pack_gbps else None,
                      "traffic": None, "traffic_source": "rocprofv3 FETCH_SIZE+WRITE_SIZE ratio from profiles/ x algorithmic bytes per launch",

@@ -89,7 +89,13 @@ typedef struct {
                                        pages the next snapshots overwrite in place (no page allocation on the write path,
                                        as with the host cache). K valid files plus one being written exist at a time. */
     int32_t prealloc_files;         /* spare files created, with all pages allocated, at registration (needs keep_last > 0) */
-    int32_t reserved[4];            /* must be zero */
+    uint64_t direct_min_bytes;      /* 0: every tensor goes through the pack kernel. N > 0: hybrid path (the paper's
+                                       tensor-by-tensor copies for what is large, coalescing for what is small): a
+                                       tensor of at least N bytes is copied by the DMA engines straight between its own
+                                       device memory and the ring slot, without pack kernel or staging; only smaller
+                                       tensors are packed. Needs window_policy CKPT_WINDOW_D2H (the copies read the
+                                       tensors themselves). At least 4096 when set. */
+    int32_t reserved[2];            /* must be zero */
 } ckpt_config;
 
 /* Sizes that follow from a tensor list and a configuration. */
@@ -101,6 +107,9 @@ typedef struct {
     uint64_t n_chunks;                             /* DMA chunks per snapshot */
     uint64_t n_superchunks;                        /* pack launches per snapshot */
     uint64_t dma_chunk_bytes, pack_superchunk_bytes, tile_bytes;
+    uint64_t n_segments;                           /* copy segments per snapshot (>= n_chunks) */
+    uint64_t n_direct_tensors, direct_bytes;       /* tensors copied without the pack kernel, and their payload */
+    uint64_t direct_data_bytes;                    /* the same tensors' share of the data region (payload + padding) */
 } ckpt_layout;
 
 /* One pack work item: `copy_bytes` bytes from device address `src` go to offset `dst_off` of the data
@@ -113,6 +122,20 @@ typedef struct {
     uint32_t total_bytes;
     uint64_t reserved;
 } ckpt_tile;
+
+/* One piece of a DMA chunk. The segments of a chunk partition it, in order. STAGED: the bytes come
+ * from (go to, on restore) device staging, where the pack kernel put them; DIRECT: they are `nbytes`
+ * bytes of a registered tensor at device address `src`; ZERO: the padding behind a DIRECT tensor,
+ * zero-filled in the ring slot by the host and skipped on restore. Without direct_min_bytes every
+ * chunk is one STAGED segment. */
+typedef enum { CKPT_SEG_STAGED = 0, CKPT_SEG_DIRECT = 1, CKPT_SEG_ZERO = 2 } ckpt_segment_kind;
+typedef struct {
+    uint64_t data_off;   /* offset in the data region */
+    uint64_t nbytes;
+    uint64_t src;        /* DIRECT: device address; otherwise 0 */
+    uint32_t kind;       /* ckpt_segment_kind */
+    uint32_t tensor;     /* DIRECT, ZERO: registration index of the tensor; otherwise 0 */
+} ckpt_segment;
 
 /* Per-snapshot measurements. Times in milliseconds on the device timeline (HIP events) unless
  * marked host. A field is -1 while not yet known. */
@@ -150,6 +173,9 @@ int ckpt_plan_offsets(const ckpt_plan *plan, uint64_t *out, size_t cap);
 /* Copies tiles [first, first+count) into out; first_tile_of_superchunk (n_superchunks+1 entries) may be NULL. */
 int ckpt_plan_tiles(const ckpt_plan *plan, uint64_t first, uint64_t count, ckpt_tile *out);
 int ckpt_plan_superchunk_tiles(const ckpt_plan *plan, uint64_t *first_tile_of_superchunk, size_t cap);
+/* Copies segments [first, first+count) into out; first_segment_of_chunk takes n_chunks+1 entries. */
+int ckpt_plan_segments(const ckpt_plan *plan, uint64_t first, uint64_t count, ckpt_segment *out);
+int ckpt_plan_chunk_segments(const ckpt_plan *plan, uint64_t *first_segment_of_chunk, size_t cap);
 void ckpt_plan_destroy(ckpt_plan *plan);
 
 /* ---- the snapshot path ---- */

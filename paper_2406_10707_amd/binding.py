@@ -32,17 +32,25 @@ class ckpt_config(C.Structure):
                 ("dma_chunk_bytes", C.c_uint64), ("pack_superchunk_bytes", C.c_uint64), ("dev_staging_bytes", C.c_uint64),
                 ("n_dma_streams", C.c_int32), ("n_io_threads", C.c_int32), ("window_policy", C.c_int32),
                 ("o_direct", C.c_int32), ("fsync_on_commit", C.c_int32), ("io_mode", C.c_int32), ("keep_last", C.c_int32),
-                ("prealloc_files", C.c_int32), ("reserved", C.c_int32 * 4)]
+                ("prealloc_files", C.c_int32), ("direct_min_bytes", C.c_uint64), ("reserved", C.c_int32 * 2)]
 
 
 class ckpt_layout(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("n_tensors", "header_bytes", "data_bytes", "file_bytes", "payload_bytes", "n_tiles",
-                                          "n_chunks", "n_superchunks", "dma_chunk_bytes", "pack_superchunk_bytes", "tile_bytes")]
+                                          "n_chunks", "n_superchunks", "dma_chunk_bytes", "pack_superchunk_bytes", "tile_bytes",
+                                          "n_segments", "n_direct_tensors", "direct_bytes", "direct_data_bytes")]
 
 
 class ckpt_tile(C.Structure):
     _fields_ = [("src", C.c_uint64), ("dst_off", C.c_uint64), ("copy_bytes", C.c_uint32), ("total_bytes", C.c_uint32),
                 ("reserved", C.c_uint64)]
+
+
+CKPT_SEG_STAGED, CKPT_SEG_DIRECT, CKPT_SEG_ZERO = 0, 1, 2
+
+
+class ckpt_segment(C.Structure):
+    _fields_ = [("data_off", C.c_uint64), ("nbytes", C.c_uint64), ("src", C.c_uint64), ("kind", C.c_uint32), ("tensor", C.c_uint32)]
 
 
 class ckpt_stats(C.Structure):
@@ -75,6 +83,8 @@ _SIGS = {
     "ckpt_plan_offsets": (C.c_int, [_vp, C.POINTER(_u64), C.c_size_t]),
     "ckpt_plan_tiles": (C.c_int, [_vp, _u64, _u64, C.POINTER(ckpt_tile)]),
     "ckpt_plan_superchunk_tiles": (C.c_int, [_vp, C.POINTER(_u64), C.c_size_t]),
+    "ckpt_plan_segments": (C.c_int, [_vp, _u64, _u64, C.POINTER(ckpt_segment)]),
+    "ckpt_plan_chunk_segments": (C.c_int, [_vp, C.POINTER(_u64), C.c_size_t]),
     "ckpt_plan_destroy": (None, [_vp]),
     "ckpt_init": (C.c_int, [C.POINTER(ckpt_config), C.POINTER(_vp)]),
     "ckpt_register_tensors": (C.c_int, [_vp, C.POINTER(ckpt_tensor_desc), C.c_size_t]),
@@ -133,7 +143,7 @@ def _struct_dict(s):
 
 def make_config(out_dir="", device=0, host_ring_bytes=0, dma_chunk_bytes=0, pack_superchunk_bytes=0, dev_staging_bytes=0,
                 n_dma_streams=0, n_io_threads=0, window_policy=CKPT_WINDOW_D2H, o_direct=0, fsync_on_commit=0,
-                io_mode=CKPT_IO_AUTO, keep_last=0, prealloc_files=0):
+                io_mode=CKPT_IO_AUTO, keep_last=0, prealloc_files=0, direct_min_bytes=0):
     cfg = ckpt_config()
     cfg.device = device
     cfg.out_dir = os.fsencode(out_dir) if out_dir else None
@@ -149,6 +159,7 @@ def make_config(out_dir="", device=0, host_ring_bytes=0, dma_chunk_bytes=0, pack
     cfg.io_mode = io_mode
     cfg.keep_last = keep_last
     cfg.prealloc_files = prealloc_files
+    cfg.direct_min_bytes = direct_min_bytes
     return cfg
 
 
@@ -202,6 +213,18 @@ class Plan:
         n = self.layout()["n_superchunks"] + 1
         out = (_u64 * n)()
         _check(lib.ckpt_plan_superchunk_tiles(self._h, out, n))
+        return list(out)
+
+    def segments(self):
+        n = self.layout()["n_segments"]
+        out = (ckpt_segment * max(1, n))()
+        _check(lib.ckpt_plan_segments(self._h, 0, n, out))
+        return out[:n]
+
+    def chunk_segments(self):
+        n = self.layout()["n_chunks"] + 1
+        out = (_u64 * n)()
+        _check(lib.ckpt_plan_chunk_segments(self._h, out, n))
         return list(out)
 
     def close(self):

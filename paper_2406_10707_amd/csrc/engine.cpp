@@ -396,6 +396,9 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
     }
 
     if ((e = hipStreamWaitEvent(c->pack_stream, s->ev_boundary, 0)) != hipSuccess) hip_fail("wait boundary", e);
+    if (p.n_direct)   // these copies read the tensors themselves
+        for (size_t k = 0; k < nk; k++)
+            if ((e = hipStreamWaitEvent(c->dma[k], s->ev_boundary, 0)) != hipSuccess) hip_fail("wait boundary", e);
     double bp_ms = 0;
     // Pack launches run `ahead` super-chunks in front of the copies: as far as staging allows when the
     // window closes with the last pack (policy PACK: get the reads of the tensors over with), two
@@ -443,8 +446,18 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
             }
             const uint64_t nbytes = p.chunk_bytes(ch);
             if (ch == 0 && (e = hipEventRecord(c->ev_first_copy, c->dma[k])) != hipSuccess) hip_fail("record", e);
-            e = hipMemcpyAsync(c->ring + slot * CH, stage_base + (ch * CH - sc * SC), nbytes, hipMemcpyDeviceToHost, c->dma[k]);
-            if (e != hipSuccess) hip_fail("hipMemcpyAsync D2H", e);
+            // the chunk's segments: packed bytes out of staging, large tensors out of their own memory,
+            // the padding behind those zero-filled here (the slot belongs to this thread until the copy event)
+            uint8_t *slot_base = c->ring + slot * CH;
+            for (uint64_t j = p.chunk_first_seg[ch]; j < p.chunk_first_seg[ch + 1]; j++) {
+                const ckpt_segment &sg = p.segs[j];
+                uint8_t *dst = slot_base + (sg.data_off - ch * CH);
+                if (sg.kind == CKPT_SEG_ZERO) { memset(dst, 0, sg.nbytes); continue; }
+                const void *src = sg.kind == CKPT_SEG_DIRECT ? reinterpret_cast<const void *>(sg.src)
+                                                             : static_cast<const void *>(stage_base + (sg.data_off - sc * SC));
+                e = hipMemcpyAsync(dst, src, sg.nbytes, hipMemcpyDeviceToHost, c->dma[k]);
+                if (e != hipSuccess) hip_fail("hipMemcpyAsync D2H", e);
+            }
             if ((e = hipEventRecord(c->ev_slot[slot], c->dma[k])) != hipSuccess) hip_fail("record", e);
             const bool last = ch + 1 == p.n_chunks;
             if (ch + 1 == c1)
@@ -522,6 +535,10 @@ static void fill_layout(const Plan &p, ckpt_layout *o) {
     o->dma_chunk_bytes = p.cfg.dma_chunk_bytes;
     o->pack_superchunk_bytes = p.cfg.pack_superchunk_bytes;
     o->tile_bytes = kTileBytes;
+    o->n_segments = p.segs.size();
+    o->n_direct_tensors = p.n_direct;
+    o->direct_bytes = p.direct_bytes;
+    o->direct_data_bytes = p.direct_data_bytes;
 }
 
 int ckpt_plan_layout(const ckpt_plan *plan, ckpt_layout *out) {
@@ -558,6 +575,22 @@ int ckpt_plan_superchunk_tiles(const ckpt_plan *plan, uint64_t *out, size_t cap)
     if (!plan || !out) return fail(CKPT_EINVAL, "null argument");
     const auto &v = plan->plan.sc_first_tile;
     if (cap < v.size()) return fail(CKPT_EINVAL, "buffer smaller than n_superchunks + 1");
+    memcpy(out, v.data(), v.size() * sizeof(uint64_t));
+    return CKPT_OK;
+}
+
+int ckpt_plan_segments(const ckpt_plan *plan, uint64_t first, uint64_t count, ckpt_segment *out) {
+    if (!plan || !out) return fail(CKPT_EINVAL, "null argument");
+    const auto &v = plan->plan.segs;
+    if (first > v.size() || count > v.size() - first) return fail(CKPT_EINVAL, "segment range out of bounds");
+    memcpy(out, v.data() + first, count * sizeof(ckpt_segment));
+    return CKPT_OK;
+}
+
+int ckpt_plan_chunk_segments(const ckpt_plan *plan, uint64_t *out, size_t cap) {
+    if (!plan || !out) return fail(CKPT_EINVAL, "null argument");
+    const auto &v = plan->plan.chunk_first_seg;
+    if (cap < v.size()) return fail(CKPT_EINVAL, "buffer smaller than n_chunks + 1");
     memcpy(out, v.data(), v.size() * sizeof(uint64_t));
     return CKPT_OK;
 }
@@ -813,6 +846,7 @@ int ckpt_set_window_policy(ckpt_ctx *c, int32_t policy) {
     if (policy != CKPT_WINDOW_D2H && policy != CKPT_WINDOW_PACK) return fail(CKPT_EINVAL, "unknown window_policy");
     std::lock_guard<std::mutex> lk(c->mu);
     if (c->last_snap && !c->last_snap->window_closed) return fail(CKPT_ESTATE, "a snapshot's window is still open");
+    if (policy == CKPT_WINDOW_PACK && c->cfg.direct_min_bytes) return fail(CKPT_EINVAL, "direct_min_bytes needs window_policy CKPT_WINDOW_D2H");
     c->cfg.window_policy = policy;
     return CKPT_OK;
 }
@@ -909,6 +943,8 @@ static int restore_body(ckpt_ctx *c, int fd, const char *path, hipStream_t strea
     // earlier work on the caller's stream (which may read or write the tensors) comes first
     HIP_TRY(c, hipEventRecord(c->ev_user, stream));
     HIP_TRY(c, hipStreamWaitEvent(c->pack_stream, c->ev_user, 0));
+    if (p.n_direct)   // these copies write the tensors themselves
+        for (size_t k = 0; k < nk; k++) HIP_TRY(c, hipStreamWaitEvent(c->dma[k], c->ev_user, 0));
 
     uint64_t &issued = *issued_out;   // chunks whose file read has been handed to the I/O threads
     auto issue_reads_upto = [&](uint64_t upto) -> int {
@@ -946,7 +982,13 @@ static int restore_body(ckpt_ctx *c, int fd, const char *path, hipStream_t strea
                 if (c->async_code) { g_last_error = c->async_err; return c->async_code; }
             }
             const size_t k = ch % nk;
-            HIP_TRY(c, hipMemcpyAsync(stage_base + (ch * CH - sc * SC), c->ring + slot * CH, p.chunk_bytes(ch), hipMemcpyHostToDevice, c->dma[k]));
+            const uint8_t *slot_base = c->ring + slot * CH;
+            for (uint64_t j = p.chunk_first_seg[ch]; j < p.chunk_first_seg[ch + 1]; j++) {
+                const ckpt_segment &sg = p.segs[j];
+                if (sg.kind == CKPT_SEG_ZERO) continue;
+                void *dst = sg.kind == CKPT_SEG_DIRECT ? reinterpret_cast<void *>(sg.src) : static_cast<void *>(stage_base + (sg.data_off - sc * SC));
+                HIP_TRY(c, hipMemcpyAsync(dst, slot_base + (sg.data_off - ch * CH), sg.nbytes, hipMemcpyHostToDevice, c->dma[k]));
+            }
             HIP_TRY(c, hipEventRecord(c->ev_slot[slot], c->dma[k]));
         }
         for (size_t k = 0; k < nk; k++) {
@@ -958,6 +1000,11 @@ static int restore_body(ckpt_ctx *c, int fd, const char *path, hipStream_t strea
         HIP_TRY(c, hipEventRecord(c->ev_packed[sc], c->pack_stream));
     }
     HIP_TRY(c, hipStreamWaitEvent(stream, c->ev_packed[p.n_superchunks - 1], 0));
+    if (p.n_direct)   // the last copies into large tensors are not followed by a scatter kernel
+        for (size_t k = 0; k < nk; k++) {
+            HIP_TRY(c, hipEventRecord(c->ev_job_tail[k], c->dma[k]));
+            HIP_TRY(c, hipStreamWaitEvent(stream, c->ev_job_tail[k], 0));
+        }
     if (iter_out) *iter_out = f_iter;
     return CKPT_OK;
 }

@@ -30,6 +30,9 @@ int resolve_config(const ckpt_config *in, ResolvedConfig *out, std::string *err)
     c.io_mode = in->io_mode;
     c.keep_last = in->keep_last;
     c.prealloc_files = in->prealloc_files;
+    c.direct_min_bytes = in->direct_min_bytes;
+    if (c.direct_min_bytes != 0 && c.direct_min_bytes < kAlign) { *err = "config: direct_min_bytes must be 0 or at least 4096"; return CKPT_EINVAL; }
+    if (c.direct_min_bytes != 0 && in->window_policy != CKPT_WINDOW_D2H) { *err = "config: direct_min_bytes needs window_policy CKPT_WINDOW_D2H"; return CKPT_EINVAL; }
     if (c.keep_last < 0 || c.prealloc_files < 0 || c.prealloc_files > 16) { *err = "config: keep_last must be >= 0 and prealloc_files 0..16"; return CKPT_EINVAL; }
     if (c.prealloc_files > 0 && c.keep_last == 0) { *err = "config: prealloc_files needs keep_last > 0"; return CKPT_EINVAL; }
     if (c.io_mode == CKPT_IO_AUTO) c.io_mode = c.o_direct ? CKPT_IO_PWRITE : CKPT_IO_MMAP;
@@ -79,6 +82,8 @@ int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cf
         t.dev_addr = uint64_t(d.dev_ptr);
         t.nbytes = d.nbytes;
         t.file_off = 0;
+        t.direct = cfg.direct_min_bytes != 0 && d.nbytes >= cfg.direct_min_bytes;
+        if (t.direct) { p.n_direct++; p.direct_bytes += d.nbytes; p.direct_data_bytes += align_up(d.nbytes, kAlign); }
         table += 2 + len + 2 + 8ull * d.ndim + 16;
         p.payload_bytes += d.nbytes;
         p.tensors.push_back(std::move(t));
@@ -122,7 +127,7 @@ int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cf
     for (const auto &t : p.tensors) {
         uint64_t d0 = t.file_off - p.header_bytes;             // data-region offset of the tensor
         uint64_t dend = d0 + align_up(t.nbytes, kAlign);
-        uint64_t pos = d0;
+        uint64_t pos = t.direct ? dend : d0;                   // a direct tensor has no tiles
         while (pos < dend) {
             uint64_t stop = (pos / kTileBytes + 1) * kTileBytes;
             if (stop > dend) stop = dend;
@@ -140,34 +145,109 @@ int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cf
         }
     }
     while (next_sc <= p.n_superchunks) p.sc_first_tile[next_sc++] = p.tiles.size();
+
+    // copy segments: what the DMA engines move for each chunk. Packed extents (payload and padding)
+    // come from staging and merge into one segment per run; a direct tensor's payload comes from the
+    // tensor itself and its padding is zero-filled on the host. Everything is cut at chunk boundaries.
+    p.chunk_first_seg.assign(p.n_chunks + 1, 0);
+    uint64_t next_ch = 0;
+    auto emit = [&](uint64_t a, uint64_t b, uint32_t kind, uint64_t src, uint32_t tensor) {
+        while (a < b) {
+            uint64_t stop = (a / CH + 1) * CH;
+            if (stop > b) stop = b;
+            while (next_ch < p.n_chunks && a >= next_ch * CH) p.chunk_first_seg[next_ch++] = p.segs.size();
+            const bool chunk_start = a % CH == 0;
+            if (kind == CKPT_SEG_STAGED && !chunk_start && !p.segs.empty() && p.segs.back().kind == CKPT_SEG_STAGED &&
+                p.segs.back().data_off + p.segs.back().nbytes == a) {
+                p.segs.back().nbytes += stop - a;
+            } else {
+                ckpt_segment sg;
+                sg.data_off = a;
+                sg.nbytes = stop - a;
+                sg.src = kind == CKPT_SEG_DIRECT ? src : 0;
+                sg.kind = kind;
+                sg.tensor = kind == CKPT_SEG_STAGED ? 0 : tensor;
+                p.segs.push_back(sg);
+            }
+            if (kind == CKPT_SEG_DIRECT) src += stop - a;
+            a = stop;
+        }
+    };
+    for (size_t k = 0; k < p.tensors.size(); k++) {
+        const TensorInfo &t = p.tensors[k];
+        const uint64_t d0 = t.file_off - p.header_bytes, dend = d0 + align_up(t.nbytes, kAlign);
+        if (t.direct) {
+            emit(d0, d0 + t.nbytes, CKPT_SEG_DIRECT, t.dev_addr, uint32_t(k));
+            emit(d0 + t.nbytes, dend, CKPT_SEG_ZERO, 0, uint32_t(k));
+        } else {
+            emit(d0, dend, CKPT_SEG_STAGED, 0, 0);
+        }
+    }
+    while (next_ch <= p.n_chunks) p.chunk_first_seg[next_ch++] = p.segs.size();
     if (!verify_plan(p, err)) return CKPT_EINVAL;
     *out = std::move(p);
     return CKPT_OK;
 }
 
 bool verify_plan(const Plan &p, std::string *err) {
-    const uint64_t SC = p.cfg.pack_superchunk_bytes;
-    uint64_t expect = 0;
-    size_t k = 0;  // tensor the tile should belong to
+    const uint64_t SC = p.cfg.pack_superchunk_bytes, CH = p.cfg.dma_chunk_bytes;
     if (p.sc_first_tile.size() != p.n_superchunks + 1 || p.sc_first_tile.back() != p.tiles.size()) { *err = "plan: super-chunk tile index broken"; return false; }
-    for (size_t i = 0; i < p.tiles.size(); i++) {
-        const ckpt_tile &t = p.tiles[i];
-        if (t.dst_off != expect || t.total_bytes == 0 || t.total_bytes % 16 || t.dst_off % 16 || t.copy_bytes > t.total_bytes ||
-            t.total_bytes > kTileBytes) { *err = "plan: tile " + std::to_string(i) + " malformed"; return false; }
-        if (t.dst_off / SC != (t.dst_off + t.total_bytes - 1) / SC) { *err = "plan: tile crosses a super-chunk"; return false; }
-        while (k < p.tensors.size() && t.dst_off >= p.tensors[k].file_off - p.header_bytes + align_up(p.tensors[k].nbytes, kAlign)) k++;
-        if (k >= p.tensors.size()) { *err = "plan: tile beyond last tensor"; return false; }
+    if (p.chunk_first_seg.size() != p.n_chunks + 1 || p.chunk_first_seg.back() != p.segs.size()) { *err = "plan: chunk segment index broken"; return false; }
+    // tiles: the padded extent of every packed tensor is covered exactly, in order; none elsewhere
+    size_t i = 0;
+    for (size_t k = 0; k < p.tensors.size(); k++) {
         const TensorInfo &ti = p.tensors[k];
-        uint64_t rel = t.dst_off - (ti.file_off - p.header_bytes);
-        if (t.copy_bytes) {
-            if (t.src != ti.dev_addr + rel || rel + t.copy_bytes > ti.nbytes) { *err = "plan: tile source outside its tensor"; return false; }
+        if (ti.direct) continue;
+        const uint64_t d0 = ti.file_off - p.header_bytes, dend = d0 + align_up(ti.nbytes, kAlign);
+        uint64_t expect = d0;
+        while (expect < dend) {
+            if (i >= p.tiles.size()) { *err = "plan: tiles end before the last packed tensor"; return false; }
+            const ckpt_tile &t = p.tiles[i];
+            if (t.dst_off != expect || t.total_bytes == 0 || t.total_bytes % 16 || t.dst_off % 16 || t.copy_bytes > t.total_bytes ||
+                t.total_bytes > kTileBytes) { *err = "plan: tile " + std::to_string(i) + " malformed"; return false; }
+            if (t.dst_off / SC != (t.dst_off + t.total_bytes - 1) / SC) { *err = "plan: tile crosses a super-chunk"; return false; }
+            const uint64_t rel = t.dst_off - d0;
+            if (t.copy_bytes && (t.src != ti.dev_addr + rel || rel + t.copy_bytes > ti.nbytes)) { *err = "plan: tile source outside its tensor"; return false; }
+            if (!t.copy_bytes && rel < ti.nbytes) { *err = "plan: tile drops payload"; return false; }
+            if (t.copy_bytes && t.copy_bytes < t.total_bytes && rel + t.copy_bytes != ti.nbytes) { *err = "plan: tile pads inside the payload"; return false; }
+            if (t.dst_off + t.total_bytes > dend) { *err = "plan: tile crosses a tensor boundary"; return false; }
+            const uint64_t s = t.dst_off / SC;
+            if (i < p.sc_first_tile[s] || i >= p.sc_first_tile[s + 1]) { *err = "plan: tile not in its super-chunk's range"; return false; }
+            expect += t.total_bytes;
+            i++;
         }
-        if (rel + t.total_bytes > align_up(ti.nbytes, kAlign)) { *err = "plan: tile crosses a tensor boundary"; return false; }
-        uint64_t s = t.dst_off / SC;
-        if (i < p.sc_first_tile[s] || i >= p.sc_first_tile[s + 1]) { *err = "plan: tile not in its super-chunk's range"; return false; }
-        expect += t.total_bytes;
     }
-    if (expect != p.data_bytes) { *err = "plan: tiles do not cover the data region"; return false; }
+    if (i != p.tiles.size()) { *err = "plan: tiles beyond the packed tensors"; return false; }
+    // segments: partition of the data region; per tensor the kinds and sources must fit
+    uint64_t pos = 0;
+    size_t k = 0;
+    for (size_t j = 0; j < p.segs.size(); j++) {
+        const ckpt_segment &sg = p.segs[j];
+        if (sg.data_off != pos || sg.nbytes == 0) { *err = "plan: segment " + std::to_string(j) + " out of order or empty"; return false; }
+        if (sg.data_off / CH != (sg.data_off + sg.nbytes - 1) / CH) { *err = "plan: segment crosses a chunk"; return false; }
+        const uint64_t ch = sg.data_off / CH;
+        if (j < p.chunk_first_seg[ch] || j >= p.chunk_first_seg[ch + 1]) { *err = "plan: segment not in its chunk's range"; return false; }
+        // every tensor the segment touches
+        uint64_t a = sg.data_off;
+        const uint64_t b = sg.data_off + sg.nbytes;
+        while (a < b) {
+            while (k < p.tensors.size() && a >= p.tensors[k].file_off - p.header_bytes + align_up(p.tensors[k].nbytes, kAlign)) k++;
+            if (k >= p.tensors.size()) { *err = "plan: segment beyond last tensor"; return false; }
+            const TensorInfo &ti = p.tensors[k];
+            const uint64_t d0 = ti.file_off - p.header_bytes, dend = d0 + align_up(ti.nbytes, kAlign);
+            const uint64_t stop = b < dend ? b : dend;
+            if (!ti.direct) {
+                if (sg.kind != CKPT_SEG_STAGED) { *err = "plan: packed tensor under a non-staged segment"; return false; }
+            } else if (sg.kind == CKPT_SEG_DIRECT) {
+                if (sg.tensor != k || b > d0 + ti.nbytes || sg.src != ti.dev_addr + (sg.data_off - d0)) { *err = "plan: direct segment outside its tensor"; return false; }
+            } else if (sg.kind == CKPT_SEG_ZERO) {
+                if (sg.tensor != k || sg.data_off < d0 + ti.nbytes || b > dend) { *err = "plan: zero segment outside its tensor's padding"; return false; }
+            } else { *err = "plan: direct tensor under a staged segment"; return false; }
+            a = stop;
+        }
+        pos = b;
+    }
+    if (pos != p.data_bytes) { *err = "plan: segments do not cover the data region"; return false; }
     return true;
 }
 

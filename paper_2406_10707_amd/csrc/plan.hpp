@@ -20,10 +20,11 @@ struct TensorInfo {
     uint64_t dev_addr;
     uint64_t nbytes;
     uint64_t file_off;
+    bool direct = false;   // copied by the DMA engines from its own memory, not packed
 };
 
 struct ResolvedConfig {
-    uint64_t host_ring_bytes, dma_chunk_bytes, pack_superchunk_bytes, dev_staging_bytes;
+    uint64_t host_ring_bytes, dma_chunk_bytes, pack_superchunk_bytes, dev_staging_bytes, direct_min_bytes;
     int n_dma_streams, n_io_threads, window_policy, o_direct, fsync_on_commit, io_mode, keep_last, prealloc_files;
 };
 
@@ -32,9 +33,11 @@ struct Plan {
     std::vector<TensorInfo> tensors;
     std::vector<uint8_t> header;          // header_bytes long, iter field zero
     uint64_t header_bytes = 0, data_bytes = 0, payload_bytes = 0;
-    std::vector<ckpt_tile> tiles;         // ordered by dst_off
+    std::vector<ckpt_tile> tiles;         // ordered by dst_off; none inside a direct tensor
     std::vector<uint64_t> sc_first_tile;  // n_superchunks + 1
-    uint64_t n_chunks = 0, n_superchunks = 0;
+    std::vector<ckpt_segment> segs;       // ordered by data_off, partition of the data region
+    std::vector<uint64_t> chunk_first_seg;  // n_chunks + 1
+    uint64_t n_chunks = 0, n_superchunks = 0, n_direct = 0, direct_bytes = 0, direct_data_bytes = 0;
 
     uint64_t file_bytes() const { return header_bytes + data_bytes; }
     uint64_t chunk_bytes(uint64_t c) const {      // last chunk may be short (still a 4 KiB multiple)
@@ -51,7 +54,8 @@ uint64_t dtype_size(int32_t dtype);
 // Fills `cfg` defaults and checks it; returns CKPT_OK or CKPT_EINVAL with `err` set.
 int resolve_config(const ckpt_config *in, ResolvedConfig *out, std::string *err);
 int build_plan(const ckpt_tensor_desc *tensors, size_t n, const ResolvedConfig &cfg, Plan *out, std::string *err);
-// Re-checks every tile against the plan's own tensors and super-chunks (defence before any launch).
+// Re-checks every tile and copy segment against the plan's own tensors, chunks and super-chunks
+// (defence before any launch or copy).
 bool verify_plan(const Plan &p, std::string *err);
 
 }  // namespace dsllm

@@ -46,8 +46,11 @@ static std::vector<uint8_t> read_file(const std::string &p) {
     return out;
 }
 
-static int scenario(const std::string &dir, int policy, int keep_last, int io_mode, uint64_t ring_bytes, uint64_t staging_bytes, int n_tensors) {
-    std::string what = "policy " + std::to_string(policy) + " keep_last " + std::to_string(keep_last) + " io_mode " + std::to_string(io_mode);
+static int scenario(const std::string &dir, int policy, int keep_last, int io_mode, uint64_t ring_bytes, uint64_t staging_bytes, int n_tensors,
+                    uint64_t direct_min = 0) {
+    std::string what = "policy " + std::to_string(policy) + " keep_last " + std::to_string(keep_last) + " io_mode " + std::to_string(io_mode) +
+                       " direct_min " + std::to_string(direct_min);
+    const std::string title = what;
     std::vector<Tensor> ts;
     for (int k = 0; k < n_tensors; k++) {
         Tensor t;
@@ -83,6 +86,7 @@ static int scenario(const std::string &dir, int policy, int keep_last, int io_mo
     cfg.io_mode = io_mode;
     cfg.keep_last = keep_last;
     cfg.prealloc_files = keep_last ? 1 : 0;
+    cfg.direct_min_bytes = direct_min;
     ckpt_ctx *ctx = nullptr;
     REQUIRE(ckpt_init(&cfg, &ctx) == CKPT_OK);
     REQUIRE(ckpt_register_tensors(ctx, descs.data(), descs.size()) == CKPT_OK);
@@ -150,9 +154,9 @@ static int scenario(const std::string &dir, int policy, int keep_last, int io_mo
     ckpt_plan_destroy(plan);
     hipStreamDestroy(compute);
     for (auto &t : ts) free(t.base);
-    printf("ok %s: %d tensors, %llu data bytes, %llu super-chunks, %llu chunks\n",
-           ("policy " + std::to_string(policy) + " keep_last " + std::to_string(keep_last) + " io_mode " + std::to_string(io_mode)).c_str(),
-           n_tensors, (unsigned long long)lay.data_bytes, (unsigned long long)lay.n_superchunks, (unsigned long long)lay.n_chunks);
+    printf("ok %s: %d tensors (%llu direct), %llu data bytes, %llu super-chunks, %llu chunks, %llu segments\n", title.c_str(),
+           n_tensors, (unsigned long long)lay.n_direct_tensors, (unsigned long long)lay.data_bytes, (unsigned long long)lay.n_superchunks,
+           (unsigned long long)lay.n_chunks, (unsigned long long)lay.n_segments);
     return 0;
 }
 
@@ -170,5 +174,9 @@ int main(int argc, char **argv) {
     if (scenario(sub(), CKPT_WINDOW_PACK, 1, CKPT_IO_MMAP, 512 << 10, 64 << 20, 60)) return 1;
     // update released after the pack with only two staging slots (packs depend on copies)
     if (scenario(sub(), CKPT_WINDOW_PACK, 0, CKPT_IO_PWRITE, 128 << 10, 0, 40)) return 1;
+    // hybrid: tensors of 30000 bytes and more are copied out of (and on restore into) their own memory
+    if (scenario(sub(), CKPT_WINDOW_D2H, 1, CKPT_IO_MMAP, 256 << 10, 0, 60, 30000)) return 1;
+    // hybrid with everything direct that may be: the pack kernel sees only what is under 4 KiB
+    if (scenario(sub(), CKPT_WINDOW_D2H, 0, CKPT_IO_PWRITE, 128 << 10, 0, 60, 4096)) return 1;
     return 0;
 }

@@ -109,6 +109,81 @@ def test_tile_table_reproduces_the_data_region(config, chunk, superchunk):
     plan.close()
 
 
+@pytest.mark.parametrize("config", [1, 5])
+@pytest.mark.parametrize("direct_min", [0, 4096, 20000, 1 << 20])
+def test_segments_reproduce_the_data_region(config, direct_min):
+    """The hybrid plan on the host: tiles fill a staging image (holes where large tensors are copied
+    directly), then every chunk is put together from its segments the way the copy engine would:
+    STAGED out of staging, DIRECT out of the tensor's own memory, ZERO by the host. The result must
+    be the oracle's data region, and no segment may cross a chunk."""
+    chunk, superchunk = 64 << 10, 256 << 10
+    spec = shards.make_shard(config, tiny=True)
+    descs, span = _fake_descs(spec)
+    mem = np.full(span + 64, 0xEE, dtype=np.uint8)
+    host = []
+    for k, (name, dtype, shape, p, nb) in enumerate(descs):
+        v = shards.host_values(spec, k)
+        mem[p - FAKE_BASE:p - FAKE_BASE + nb] = v
+        host.append(v)
+    plan = B.Plan(descs, B.make_config(dma_chunk_bytes=chunk, pack_superchunk_bytes=superchunk, direct_min_bytes=direct_min))
+    lay = plan.layout()
+    big = [k for k, d in enumerate(descs) if direct_min and d[4] >= direct_min]
+    assert lay["n_direct_tensors"] == len(big) and lay["direct_bytes"] == sum(descs[k][4] for k in big)
+    staging = np.full(lay["data_bytes"], 0xCC, dtype=np.uint8)       # 0xCC: never written by a pack kernel
+    packed = np.zeros(lay["data_bytes"], dtype=bool)
+    for t in plan.tiles():
+        s = t.src - FAKE_BASE
+        staging[t.dst_off:t.dst_off + t.copy_bytes] = mem[s:s + t.copy_bytes]
+        staging[t.dst_off + t.copy_bytes:t.dst_off + t.total_bytes] = 0
+        assert not packed[t.dst_off:t.dst_off + t.total_bytes].any()
+        packed[t.dst_off:t.dst_off + t.total_bytes] = True
+    segs, first = plan.segments(), plan.chunk_segments()
+    assert first[0] == 0 and first[-1] == len(segs) == lay["n_segments"] and len(first) == lay["n_chunks"] + 1
+    out = np.full(lay["data_bytes"], 0x77, dtype=np.uint8)
+    pos = 0
+    kinds = set()
+    for ch in range(lay["n_chunks"]):
+        assert first[ch] < first[ch + 1]
+        for j in range(first[ch], first[ch + 1]):
+            sg = segs[j]
+            assert sg.data_off == pos and sg.nbytes > 0 and sg.data_off // chunk == ch == (sg.data_off + sg.nbytes - 1) // chunk
+            a, b = sg.data_off, sg.data_off + sg.nbytes
+            kinds.add(sg.kind)
+            if sg.kind == B.CKPT_SEG_STAGED:
+                assert packed[a:b].all()
+                out[a:b] = staging[a:b]
+            elif sg.kind == B.CKPT_SEG_DIRECT:
+                assert not packed[a:b].any() and sg.tensor in big
+                assert descs[sg.tensor][3] <= sg.src and sg.src + sg.nbytes <= descs[sg.tensor][3] + descs[sg.tensor][4]
+                out[a:b] = mem[sg.src - FAKE_BASE:sg.src - FAKE_BASE + sg.nbytes]
+            else:
+                assert sg.kind == B.CKPT_SEG_ZERO and not packed[a:b].any() and sg.nbytes < 4096
+                out[a:b] = 0
+            pos = b
+    assert pos == lay["data_bytes"]
+    if direct_min == 0:
+        assert kinds == {B.CKPT_SEG_STAGED} and len(segs) == lay["n_chunks"]
+    elif direct_min == 4096:
+        assert B.CKPT_SEG_DIRECT in kinds and lay["n_direct_tensors"] > 0
+    ots = [(t.name, t.dtype, t.shape, h) for t, h in zip(spec.tensors, host)]
+    assert out.tobytes() == oracle.serialize_bytes(ots, 0)[lay["header_bytes"]:]
+    plan.close()
+
+
+def test_full_size_hybrid_plan_counts():
+    """Llama-7B with everything of 1 MiB and more copied directly: only the norm weights are packed."""
+    spec = shards.make_shard(2)
+    descs, _ = _fake_descs(spec)
+    plan = B.Plan(descs, B.make_config(direct_min_bytes=1 << 20))
+    lay = plan.layout()
+    small = [d for d in descs if d[4] < (1 << 20)]
+    assert lay["n_direct_tensors"] == len(descs) - len(small) and 0 < len(small) < len(descs)
+    assert len(small) <= lay["n_tiles"] <= 2 * len(small)      # 8 and 16 KiB norm weights: one or two tiles each
+    assert lay["direct_bytes"] == sum(d[4] for d in descs) - sum(d[4] for d in small)
+    assert lay["n_segments"] <= lay["n_chunks"] + 3 * len(descs)
+    plan.close()
+
+
 def test_full_size_tile_counts():
     spec = shards.make_shard(2)
     descs, _ = _fake_descs(spec)
@@ -128,6 +203,8 @@ def _expect(code, descs, **cfg):
 def test_bad_descriptions_and_configs_are_rejected():
     ok = ("t", B.CKPT_F32, (4,), FAKE_BASE, 16)
     B.Plan([ok]).close()
+    _expect(B.CKPT_EINVAL, [ok], direct_min_bytes=100)                        # below one alignment unit
+    _expect(B.CKPT_EINVAL, [ok], direct_min_bytes=4096, window_policy=B.CKPT_WINDOW_PACK)
     _expect(B.CKPT_EINVAL, [("t", 9, (4,), FAKE_BASE, 16)])                   # unknown dtype
     _expect(B.CKPT_EINVAL, [("t", B.CKPT_F32, (4,), FAKE_BASE, 12)])          # nbytes != dtype x shape
     _expect(B.CKPT_EINVAL, [("t", B.CKPT_F32, (0,), FAKE_BASE, 0)])           # empty tensor
