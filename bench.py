@@ -53,6 +53,8 @@ def parse_args():
                          "memory, only smaller ones are packed (0: everything is packed)")
     ap.add_argument("--out-dir", default="")
     ap.add_argument("--baseline-steps", type=int, default=6)
+    ap.add_argument("--baseline-discard-s", type=float, default=4.0,
+                    help="seconds of steps run and discarded at the start of each no-checkpoint baseline phase")
     ap.add_argument("--oracle-sample-gb", type=float, default=8.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-restore", action="store_true")
@@ -155,13 +157,20 @@ def main():
         shutil.rmtree(out_dir, ignore_errors=True)
 
 
+def say(msg):
+    """Progress line on stderr (stdout carries the one JSON line)."""
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
 def run(args, B, harness, spec, every, compute_ms, out_dir):
     info = B.proxy_device_info()
     stream = harness.make_compute_stream()
+    say("link peak and copy-kernel ceiling")
     link = measure_link_peak(B, harness, stream)
     devcopy_gbps = measure_devcopy(B, harness, stream)
 
     shard = harness.DeviceShard(spec)
+    say(f"shard {spec.name}: fill on device")
     shard.fill_device(stream)
     stream.synchronize()
     gemm = harness.GemmProxy(8192)
@@ -190,6 +199,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                         window_policy=policy, direct_min_bytes=int(args.direct_min_mib * (1 << 20)),
                         io_mode={"auto": B.CKPT_IO_AUTO, "pwrite": B.CKPT_IO_PWRITE, "mmap": B.CKPT_IO_MMAP}[args.io_mode],
                         keep_last=args.keep_last, prealloc_files=args.prealloc if args.keep_last else 0)
+    say("ckpt_init + ckpt_register_tensors (ring pinned and touched, spare files pre-allocated)")
     t0 = time.perf_counter()
     ck = B.Checkpointer(cfg)
     ck.register_tensors(shard.descs())
@@ -231,8 +241,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         """Same steps with checkpointing off: (median step ms, median GEMM-phase ms). After an idle period
         the card runs a few per cent faster for some seconds, so the first ~4 s of steps are discarded."""
         marks = []
-        skip = max(2, int(4000.0 / max(compute_ms, 1.0)) + 1)
-        skip = min(skip, 40)
+        skip = min(max(2, int(args.baseline_discard_s * 1000.0 / max(compute_ms, 1.0)) + 1), 40) if args.baseline_discard_s > 0 else 0
         for i in range(skip + n):
             iteration(1000000 + i, False, marks)
         stream.synchronize()
@@ -310,9 +319,13 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
             "gemm_slowdown_pct": round(100.0 * (statistics.median(busy) / ref_gemm - 1), 3) if busy else None}, ref_gemm
 
     # ---- baseline before; warm-up (untimed); the timed region of exactly K steps
+    say("baseline phase (no checkpoints)")
     base_before = baseline_phase(args.baseline_steps)
+    say(f"warm-up, {args.warmup} steps")
     region(args.warmup)
+    say(f"timed region, {args.steps} steps")
     main = region(args.steps)
+    say("drain, restore check")
     ms_per_step = main["wall_s"] * 1e3 / args.steps
 
     # ---- drain (the paper counts pending flushes in end-to-end time; reported, not part of the K steps)
@@ -341,6 +354,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     paired = None
     if every == 1 and args.paired_blocks > 0:
         ck.flush()
+        say("alternating blocks of checkpointed and quiet steps")
         block_len = max(5, min(20, int(1000.0 / max(compute_ms, 1.0) + 0.999)))
         alt = alternating_phase(args.paired_blocks, block_len)
         ck.flush()
@@ -355,6 +369,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     # ---- variant: window released after the pack (policy PACK, staging holds the whole data region)
     variant = None
     if want_variant:
+        say(f"variant: window policy PACK, {args.variant_steps} steps")
         ck.set_window_policy(B.CKPT_WINDOW_PACK)
         if state["step"] % every:                        # start the variant right after a multiple of the interval
             region(every - state["step"] % every)
@@ -364,6 +379,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         ck.set_window_policy(B.CKPT_WINDOW_D2H)
 
     # ---- baseline after; GEMM speed drifts a few per cent with temperature, so before and after are averaged
+    say("baseline phase (no checkpoints)")
     base_after = baseline_phase(args.baseline_steps)
     base_iter_ms = 0.5 * (base_before[0] + base_after[0])
     base_gemm_ms = 0.5 * (base_before[1] + base_after[1])
@@ -451,6 +467,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     if restore_result:
         result["restore"] = restore_result
     if not args.no_cpu_baseline:
+        say("oracle on the host cores (bounded sample)")
         result["cpu_baseline"] = cpu_baseline(harness, shard, int(args.oracle_sample_gb * 1e9), out_dir)
     ck.destroy()
     print(json.dumps(result), flush=True)
