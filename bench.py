@@ -51,6 +51,9 @@ def parse_args():
     ap.add_argument("--direct-min-mib", type=float, default=0.0,
                     help="hybrid path: tensors of at least this size are copied by the DMA engines straight out of their own "
                          "memory, only smaller ones are packed (0: everything is packed)")
+    ap.add_argument("--tier2-dir", default="", help="second, slower storage tier: committed files are copied on to this directory in the background")
+    ap.add_argument("--tier2-threads", type=int, default=4)
+    ap.add_argument("--tier2-direct", type=int, default=1, help="1: second-tier files are written with O_DIRECT")
     ap.add_argument("--out-dir", default="")
     ap.add_argument("--baseline-steps", type=int, default=6)
     ap.add_argument("--baseline-discard-s", type=float, default=4.0,
@@ -203,6 +206,10 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     t0 = time.perf_counter()
     ck = B.Checkpointer(cfg)
     ck.register_tensors(shard.descs())
+    tier2_dir = ""
+    if args.tier2_dir:
+        tier2_dir = tempfile.mkdtemp(prefix="dsllm_tier2_", dir=args.tier2_dir)
+        ck.enable_second_tier(tier2_dir, n_threads=args.tier2_threads, o_direct=args.tier2_direct, keep_last=1)
     init_s = time.perf_counter() - t0
     lay = ck.layout()
     S = lay["data_bytes"]
@@ -464,12 +471,28 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     ratio = traffic_ratio()
     if ratio and pack_launches:
         result["roofline"]["traffic"] = round(ratio * result["roofline"]["bytes_per_launch"])
+    if tier2_dir:
+        say("second tier: waiting for the last copy")
+        t0 = time.perf_counter()
+        ck.wait_second_tier()
+        t2_wait = time.perf_counter() - t0
+        t2 = [ck.stats(it) for it in requested]
+        done = [s for s in t2 if s["tier2_state"] == B.CKPT_TIER2_DONE]
+        result["second_tier"] = {
+            "dir": args.tier2_dir, "threads": args.tier2_threads, "o_direct": args.tier2_direct,
+            "snapshots": len(t2), "copied": len(done), "superseded": sum(s["tier2_state"] == B.CKPT_TIER2_SKIPPED for s in t2),
+            "failed": sum(s["tier2_state"] == B.CKPT_TIER2_FAILED for s in t2),
+            "copy_gbps": round(statistics.median(s["file_bytes"] / (s["host_tier2_ms"] * 1e-3) / 1e9 for s in done), 3) if done else None,
+            "copy_seconds": round(statistics.median(s["host_tier2_ms"] for s in done) / 1e3, 2) if done else None,
+            "wait_after_run_s": round(t2_wait, 2)}
     if restore_result:
         result["restore"] = restore_result
     if not args.no_cpu_baseline:
         say("oracle on the host cores (bounded sample)")
         result["cpu_baseline"] = cpu_baseline(harness, shard, int(args.oracle_sample_gb * 1e9), out_dir)
     ck.destroy()
+    if tier2_dir:
+        shutil.rmtree(tier2_dir, ignore_errors=True)
     print(json.dumps(result), flush=True)
 
 

@@ -137,6 +137,16 @@ typedef struct {
     uint32_t tensor;     /* DIRECT, ZERO: registration index of the tensor; otherwise 0 */
 } ckpt_segment;
 
+/* Where a snapshot stands with respect to the second storage tier (ckpt_enable_second_tier). */
+typedef enum {
+    CKPT_TIER2_NONE = 0,     /* no second tier, or not committed to the first tier yet */
+    CKPT_TIER2_QUEUED = 1,   /* committed; the newest snapshot waiting for the second tier */
+    CKPT_TIER2_COPYING = 2,
+    CKPT_TIER2_DONE = 3,     /* whole, fsync'ed and renamed in the second-tier directory */
+    CKPT_TIER2_SKIPPED = 4,  /* a newer snapshot was committed before the second tier got to this one */
+    CKPT_TIER2_FAILED = 5
+} ckpt_tier2_state;
+
 /* Per-snapshot measurements. Times in milliseconds on the device timeline (HIP events) unless
  * marked host. A field is -1 while not yet known. */
 typedef struct {
@@ -144,7 +154,7 @@ typedef struct {
     uint64_t payload_bytes, data_bytes, file_bytes;
     int32_t d2h_done, committed;      /* 1 once the last copy has landed / the file has its final name */
     int32_t pack_launches;
-    int32_t reserved0;
+    int32_t tier2_state;              /* ckpt_tier2_state */
     double pack_ms_sum;               /* sum over pack launches of (end - start) on the pack stream */
     double request_to_d2h_end_ms;     /* boundary event on the caller's stream -> last copy done */
     double d2h_span_ms;               /* first copy start -> last copy done */
@@ -156,6 +166,7 @@ typedef struct {
     double host_flush_span_ms;        /* host: first chunk on the host -> file renamed (the flush proper) */
     double host_io_wait_ms_sum;       /* host: summed over I/O threads, time waiting for chunks' copy events */
     double host_io_copy_ms_sum;       /* host: summed over I/O threads, time writing ring slots to the file */
+    double host_tier2_ms;             /* host: copy of the committed file to the second tier, open to rename (-1: none yet) */
 } ckpt_stats;
 
 #define CKPT_ITER_ALL UINT64_MAX
@@ -223,6 +234,25 @@ int ckpt_flush(ckpt_ctx *ctx, uint64_t iter);
  * iter_out may be NULL. CKPT_ESTATE while a snapshot is in flight. */
 int ckpt_restore(ckpt_ctx *ctx, const char *path, void *hip_stream, uint64_t *iter_out);
 
+/* The paper's multi-level flush, one level further: out_dir is the fast tier (host memory file system
+ * or node-local NVMe) that absorbs checkpoints at the speed of the host link; every file committed
+ * there is then copied, by a thread of its own and without holding up training or later snapshots,
+ * to `dir` on slower, durable storage (n_threads writers, default 2, each moving 8 MiB blocks;
+ * o_direct != 0 opens the copy with O_DIRECT; always fsync'ed before it gets its final name, the same
+ * name as in out_dir). The slower tier takes the newest committed snapshot whenever it is free; one
+ * that is still waiting when a newer one is committed is skipped (CKPT_TIER2_SKIPPED), so the second
+ * tier lags by at most one copy. With retention in the fast tier (keep_last > 0) the file being
+ * copied is exempt from recycling until the copy is over. keep_last here: second-tier files kept
+ * (0: all). To be called after ckpt_init and before the first snapshot; CKPT_ESTATE otherwise. */
+int ckpt_enable_second_tier(ckpt_ctx *ctx, const char *dir, int32_t n_threads, int32_t o_direct, int32_t keep_last);
+/* Blocks until the snapshot of `iter` is durable in the second tier (CKPT_OK), was skipped
+ * (CKPT_ESTATE) or failed; with CKPT_ITER_ALL until the second tier has nothing left to do. Failures
+ * of second-tier copies are kept apart from those of the snapshot path: the first one is returned
+ * here (CKPT_EIO) and cleared, or by ckpt_destroy; ckpt_flush and ckpt_snapshot_async never report them. */
+int ckpt_wait_second_tier(ckpt_ctx *ctx, uint64_t iter);
+/* Writes "<second-tier dir>/ckpt_iter<20 digits>.dsl" into buf. */
+int ckpt_second_tier_file_name(ckpt_ctx *ctx, uint64_t iter, char *buf, size_t cap);
+
 int ckpt_get_layout(ckpt_ctx *ctx, ckpt_layout *out);
 /* Measurements of one requested snapshot; CKPT_EINVAL if unknown. Device-timeline fields are filled
  * once d2h_done is set. */
@@ -233,7 +263,7 @@ int ckpt_file_name(ckpt_ctx *ctx, uint64_t iter, char *buf, size_t cap);
 /* Text of the calling thread's last error; library-owned, valid until that thread's next failing call. */
 const char *ckpt_last_error(void);
 
-/* Drains every pending snapshot (as ckpt_flush(ALL)), stops the threads, frees ring, staging,
+/* Drains every pending snapshot (as ckpt_flush(ALL)) and the second tier, stops the threads, frees ring, staging,
  * streams and events. */
 int ckpt_destroy(ckpt_ctx *ctx);
 

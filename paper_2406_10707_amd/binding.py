@@ -55,11 +55,14 @@ class ckpt_segment(C.Structure):
 
 class ckpt_stats(C.Structure):
     _fields_ = [("iter", C.c_uint64), ("payload_bytes", C.c_uint64), ("data_bytes", C.c_uint64), ("file_bytes", C.c_uint64),
-                ("d2h_done", C.c_int32), ("committed", C.c_int32), ("pack_launches", C.c_int32), ("reserved0", C.c_int32),
+                ("d2h_done", C.c_int32), ("committed", C.c_int32), ("pack_launches", C.c_int32), ("tier2_state", C.c_int32),
                 ("pack_ms_sum", C.c_double), ("request_to_d2h_end_ms", C.c_double), ("d2h_span_ms", C.c_double),
                 ("request_to_pack_end_ms", C.c_double), ("host_submit_ms", C.c_double), ("host_request_to_commit_ms", C.c_double),
                 ("host_backpressure_ms", C.c_double), ("host_snapshot_call_ms", C.c_double),
-                ("host_flush_span_ms", C.c_double), ("host_io_wait_ms_sum", C.c_double), ("host_io_copy_ms_sum", C.c_double)]
+                ("host_flush_span_ms", C.c_double), ("host_io_wait_ms_sum", C.c_double), ("host_io_copy_ms_sum", C.c_double),
+                ("host_tier2_ms", C.c_double)]
+
+CKPT_TIER2_NONE, CKPT_TIER2_QUEUED, CKPT_TIER2_COPYING, CKPT_TIER2_DONE, CKPT_TIER2_SKIPPED, CKPT_TIER2_FAILED = range(6)
 
 
 class CkptError(RuntimeError):
@@ -93,6 +96,9 @@ _SIGS = {
     "ckpt_set_window_policy": (C.c_int, [_vp, _i32]),
     "ckpt_flush": (C.c_int, [_vp, _u64]),
     "ckpt_restore": (C.c_int, [_vp, C.c_char_p, _vp, C.POINTER(_u64)]),
+    "ckpt_enable_second_tier": (C.c_int, [_vp, C.c_char_p, _i32, _i32, _i32]),
+    "ckpt_wait_second_tier": (C.c_int, [_vp, _u64]),
+    "ckpt_second_tier_file_name": (C.c_int, [_vp, _u64, C.c_char_p, C.c_size_t]),
     "ckpt_get_layout": (C.c_int, [_vp, C.POINTER(ckpt_layout)]),
     "ckpt_get_stats": (C.c_int, [_vp, _u64, C.POINTER(ckpt_stats)]),
     "ckpt_file_name": (C.c_int, [_vp, _u64, C.c_char_p, C.c_size_t]),
@@ -275,6 +281,17 @@ class Checkpointer:
         out = ckpt_stats()
         _check(lib.ckpt_get_stats(self._h, it, C.byref(out)))
         return _struct_dict(out)
+
+    def enable_second_tier(self, directory, n_threads=0, o_direct=0, keep_last=1):
+        _check(lib.ckpt_enable_second_tier(self._h, os.fsencode(directory), n_threads, o_direct, keep_last))
+
+    def wait_second_tier(self, it=CKPT_ITER_ALL):
+        _check(lib.ckpt_wait_second_tier(self._h, it))
+
+    def second_tier_file_name(self, it):
+        buf = C.create_string_buffer(4096)
+        _check(lib.ckpt_second_tier_file_name(self._h, it, buf, 4096))
+        return os.fsdecode(buf.value)
 
     def file_name(self, it):
         buf = C.create_string_buffer(4096)

@@ -47,9 +47,9 @@ static std::vector<uint8_t> read_file(const std::string &p) {
 }
 
 static int scenario(const std::string &dir, int policy, int keep_last, int io_mode, uint64_t ring_bytes, uint64_t staging_bytes, int n_tensors,
-                    uint64_t direct_min = 0) {
+                    uint64_t direct_min = 0, bool second_tier = false) {
     std::string what = "policy " + std::to_string(policy) + " keep_last " + std::to_string(keep_last) + " io_mode " + std::to_string(io_mode) +
-                       " direct_min " + std::to_string(direct_min);
+                       " direct_min " + std::to_string(direct_min) + (second_tier ? " second tier" : "");
     const std::string title = what;
     std::vector<Tensor> ts;
     for (int k = 0; k < n_tensors; k++) {
@@ -90,6 +90,14 @@ static int scenario(const std::string &dir, int policy, int keep_last, int io_mo
     ckpt_ctx *ctx = nullptr;
     REQUIRE(ckpt_init(&cfg, &ctx) == CKPT_OK);
     REQUIRE(ckpt_register_tensors(ctx, descs.data(), descs.size()) == CKPT_OK);
+    const std::string dir2 = dir + "/tier2";
+    if (second_tier) {
+        mkdir(dir2.c_str(), 0755);
+        REQUIRE(ckpt_wait_second_tier(ctx, CKPT_ITER_ALL) == CKPT_ESTATE);      // not enabled yet
+        REQUIRE(ckpt_enable_second_tier(ctx, dir.c_str(), 2, 0, 1) == CKPT_EINVAL);   // same directory as the first tier
+        REQUIRE(ckpt_enable_second_tier(ctx, dir2.c_str(), 2, 0, 1) == CKPT_OK);
+        REQUIRE(ckpt_enable_second_tier(ctx, dir2.c_str(), 2, 0, 1) == CKPT_ESTATE);
+    }
     ckpt_layout lay;
     REQUIRE(ckpt_get_layout(ctx, &lay) == CKPT_OK);
     ckpt_plan *plan = nullptr;
@@ -127,6 +135,24 @@ static int scenario(const std::string &dir, int policy, int keep_last, int io_mo
         REQUIRE(got == expect[it]);
         ckpt_stats st;
         REQUIRE(ckpt_get_stats(ctx, uint64_t(it), &st) == CKPT_OK && st.committed == 1 && st.d2h_done == 1);
+    }
+    if (second_tier) {
+        // the slower tier ends with the newest snapshot, whole; older ones were copied or skipped, never torn
+        what = "second tier";
+        REQUIRE(ckpt_wait_second_tier(ctx, CKPT_ITER_ALL) == CKPT_OK);
+        int done = 0;
+        for (int it = 1; it <= iters; it++) {
+            ckpt_stats st;
+            REQUIRE(ckpt_get_stats(ctx, uint64_t(it), &st) == CKPT_OK);
+            REQUIRE(st.tier2_state == CKPT_TIER2_DONE || st.tier2_state == CKPT_TIER2_SKIPPED);
+            REQUIRE((st.tier2_state == CKPT_TIER2_DONE) == (ckpt_wait_second_tier(ctx, uint64_t(it)) == CKPT_OK));
+            done += st.tier2_state == CKPT_TIER2_DONE;
+            REQUIRE(ckpt_second_tier_file_name(ctx, uint64_t(it), name, sizeof name) == CKPT_OK);
+            std::vector<uint8_t> got = read_file(name);
+            if (it == iters) { REQUIRE(st.tier2_state == CKPT_TIER2_DONE && got == expect[it]); }
+            else REQUIRE(got.empty());      // second-tier retention keeps one file
+        }
+        printf("   second tier: %d of %d snapshots copied, the others superseded\n", done, iters);
     }
     // restore the newest file into poisoned tensors; bytes around the tensors must stay untouched
     for (auto &t : ts) memset(t.base, 0xA5, (t.lead + t.nbytes + 15) / 16 * 16);
@@ -176,6 +202,10 @@ int main(int argc, char **argv) {
     if (scenario(sub(), CKPT_WINDOW_PACK, 0, CKPT_IO_PWRITE, 128 << 10, 0, 40)) return 1;
     // hybrid: tensors of 30000 bytes and more are copied out of (and on restore into) their own memory
     if (scenario(sub(), CKPT_WINDOW_D2H, 1, CKPT_IO_MMAP, 256 << 10, 0, 60, 30000)) return 1;
+    // second tier behind a recycling first tier (the file being copied on must not be recycled under the copy)
+    if (scenario(sub(), CKPT_WINDOW_D2H, 1, CKPT_IO_MMAP, 256 << 10, 0, 60, 0, true)) return 1;
+    // second tier behind a first tier that keeps every file (read back by path)
+    if (scenario(sub(), CKPT_WINDOW_D2H, 0, CKPT_IO_PWRITE, 256 << 10, 0, 40, 0, true)) return 1;
     // hybrid with everything direct that may be: the pack kernel sees only what is under 4 KiB
     if (scenario(sub(), CKPT_WINDOW_D2H, 0, CKPT_IO_PWRITE, 128 << 10, 0, 60, 4096)) return 1;
     return 0;
