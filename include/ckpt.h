@@ -43,12 +43,21 @@ typedef enum {
 
 typedef enum { CKPT_BF16 = 1, CKPT_F32 = 2, CKPT_F16 = 3, CKPT_U8 = 4, CKPT_I32 = 5, CKPT_I64 = 6 } ckpt_dtype;
 
+/* Placement flag, OR'ed into ckpt_tensor_desc.dtype: the object lives in HOST memory (the paper's
+ * heterogeneous state: host-resident tensors of an offloaded optimizer, and small non-tensor objects
+ * such as generator state or serialized arguments, registered as CKPT_U8 blobs of a fixed size).
+ * dev_ptr is then a host address. Such an object is read inside ckpt_snapshot_async, before the call
+ * returns (the caller may change it right afterwards; nothing orders host memory with the stream), and
+ * written inside ckpt_restore, before that call returns. It takes its place in the file like any
+ * other tensor; the file does not record where a tensor lived. */
+#define CKPT_PLACE_HOST 0x100
+
 /* One tensor of the shard. Caller-owned; the library copies name and shape at registration.
  * dev_ptr must be aligned to the element size only. The memory must stay allocated, at this
  * address, for as long as the registration lives. */
 typedef struct {
     const char *name;      /* UTF-8, NUL-terminated, 1..65535 bytes */
-    int32_t dtype;         /* ckpt_dtype */
+    int32_t dtype;         /* ckpt_dtype, optionally | CKPT_PLACE_HOST */
     uint32_t ndim;         /* 0..8; 0 = scalar */
     const int64_t *shape;  /* ndim entries, each >= 0 */
     void *dev_ptr;         /* device address of the first element (ignored by ckpt_plan_create) */
@@ -110,6 +119,8 @@ typedef struct {
     uint64_t n_segments;                           /* copy segments per snapshot (>= n_chunks) */
     uint64_t n_direct_tensors, direct_bytes;       /* tensors copied without the pack kernel, and their payload */
     uint64_t direct_data_bytes;                    /* the same tensors' share of the data region (payload + padding) */
+    uint64_t n_host_objects, host_bytes;           /* host-resident objects (CKPT_PLACE_HOST) and their payload */
+    uint64_t host_data_bytes;                      /* their share of the data region */
 } ckpt_layout;
 
 /* One pack work item: `copy_bytes` bytes from device address `src` go to offset `dst_off` of the data
@@ -125,16 +136,17 @@ typedef struct {
 
 /* One piece of a DMA chunk. The segments of a chunk partition it, in order. STAGED: the bytes come
  * from (go to, on restore) device staging, where the pack kernel put them; DIRECT: they are `nbytes`
- * bytes of a registered tensor at device address `src`; ZERO: the padding behind a DIRECT tensor,
- * zero-filled in the ring slot by the host and skipped on restore. Without direct_min_bytes every
- * chunk is one STAGED segment. */
-typedef enum { CKPT_SEG_STAGED = 0, CKPT_SEG_DIRECT = 1, CKPT_SEG_ZERO = 2 } ckpt_segment_kind;
+ * bytes of a registered tensor at device address `src`; HOST: bytes of a host-resident object at host
+ * address `src`, copied by the CPU; ZERO: the padding behind a DIRECT or HOST tensor, zero-filled in
+ * the ring slot by the host and skipped on restore. Without direct_min_bytes and host-resident
+ * objects every chunk is one STAGED segment. */
+typedef enum { CKPT_SEG_STAGED = 0, CKPT_SEG_DIRECT = 1, CKPT_SEG_ZERO = 2, CKPT_SEG_HOST = 3 } ckpt_segment_kind;
 typedef struct {
     uint64_t data_off;   /* offset in the data region */
     uint64_t nbytes;
-    uint64_t src;        /* DIRECT: device address; otherwise 0 */
+    uint64_t src;        /* DIRECT: device address; HOST: host address; otherwise 0 */
     uint32_t kind;       /* ckpt_segment_kind */
-    uint32_t tensor;     /* DIRECT, ZERO: registration index of the tensor; otherwise 0 */
+    uint32_t tensor;     /* DIRECT, HOST, ZERO: registration index of the tensor; otherwise 0 */
 } ckpt_segment;
 
 /* Where a snapshot stands with respect to the second storage tier (ckpt_enable_second_tier). */

@@ -38,7 +38,8 @@ class ckpt_config(C.Structure):
 class ckpt_layout(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("n_tensors", "header_bytes", "data_bytes", "file_bytes", "payload_bytes", "n_tiles",
                                           "n_chunks", "n_superchunks", "dma_chunk_bytes", "pack_superchunk_bytes", "tile_bytes",
-                                          "n_segments", "n_direct_tensors", "direct_bytes", "direct_data_bytes")]
+                                          "n_segments", "n_direct_tensors", "direct_bytes", "direct_data_bytes",
+                                          "n_host_objects", "host_bytes", "host_data_bytes")]
 
 
 class ckpt_tile(C.Structure):
@@ -46,7 +47,8 @@ class ckpt_tile(C.Structure):
                 ("reserved", C.c_uint64)]
 
 
-CKPT_SEG_STAGED, CKPT_SEG_DIRECT, CKPT_SEG_ZERO = 0, 1, 2
+CKPT_SEG_STAGED, CKPT_SEG_DIRECT, CKPT_SEG_ZERO, CKPT_SEG_HOST = 0, 1, 2, 3
+CKPT_PLACE_HOST = 0x100
 
 
 class ckpt_segment(C.Structure):

@@ -80,6 +80,7 @@ struct Snap {
     double call_ms = 0, backpressure_ms = 0;
     std::atomic<uint64_t> io_wait_us{0}, io_copy_us{0};   // summed over the I/O threads
     double pack_ms_sum = -1, req_to_d2h_end_ms = -1, d2h_span_ms = -1, req_to_pack_end_ms = -1;
+    std::vector<uint8_t> host_capture;      // the host-resident objects as they were when the snapshot was requested
     int tier2_state = CKPT_TIER2_NONE;      // ckpt_tier2_state
     double tier2_ms = -1;                   // host: copy to the second tier, open to rename
 };
@@ -598,6 +599,11 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
                 const ckpt_segment &sg = p.segs[j];
                 uint8_t *dst = slot_base + (sg.data_off - ch * CH);
                 if (sg.kind == CKPT_SEG_ZERO) { memset(dst, 0, sg.nbytes); continue; }
+                if (sg.kind == CKPT_SEG_HOST) {   // from the copy taken at the request
+                    const TensorInfo &ti = p.tensors[sg.tensor];
+                    memcpy(dst, s->host_capture.data() + ti.capture_off + (sg.src - ti.dev_addr), sg.nbytes);
+                    continue;
+                }
                 const void *src = sg.kind == CKPT_SEG_DIRECT ? reinterpret_cast<const void *>(sg.src)
                                                              : static_cast<const void *>(stage_base + (sg.data_off - sc * SC));
                 e = hipMemcpyAsync(dst, src, sg.nbytes, hipMemcpyDeviceToHost, c->dma[k]);
@@ -626,6 +632,7 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
         }
         if (sc + ahead < p.n_superchunks) enqueue_pack(sc + ahead);
     }
+    std::vector<uint8_t>().swap(s->host_capture);   // every byte of it is in a ring slot by now
     std::lock_guard<std::mutex> lk(c->mu);
     s->backpressure_ms = bp_ms;
     s->t_submitted = Clock::now();
@@ -684,6 +691,9 @@ static void fill_layout(const Plan &p, ckpt_layout *o) {
     o->n_direct_tensors = p.n_direct;
     o->direct_bytes = p.direct_bytes;
     o->direct_data_bytes = p.direct_data_bytes;
+    o->n_host_objects = p.n_host;
+    o->host_bytes = p.host_bytes;
+    o->host_data_bytes = p.host_data_bytes;
 }
 
 int ckpt_plan_layout(const ckpt_plan *plan, ckpt_layout *out) {
@@ -825,6 +835,7 @@ int ckpt_register_tensors(ckpt_ctx *c, const ckpt_tensor_desc *tensors, size_t n
     if (r) return fail(r, err);
     // every source range must be device memory of this GPU: checked here, once, before any launch
     for (const auto &t : p.tensors) {
+        if (t.host) continue;   // host-resident object: the caller vouches for the range
         hipPointerAttribute_t attr;
         hipError_t e = hipPointerGetAttributes(&attr, reinterpret_cast<void *>(t.dev_addr));
         if (e != hipSuccess || attr.type != hipMemoryTypeDevice || attr.device != c->device) {
@@ -942,6 +953,11 @@ int ckpt_snapshot_async(ckpt_ctx *c, uint64_t iter, void *stream) {
     sp->tmp_path = sp->final_path + ".tmp";
     sp->chunks_left = c->plan.n_chunks;
     sp->t_request = t0;
+    if (c->plan.n_host) {   // host memory is not ordered with the stream: read it now, the caller may change it after this call
+        sp->host_capture.resize(c->plan.host_bytes);
+        for (const auto &t : c->plan.tensors)
+            if (t.host) memcpy(sp->host_capture.data() + t.capture_off, reinterpret_cast<const void *>(t.dev_addr), t.nbytes);
+    }
     HIP_TRY(c, hipEventCreate(&sp->ev_boundary));
     hipError_t e = hipEventRecord(sp->ev_boundary, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) { (void)hipEventDestroy(sp->ev_boundary); return fail(CKPT_EHIP, std::string("record boundary: ") + hipGetErrorString(e)); }
@@ -1192,6 +1208,10 @@ static int restore_body(ckpt_ctx *c, int fd, const char *path, hipStream_t strea
             for (uint64_t j = p.chunk_first_seg[ch]; j < p.chunk_first_seg[ch + 1]; j++) {
                 const ckpt_segment &sg = p.segs[j];
                 if (sg.kind == CKPT_SEG_ZERO) continue;
+                if (sg.kind == CKPT_SEG_HOST) {   // the slot has been read: host objects are put back by this thread
+                    memcpy(reinterpret_cast<void *>(sg.src), slot_base + (sg.data_off - ch * CH), sg.nbytes);
+                    continue;
+                }
                 void *dst = sg.kind == CKPT_SEG_DIRECT ? reinterpret_cast<void *>(sg.src) : static_cast<void *>(stage_base + (sg.data_off - sc * SC));
                 HIP_TRY(c, hipMemcpyAsync(dst, slot_base + (sg.data_off - ch * CH), sg.nbytes, hipMemcpyHostToDevice, c->dma[k]));
             }

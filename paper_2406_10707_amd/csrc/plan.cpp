@@ -63,7 +63,9 @@ int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cf
     uint64_t table = 0;
     for (size_t k = 0; k < n; k++) {
         const ckpt_tensor_desc &d = descs[k];
-        uint64_t es = dtype_size(d.dtype);
+        const bool host = (d.dtype & CKPT_PLACE_HOST) != 0;
+        const int32_t dtype = d.dtype & ~CKPT_PLACE_HOST;
+        uint64_t es = dtype_size(dtype);
         size_t len = d.name ? strlen(d.name) : 0;
         if (len < 1 || len > 65535) { *err = "tensor " + std::to_string(k) + ": name must be 1..65535 bytes"; return CKPT_EINVAL; }
         if (es == 0) { *err = std::string("tensor ") + d.name + ": unknown dtype"; return CKPT_EINVAL; }
@@ -76,13 +78,15 @@ int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cf
             t.shape.push_back(d.shape[i]);
         }
         if (d.nbytes == 0 || d.nbytes != numel * es) { *err = std::string("tensor ") + d.name + ": nbytes must be > 0 and equal dtype size x shape"; return CKPT_EINVAL; }
-        if (uint64_t(d.dev_ptr) % es != 0) { *err = std::string("tensor ") + d.name + ": address not aligned to its element size"; return CKPT_EINVAL; }
+        if (!host && uint64_t(d.dev_ptr) % es != 0) { *err = std::string("tensor ") + d.name + ": address not aligned to its element size"; return CKPT_EINVAL; }
         t.name.assign(d.name, len);
-        t.dtype = d.dtype;
+        t.dtype = dtype;
+        t.host = host;
         t.dev_addr = uint64_t(d.dev_ptr);
         t.nbytes = d.nbytes;
         t.file_off = 0;
-        t.direct = cfg.direct_min_bytes != 0 && d.nbytes >= cfg.direct_min_bytes;
+        t.direct = !host && cfg.direct_min_bytes != 0 && d.nbytes >= cfg.direct_min_bytes;
+        if (host) { t.capture_off = p.host_bytes; p.n_host++; p.host_bytes += d.nbytes; p.host_data_bytes += align_up(d.nbytes, kAlign); }
         if (t.direct) { p.n_direct++; p.direct_bytes += d.nbytes; p.direct_data_bytes += align_up(d.nbytes, kAlign); }
         table += 2 + len + 2 + 8ull * d.ndim + 16;
         p.payload_bytes += d.nbytes;
@@ -127,7 +131,7 @@ int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cf
     for (const auto &t : p.tensors) {
         uint64_t d0 = t.file_off - p.header_bytes;             // data-region offset of the tensor
         uint64_t dend = d0 + align_up(t.nbytes, kAlign);
-        uint64_t pos = t.direct ? dend : d0;                   // a direct tensor has no tiles
+        uint64_t pos = t.direct || t.host ? dend : d0;         // direct tensors and host objects have no tiles
         while (pos < dend) {
             uint64_t stop = (pos / kTileBytes + 1) * kTileBytes;
             if (stop > dend) stop = dend;
@@ -164,20 +168,20 @@ int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cf
                 ckpt_segment sg;
                 sg.data_off = a;
                 sg.nbytes = stop - a;
-                sg.src = kind == CKPT_SEG_DIRECT ? src : 0;
+                sg.src = kind == CKPT_SEG_DIRECT || kind == CKPT_SEG_HOST ? src : 0;
                 sg.kind = kind;
                 sg.tensor = kind == CKPT_SEG_STAGED ? 0 : tensor;
                 p.segs.push_back(sg);
             }
-            if (kind == CKPT_SEG_DIRECT) src += stop - a;
+            if (kind == CKPT_SEG_DIRECT || kind == CKPT_SEG_HOST) src += stop - a;
             a = stop;
         }
     };
     for (size_t k = 0; k < p.tensors.size(); k++) {
         const TensorInfo &t = p.tensors[k];
         const uint64_t d0 = t.file_off - p.header_bytes, dend = d0 + align_up(t.nbytes, kAlign);
-        if (t.direct) {
-            emit(d0, d0 + t.nbytes, CKPT_SEG_DIRECT, t.dev_addr, uint32_t(k));
+        if (t.direct || t.host) {
+            emit(d0, d0 + t.nbytes, t.host ? CKPT_SEG_HOST : CKPT_SEG_DIRECT, t.dev_addr, uint32_t(k));
             emit(d0 + t.nbytes, dend, CKPT_SEG_ZERO, 0, uint32_t(k));
         } else {
             emit(d0, dend, CKPT_SEG_STAGED, 0, 0);
@@ -197,7 +201,7 @@ bool verify_plan(const Plan &p, std::string *err) {
     size_t i = 0;
     for (size_t k = 0; k < p.tensors.size(); k++) {
         const TensorInfo &ti = p.tensors[k];
-        if (ti.direct) continue;
+        if (ti.direct || ti.host) continue;
         const uint64_t d0 = ti.file_off - p.header_bytes, dend = d0 + align_up(ti.nbytes, kAlign);
         uint64_t expect = d0;
         while (expect < dend) {
@@ -236,9 +240,9 @@ bool verify_plan(const Plan &p, std::string *err) {
             const TensorInfo &ti = p.tensors[k];
             const uint64_t d0 = ti.file_off - p.header_bytes, dend = d0 + align_up(ti.nbytes, kAlign);
             const uint64_t stop = b < dend ? b : dend;
-            if (!ti.direct) {
+            if (!ti.direct && !ti.host) {
                 if (sg.kind != CKPT_SEG_STAGED) { *err = "plan: packed tensor under a non-staged segment"; return false; }
-            } else if (sg.kind == CKPT_SEG_DIRECT) {
+            } else if (sg.kind == (ti.host ? CKPT_SEG_HOST : CKPT_SEG_DIRECT)) {
                 if (sg.tensor != k || b > d0 + ti.nbytes || sg.src != ti.dev_addr + (sg.data_off - d0)) { *err = "plan: direct segment outside its tensor"; return false; }
             } else if (sg.kind == CKPT_SEG_ZERO) {
                 if (sg.tensor != k || sg.data_off < d0 + ti.nbytes || b > dend) { *err = "plan: zero segment outside its tensor's padding"; return false; }

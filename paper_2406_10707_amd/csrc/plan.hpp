@@ -21,6 +21,8 @@ struct TensorInfo {
     uint64_t nbytes;
     uint64_t file_off;
     bool direct = false;   // copied by the DMA engines from its own memory, not packed
+    bool host = false;     // lives in host memory: captured by the CPU at the request, not packed
+    uint64_t capture_off = 0;   // host objects: offset in a snapshot's capture buffer
 };
 
 struct ResolvedConfig {
@@ -38,6 +40,7 @@ struct Plan {
     std::vector<ckpt_segment> segs;       // ordered by data_off, partition of the data region
     std::vector<uint64_t> chunk_first_seg;  // n_chunks + 1
     uint64_t n_chunks = 0, n_superchunks = 0, n_direct = 0, direct_bytes = 0, direct_data_bytes = 0;
+    uint64_t n_host = 0, host_bytes = 0, host_data_bytes = 0;
 
     uint64_t file_bytes() const { return header_bytes + data_bytes; }
     uint64_t chunk_bytes(uint64_t c) const {      // last chunk may be short (still a 4 KiB multiple)

@@ -31,7 +31,7 @@ static uint64_t rnd() {
         if (!(cond)) { printf("FAILED %s line %d: %s (%s)\n", #cond, __LINE__, ckpt_last_error(), what.c_str()); return 1; } \
     } while (0)
 
-struct Tensor { uint8_t *base; uint64_t lead, nbytes; std::string name; int64_t shape; };
+struct Tensor { uint8_t *base; uint64_t lead, nbytes; std::string name; int64_t shape; bool host = false; };
 
 static std::vector<uint8_t> read_file(const std::string &p) {
     std::vector<uint8_t> out;
@@ -47,9 +47,9 @@ static std::vector<uint8_t> read_file(const std::string &p) {
 }
 
 static int scenario(const std::string &dir, int policy, int keep_last, int io_mode, uint64_t ring_bytes, uint64_t staging_bytes, int n_tensors,
-                    uint64_t direct_min = 0, bool second_tier = false) {
+                    uint64_t direct_min = 0, bool second_tier = false, bool host_objects = false) {
     std::string what = "policy " + std::to_string(policy) + " keep_last " + std::to_string(keep_last) + " io_mode " + std::to_string(io_mode) +
-                       " direct_min " + std::to_string(direct_min) + (second_tier ? " second tier" : "");
+                       " direct_min " + std::to_string(direct_min) + (second_tier ? " second tier" : "") + (host_objects ? " host objects" : "");
     const std::string title = what;
     std::vector<Tensor> ts;
     for (int k = 0; k < n_tensors; k++) {
@@ -63,6 +63,7 @@ static int scenario(const std::string &dir, int policy, int keep_last, int io_mo
         }
         t.base = static_cast<uint8_t *>(aligned_alloc(16, (t.lead + t.nbytes + 15) / 16 * 16));
         for (uint64_t i = 0; i < t.lead + t.nbytes; i++) t.base[i] = uint8_t(rnd());
+        t.host = host_objects && k % 7 == 3;      // every seventh object lives on the "host": the caller owns it, no stream orders it
         t.name = "t" + std::to_string(k);
         t.shape = int64_t(t.nbytes);
         ts.push_back(t);
@@ -70,7 +71,7 @@ static int scenario(const std::string &dir, int policy, int keep_last, int io_mo
     std::vector<ckpt_tensor_desc> descs;
     for (auto &t : ts) {
         ckpt_tensor_desc d{};
-        d.name = t.name.c_str(); d.dtype = CKPT_U8; d.ndim = 1; d.shape = &t.shape; d.dev_ptr = t.base + t.lead; d.nbytes = t.nbytes;
+        d.name = t.name.c_str(); d.dtype = CKPT_U8 | (t.host ? CKPT_PLACE_HOST : 0); d.ndim = 1; d.shape = &t.shape; d.dev_ptr = t.base + t.lead; d.nbytes = t.nbytes;
         descs.push_back(d);
     }
     ckpt_config cfg{};
@@ -111,17 +112,21 @@ static int scenario(const std::string &dir, int policy, int keep_last, int io_mo
     std::vector<std::vector<uint8_t>> expect(iters + 1);
     for (int it = 1; it <= iters; it++) {
         // forward/backward stand-in: reads every tensor (must be allowed to overlap the snapshot)
-        emu_submit(compute, [&ts] { volatile uint64_t sum = 0; for (auto &t : ts) for (uint64_t i = 0; i < t.nbytes; i += 64) sum = sum + t.base[t.lead + i]; });
+        emu_submit(compute, [&ts] { volatile uint64_t sum = 0; for (auto &t : ts) if (!t.host) for (uint64_t i = 0; i < t.nbytes; i += 64) sum = sum + t.base[t.lead + i]; });
         REQUIRE(ckpt_wait_immutable_window_end(ctx, compute, 0) == CKPT_OK);
         // update: mutates every byte, then the expected image of this boundary is taken, in stream order
-        emu_submit(compute, [&ts, it] { for (auto &t : ts) for (uint64_t i = 0; i < t.nbytes; i++) t.base[t.lead + i] = uint8_t(t.base[t.lead + i] * 31 + it); });
+        emu_submit(compute, [&ts, it] { for (auto &t : ts) if (!t.host) for (uint64_t i = 0; i < t.nbytes; i++) t.base[t.lead + i] = uint8_t(t.base[t.lead + i] * 31 + it); });
         std::vector<uint8_t> *img = &expect[it];
+        img->assign(lay.file_bytes, 0);
         emu_submit(compute, [&ts, &offs, &lay, plan, img, it] {
-            img->assign(lay.file_bytes, 0);
             ckpt_plan_header(plan, uint64_t(it), img->data(), lay.header_bytes);
-            for (size_t k = 0; k < ts.size(); k++) memcpy(img->data() + offs[k], ts[k].base + ts[k].lead, ts[k].nbytes);
+            for (size_t k = 0; k < ts.size(); k++) if (!ts[k].host) memcpy(img->data() + offs[k], ts[k].base + ts[k].lead, ts[k].nbytes);
         });
+        // host objects: the caller's thread owns them; their state at the request is what the file must hold
+        for (size_t k = 0; k < ts.size(); k++) if (ts[k].host) memcpy(img->data() + offs[k], ts[k].base + ts[k].lead, ts[k].nbytes);
         REQUIRE(ckpt_snapshot_async(ctx, uint64_t(it), compute) == CKPT_OK);
+        // ... and may change them the moment the call has returned
+        for (auto &t : ts) if (t.host) for (uint64_t i = 0; i < t.nbytes; i++) t.base[t.lead + i] = uint8_t(t.base[t.lead + i] * 13 + it);
     }
     REQUIRE(ckpt_flush(ctx, CKPT_ITER_ALL) == CKPT_OK);
     hipStreamSynchronize(compute);
@@ -206,6 +211,10 @@ int main(int argc, char **argv) {
     if (scenario(sub(), CKPT_WINDOW_D2H, 1, CKPT_IO_MMAP, 256 << 10, 0, 60, 0, true)) return 1;
     // second tier behind a first tier that keeps every file (read back by path)
     if (scenario(sub(), CKPT_WINDOW_D2H, 0, CKPT_IO_PWRITE, 256 << 10, 0, 40, 0, true)) return 1;
+    // host-resident objects among the tensors, changed by the caller right after each request; with direct copies too
+    if (scenario(sub(), CKPT_WINDOW_D2H, 1, CKPT_IO_MMAP, 256 << 10, 0, 60, 0, false, true)) return 1;
+    if (scenario(sub(), CKPT_WINDOW_PACK, 0, CKPT_IO_PWRITE, 128 << 10, 0, 60, 0, false, true)) return 1;
+    if (scenario(sub(), CKPT_WINDOW_D2H, 0, CKPT_IO_PWRITE, 256 << 10, 0, 60, 30000, false, true)) return 1;
     // hybrid with everything direct that may be: the pack kernel sees only what is under 4 KiB
     if (scenario(sub(), CKPT_WINDOW_D2H, 0, CKPT_IO_PWRITE, 128 << 10, 0, 60, 4096)) return 1;
     return 0;

@@ -1,0 +1,100 @@
+"""Host-resident objects (CKPT_PLACE_HOST) in the same checkpoint as the device tensors, on a real
+GPU: the file is the oracle's file of (device state at the boundary, host state at the request), the
+caller may overwrite host objects as soon as the request has returned, and a restore puts both kinds
+back."""
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2406_10707_amd import binding as B
+from paper_2406_10707_amd import harness, shards
+
+pytestmark = pytest.mark.gpu
+
+SMALL = dict(dma_chunk_bytes=64 << 10, pack_superchunk_bytes=128 << 10, host_ring_bytes=256 << 10)
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _host_objects(seed):
+    g = np.random.default_rng(seed)
+    return [("rng_state", B.CKPT_U8, (5056,), g.integers(0, 256, 5056, dtype=np.uint8)),
+            ("offloaded.exp_avg", B.CKPT_F32, (300, 77), g.standard_normal((300, 77)).astype(np.float32)),
+            ("args.blob", B.CKPT_U8, (137,), g.integers(0, 256, 137, dtype=np.uint8)),
+            ("offloaded.big", B.CKPT_BF16, (1 << 18,), g.integers(0, 65536, 1 << 18, dtype=np.uint16))]
+
+
+def _bytes(a):
+    return np.ascontiguousarray(a).view(np.uint8).reshape(-1)
+
+
+@pytest.mark.parametrize("direct_min,policy", [(0, B.CKPT_WINDOW_D2H), (0, B.CKPT_WINDOW_PACK), (16384, B.CKPT_WINDOW_D2H)])
+@pytest.mark.parametrize("config", [1, 5])
+def test_mixed_device_and_host_state(config, direct_min, policy, tmp_path):
+    _say(f"host objects config {config} direct_min {direct_min} policy {policy}")
+    spec = shards.make_shard(config, tiny=True)
+    shard = harness.DeviceShard(spec)
+    shard.upload_host_values()
+    stream = harness.Stream()
+    objs = _host_objects(config)
+    dev = shard.descs()
+    # host objects interleaved with the device tensors: first, in the middle, last
+    where = [0, len(dev) // 2, len(dev) // 2, len(dev)]
+    order = []           # ("dev", k) or ("host", j) in registration order
+    for k in range(len(dev) + 1):
+        order += [("host", j) for j, w in enumerate(where) if w == k]
+        if k < len(dev):
+            order.append(("dev", k))
+    descs = [dev[i] if kind == "dev" else (objs[i][0], objs[i][1] | B.CKPT_PLACE_HOST, objs[i][2], objs[i][3].ctypes.data, objs[i][3].nbytes)
+             for kind, i in order]
+    ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), window_policy=policy, direct_min_bytes=direct_min, **SMALL))
+    ck.register_tensors(descs)
+    lay = ck.layout()
+    assert lay["n_host_objects"] == 4 and lay["host_bytes"] == sum(o[3].nbytes for o in objs)
+
+    def oracle_list(dev_arrays, host_arrays):
+        return [(dev[i][0], dev[i][1], dev[i][2], dev_arrays[i]) if kind == "dev" else (objs[i][0], objs[i][1], objs[i][2], host_arrays[i])
+                for kind, i in order]
+
+    clones, host_then = {}, {}
+    for it in range(1, 5):
+        ck.wait_immutable_window_end(stream.cuda_stream)
+        shard.update(it, stream)
+        clones[it] = shard.clone_all(stream)
+        host_then[it] = [_bytes(o[3]).copy() for o in objs]
+        ck.snapshot_async(it, stream.cuda_stream)
+        for o in objs:                                   # the caller changes its host state right away
+            _bytes(o[3])[:] = _bytes(o[3]) * 7 + it
+    ck.flush()
+    stream.synchronize()
+    for it in range(1, 5):
+        devs = [c.download() for c in clones[it]]
+        assert oracle.compare_file(oracle_list(devs, host_then[it]), it, ck.file_name(it)) is None, f"iteration {it}"
+    # restore iteration 2: device tensors and host objects return to their state of then
+    shard.poison(0xA5)
+    for o in objs:
+        _bytes(o[3])[:] = 0x5A
+    assert ck.restore(ck.file_name(2), stream.cuda_stream) == 2
+    for j, o in enumerate(objs):                         # host objects are back when the call returns
+        assert np.array_equal(_bytes(o[3]), host_then[2][j]), o[0]
+    stream.synchronize()
+    for k, got in enumerate(shard.readback_all()):
+        assert np.array_equal(got, clones[2][k].download()), spec.tensors[k].name
+    ck.destroy()
+
+
+def test_host_only_registration(tmp_path):
+    """Nothing but host objects: no pack launch has any work, the file is still the oracle's."""
+    _say("host objects only")
+    objs = _host_objects(9)
+    descs = [(n, d | B.CKPT_PLACE_HOST, s, a.ctypes.data, a.nbytes) for n, d, s, a in objs]
+    stream = harness.Stream()
+    ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), **SMALL))
+    ck.register_tensors(descs)
+    assert ck.layout()["n_tiles"] == 0
+    ck.snapshot_async(1, stream.cuda_stream)
+    ck.flush(1)
+    assert open(ck.file_name(1), "rb").read() == oracle.serialize_bytes([(n, d, s, _bytes(a)) for n, d, s, a in objs], 1)
+    ck.destroy()

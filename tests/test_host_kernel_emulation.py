@@ -50,4 +50,4 @@ def test_engine_event_graph_under_thread_sanitizer(emu_engine, seed, tmp_path):
     r = subprocess.run([emu_engine, str(tmp_path), str(seed)], capture_output=True, text=True, timeout=600)
     out = r.stdout + r.stderr
     assert r.returncode == 0 and "ThreadSanitizer" not in out and "FAILED" not in out, out[-6000:]
-    assert out.count("ok policy") == 8 and out.count("snapshots copied") == 2
+    assert out.count("ok policy") == 11 and out.count("snapshots copied") == 2

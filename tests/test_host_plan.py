@@ -170,6 +170,42 @@ def test_segments_reproduce_the_data_region(config, direct_min):
     plan.close()
 
 
+def test_host_resident_objects_in_the_plan():
+    """Objects flagged CKPT_PLACE_HOST: same header and offsets as if they lived on the device (the
+    file does not record placement), no tiles, HOST segments that point into the objects, ZERO
+    segments for their padding; any address alignment is accepted for them."""
+    chunk = 64 << 10
+    spec = shards.make_shard(1, tiny=True)
+    descs, span = _fake_descs(spec)
+    host_base = 0x5000_0000_0001                 # odd on purpose
+    extra = [("rng_state", B.CKPT_U8 | B.CKPT_PLACE_HOST, (5056,), host_base, 5056),
+             ("offloaded.exp_avg", B.CKPT_F32 | B.CKPT_PLACE_HOST, (300, 77), host_base + 8192, 300 * 77 * 4),
+             ("args", B.CKPT_U8 | B.CKPT_PLACE_HOST, (137,), host_base + 200000, 137)]
+    mixed = descs[:5] + extra[:2] + descs[5:] + extra[2:]
+    plan = B.Plan(mixed, B.make_config(dma_chunk_bytes=chunk, pack_superchunk_bytes=4 * chunk))
+    lay = plan.layout()
+    assert lay["n_host_objects"] == 3 and lay["host_bytes"] == 5056 + 92400 + 137
+    assert lay["host_data_bytes"] == 8192 + 94208 + 4096
+    plain = [(n, d & 0xFF, s, None) for n, d, s, p_, nb in mixed]
+    assert plan.header(5) == oracle.build_header(plain, 5)
+    assert plan.offsets() == oracle.tensor_offsets(plain)
+    offs = plan.offsets()
+    host_idx = {k for k, d in enumerate(mixed) if d[1] & B.CKPT_PLACE_HOST}
+    covered = {k: 0 for k in host_idx}
+    for sg in plan.segments():
+        if sg.kind == B.CKPT_SEG_HOST:
+            d = mixed[sg.tensor]
+            assert sg.tensor in host_idx and d[3] <= sg.src and sg.src + sg.nbytes <= d[3] + d[4]
+            assert sg.data_off + lay["header_bytes"] == offs[sg.tensor] + (sg.src - d[3])
+            covered[sg.tensor] += sg.nbytes
+        elif sg.kind == B.CKPT_SEG_ZERO:
+            assert sg.tensor in host_idx
+    assert all(covered[k] == mixed[k][4] for k in host_idx)
+    for t in plan.tiles():        # no tile reads a host address
+        assert t.copy_bytes == 0 or FAKE_BASE <= t.src < FAKE_BASE + span
+    plan.close()
+
+
 def test_full_size_hybrid_plan_counts():
     """Llama-7B with everything of 1 MiB and more copied directly: only the norm weights are packed."""
     spec = shards.make_shard(2)
