@@ -405,6 +405,8 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     # physical floor under the paper's rule: the copies cannot end before D / B_link, the window is the GEMM phase
     stall["floor_ms_per_snapshot"] = round(max(0.0, S / (link["d2h"] * 1e9) * 1e3 - ref_gemm_ms), 2)
     stall["stall_minus_floor_ms_per_snapshot"] = round(stall["stall_ms_per_snapshot"] - stall["floor_ms_per_snapshot"], 2)
+    # the paper's own throughput figure: checkpoint size over the time training was blocked by it
+    stall["perceived_gbps_paper_definition"] = round(S / (stall["stall_ms_per_snapshot"] * 1e-3) / 1e9, 1) if stall["stall_ms_per_snapshot"] > 0 else None
     if paired:
         paired["stall_minus_floor_ms_per_step"] = round(paired["stall_ms_per_step"] - stall["floor_ms_per_snapshot"], 2)
         stall["paired_alternating_blocks"] = paired
