@@ -1,0 +1,145 @@
+// Restore: the snapshot path run backwards (file -> ring slots -> device -> scatter kernel).
+#include "engine_internal.hpp"
+
+using namespace dsllm;
+
+static int restore_body(ckpt_ctx *c, int fd, const char *path, hipStream_t stream, uint64_t base, uint64_t *issued_out, uint64_t *iter_out) {
+    const Plan &p = c->plan;
+    const uint64_t CH = c->cfg.dma_chunk_bytes, SC = c->cfg.pack_superchunk_bytes;
+    const size_t nk = c->dma.size();
+    struct stat st;
+    if (fstat(fd, &st) != 0) return fail(CKPT_EIO, std::string(path) + ": fstat: " + strerror(errno));
+    // header: read the first 4 KiB unit, check the fixed fields, then compare the whole header with
+    // the registration's (everything but the iteration field must be identical)
+    std::string err;
+    if (uint64_t(st.st_size) < kAlign) return fail(CKPT_EFORMAT, "file shorter than one header unit");
+    uint8_t *hb = c->hdr_buf;
+    if (!pread_all(fd, hb, kAlign, 0, &err)) return fail(CKPT_EIO, err);
+    auto le = [&](const uint8_t *q, int n) { uint64_t v = 0; for (int i = 0; i < n; i++) v |= uint64_t(q[i]) << (8 * i); return v; };
+    if (memcmp(hb, p.header.data(), 8) != 0 || le(hb + 8, 4) != 1 || le(hb + 12, 4) != kAlign || le(hb + 56, 8) != 0)
+        return fail(CKPT_EFORMAT, "bad magic, version or alignment");
+    const uint64_t f_hb = le(hb + 32, 8), f_db = le(hb + 40, 8), f_fb = le(hb + 48, 8), f_iter = le(hb + 16, 8);
+    if (f_hb % kAlign || f_hb < kAlign || f_fb != f_hb + f_db || f_fb != uint64_t(st.st_size))
+        return fail(CKPT_EFORMAT, "size fields inconsistent with the file (truncated?)");
+    if (le(hb + 24, 8) != p.tensors.size() || f_hb != p.header_bytes || f_db != p.data_bytes)
+        return fail(CKPT_EMISMATCH, "tensor count or sizes differ from the registration");
+    if (p.header_bytes > kAlign && !pread_all(fd, hb + kAlign, p.header_bytes - kAlign, kAlign, &err)) return fail(CKPT_EIO, err);
+    if (memcmp(hb, p.header.data(), 16) != 0 || memcmp(hb + 24, p.header.data() + 24, p.header_bytes - 24) != 0)
+        return fail(CKPT_EMISMATCH, "tensor table differs from the registration");
+
+    // earlier work on the caller's stream (which may read or write the tensors) comes first
+    HIP_TRY(c, hipEventRecord(c->ev_user, stream));
+    HIP_TRY(c, hipStreamWaitEvent(c->pack_stream, c->ev_user, 0));
+    if (p.n_direct)   // these copies write the tensors themselves
+        for (size_t k = 0; k < nk; k++) HIP_TRY(c, hipStreamWaitEvent(c->dma[k], c->ev_user, 0));
+
+    uint64_t &issued = *issued_out;   // chunks whose file read has been handed to the I/O threads
+    auto issue_reads_upto = [&](uint64_t upto) -> int {
+        for (; issued < upto && issued < p.n_chunks; issued++) {
+            const uint64_t slot = (base + issued) % c->n_slots;
+            if (issued >= c->n_slots) HIP_TRY(c, hipEventSynchronize(c->ev_slot[slot]));   // previous chunk's copy out of the slot
+            IoJob job;
+            job.kind = IoJob::READ;
+            job.fd = fd;
+            job.slot = slot;
+            job.file_off = p.header_bytes + issued * CH;
+            job.nbytes = p.chunk_bytes(issued);
+            {
+                std::lock_guard<std::mutex> lk(c->mu);
+                c->slot_state[slot] = SLOT_BUSY;
+                c->io_q.push_back(job);
+            }
+            c->cv_io.notify_one();
+        }
+        return CKPT_OK;
+    };
+    for (uint64_t sc = 0; sc < p.n_superchunks; sc++) {
+        const uint64_t stage = sc % c->n_stage;
+        uint8_t *stage_base = c->staging + stage * SC;
+        if (sc >= c->n_stage)   // staging slot still being scattered from
+            for (size_t k = 0; k < nk; k++) HIP_TRY(c, hipStreamWaitEvent(c->dma[k], c->ev_packed[sc - c->n_stage], 0));
+        const uint64_t c0 = sc * (SC / CH), c1 = std::min<uint64_t>(p.n_chunks, c0 + SC / CH);
+        for (uint64_t ch = c0; ch < c1; ch++) {
+            int r = issue_reads_upto(ch + c->n_slots);
+            if (r != CKPT_OK) return r;
+            const uint64_t slot = (base + ch) % c->n_slots;
+            {
+                std::unique_lock<std::mutex> lk(c->mu);
+                c->cv_state.wait(lk, [&] { return c->slot_state[slot] == SLOT_READ_DONE; });
+                if (c->async_code) { g_last_error = c->async_err; return c->async_code; }
+            }
+            const size_t k = ch % nk;
+            const uint8_t *slot_base = c->ring + slot * CH;
+            for (uint64_t j = p.chunk_first_seg[ch]; j < p.chunk_first_seg[ch + 1]; j++) {
+                const ckpt_segment &sg = p.segs[j];
+                if (sg.kind == CKPT_SEG_ZERO) continue;
+                if (sg.kind == CKPT_SEG_HOST) {   // the slot has been read: host objects are put back by this thread
+                    memcpy(reinterpret_cast<void *>(sg.src), slot_base + (sg.data_off - ch * CH), sg.nbytes);
+                    continue;
+                }
+                void *dst = sg.kind == CKPT_SEG_DIRECT ? reinterpret_cast<void *>(sg.src) : static_cast<void *>(stage_base + (sg.data_off - sc * SC));
+                HIP_TRY(c, hipMemcpyAsync(dst, slot_base + (sg.data_off - ch * CH), sg.nbytes, hipMemcpyHostToDevice, c->dma[k]));
+            }
+            HIP_TRY(c, hipEventRecord(c->ev_slot[slot], c->dma[k]));
+        }
+        for (size_t k = 0; k < nk; k++) {
+            HIP_TRY(c, hipEventRecord(c->ev_stage_done[stage][k], c->dma[k]));
+            HIP_TRY(c, hipStreamWaitEvent(c->pack_stream, c->ev_stage_done[stage][k], 0));
+        }
+        const uint64_t t0 = p.sc_first_tile[sc], t1 = p.sc_first_tile[sc + 1];
+        HIP_TRY(c, launch_scatter(c->dev_tiles + t0, t1 - t0, stage_base, sc * SC, c->pack_stream));
+        HIP_TRY(c, hipEventRecord(c->ev_packed[sc], c->pack_stream));
+    }
+    HIP_TRY(c, hipStreamWaitEvent(stream, c->ev_packed[p.n_superchunks - 1], 0));
+    if (p.n_direct)   // the last copies into large tensors are not followed by a scatter kernel
+        for (size_t k = 0; k < nk; k++) {
+            HIP_TRY(c, hipEventRecord(c->ev_job_tail[k], c->dma[k]));
+            HIP_TRY(c, hipStreamWaitEvent(stream, c->ev_job_tail[k], 0));
+        }
+    if (iter_out) *iter_out = f_iter;
+    return CKPT_OK;
+}
+
+
+extern "C" {
+
+int ckpt_restore(ckpt_ctx *c, const char *path, void *stream, uint64_t *iter_out) {
+    if (!c || !path) return fail(CKPT_EINVAL, "null argument");
+    if (!c->registered) return fail(CKPT_ESTATE, "no tensors registered");
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        for (auto &kv : c->snaps) if (!kv.second->committed) return fail(CKPT_ESTATE, "a snapshot is still in flight");
+        if (c->restoring) return fail(CKPT_ESTATE, "restore already in progress");
+        c->restoring = true;
+    }
+    int rc = CKPT_OK;
+    uint64_t issued = 0;
+    const uint64_t base = c->ring_next;
+    int fd = -1;
+    hipError_t he = hipSetDevice(c->device);
+    if (he != hipSuccess) rc = fail(CKPT_EHIP, std::string("hipSetDevice: ") + hipGetErrorString(he));
+    if (rc == CKPT_OK) {
+        fd = open(path, O_RDONLY | (c->cfg.o_direct ? O_DIRECT : 0));
+        if (fd < 0) rc = fail(CKPT_EIO, std::string(path) + ": open: " + strerror(errno));
+    }
+    if (rc == CKPT_OK) rc = restore_body(c, fd, path, static_cast<hipStream_t>(stream), base, &issued, iter_out);
+    // the ring goes back to the snapshot path: all host-to-device copies out of it must be over and
+    // every read handed to the I/O threads must have returned, whether or not the restore succeeded
+    for (auto s : c->dma) (void)hipStreamSynchronize(s);
+    {
+        std::unique_lock<std::mutex> lk(c->mu);
+        c->cv_state.wait(lk, [&] {
+            for (uint64_t i = 0; i < issued; i++) if (c->slot_state[(base + i) % c->n_slots] == SLOT_BUSY) return false;
+            return true;
+        });
+        for (auto &s : c->slot_state) s = SLOT_FREE;
+        c->restoring = false;
+    }
+    c->ring_next = base + issued;
+    if (fd >= 0) close(fd);
+    if (rc == CKPT_OK) rc = take_async_error(c);
+    else { std::lock_guard<std::mutex> lk(c->mu); c->async_code = 0; c->async_err.clear(); }
+    return rc;
+}
+
+}  // extern "C"

@@ -40,7 +40,8 @@ def emu_engine(tmp_path_factory):
     csrc = os.path.join(ROOT, "paper_2406_10707_amd", "csrc")
     cmd = [CLANG, "-x", "c++", "-std=c++17", "-O1", "-g", "-fsanitize=thread", "-fno-omit-frame-pointer", "-pthread",
            "-I", os.path.join(ROOT, "tests", "emu"), "-o", exe, os.path.join(ROOT, "tests", "emu", "emu_engine.cpp"),
-           os.path.join(csrc, "engine.cpp"), os.path.join(csrc, "plan.cpp"), os.path.join(csrc, "pack_kernels.hip")]
+           *[os.path.join(csrc, f) for f in ("engine.cpp", "submit.cpp", "io_threads.cpp", "restore.cpp", "second_tier.cpp", "plan.cpp",
+                                             "pack_kernels.hip")]]
     subprocess.run(cmd, check=True, cwd=os.path.join(ROOT, "tests", "emu"))
     return exe
 
