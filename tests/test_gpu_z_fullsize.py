@@ -40,9 +40,11 @@ def _offsets(spec):
     return ots, hb, out, off
 
 
-@pytest.mark.parametrize("config", [2, 3, 4, 5])
-def test_full_size_snapshot_and_restore(config):
-    print(f"full size workload {config}", flush=True)
+@pytest.mark.parametrize("config,direct_min", [(2, 0), (3, 0), (4, 0), (5, 0), (5, 1 << 20)])
+def test_full_size_snapshot_and_restore(config, direct_min):
+    """direct_min > 0: the hybrid path on the fragmented workload (6,606 of its 20,000 tensors, most of
+    them at unaligned addresses, go by DMA straight from and to their own memory)."""
+    print(f"full size workload {config} direct_min {direct_min}", flush=True)
     spec = shards.make_shard(config)
     base = "/dev/shm" if os.path.isdir("/dev/shm") else None
     d = tempfile.mkdtemp(prefix="dsllm_full_", dir=base)
@@ -53,8 +55,10 @@ def test_full_size_snapshot_and_restore(config):
         shard.fill_device(stream)
         shard.update(1, stream)
         ck = B.Checkpointer(B.make_config(out_dir=d, host_ring_bytes=16 << 30, dma_chunk_bytes=64 << 20,
-                                          pack_superchunk_bytes=1 << 30, n_dma_streams=2, n_io_threads=12, keep_last=1))
+                                          pack_superchunk_bytes=1 << 30, n_dma_streams=2, n_io_threads=12, keep_last=1,
+                                          direct_min_bytes=direct_min))
         ck.register_tensors(shard.descs())
+        assert (ck.layout()["n_direct_tensors"] > 1000) == (direct_min > 0)
         ots, hb, offs, fb = _offsets(spec)
         ks = _sample(spec)
         # oracle input: device-side clones of the sampled tensors, ordered on the stream between update 1
