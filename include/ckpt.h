@@ -265,6 +265,15 @@ int ckpt_wait_second_tier(ckpt_ctx *ctx, uint64_t iter);
 /* Writes "<second-tier dir>/ckpt_iter<20 digits>.dsl" into buf. */
 int ckpt_second_tier_file_name(ckpt_ctx *ctx, uint64_t iter, char *buf, size_t cap);
 
+/* Restart helper, no context and no device needed: looks through `dir` for files named like the
+ * library's own ("ckpt_iter<20 digits>.dsl") and returns the one with the highest iteration number
+ * that is whole: magic, version and alignment as in docs/FORMAT.md, size fields consistent with each
+ * other and with the file's size, iteration field equal to the name's. Files still under their
+ * temporary name, truncated or foreign files are passed over. iter_out and path_buf may be NULL.
+ * CKPT_EINVAL if nothing valid is there, CKPT_EIO if the directory cannot be read. Works for either
+ * storage tier. */
+int ckpt_find_latest(const char *dir, uint64_t *iter_out, char *path_buf, size_t cap);
+
 int ckpt_get_layout(ckpt_ctx *ctx, ckpt_layout *out);
 /* Measurements of one requested snapshot; CKPT_EINVAL if unknown. Device-timeline fields are filled
  * once d2h_done is set. */

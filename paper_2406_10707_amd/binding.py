@@ -101,6 +101,7 @@ _SIGS = {
     "ckpt_enable_second_tier": (C.c_int, [_vp, C.c_char_p, _i32, _i32, _i32]),
     "ckpt_wait_second_tier": (C.c_int, [_vp, _u64]),
     "ckpt_second_tier_file_name": (C.c_int, [_vp, _u64, C.c_char_p, C.c_size_t]),
+    "ckpt_find_latest": (C.c_int, [C.c_char_p, C.POINTER(_u64), C.c_char_p, C.c_size_t]),
     "ckpt_get_layout": (C.c_int, [_vp, C.POINTER(ckpt_layout)]),
     "ckpt_get_stats": (C.c_int, [_vp, _u64, C.POINTER(ckpt_stats)]),
     "ckpt_file_name": (C.c_int, [_vp, _u64, C.c_char_p, C.c_size_t]),
@@ -182,6 +183,14 @@ def make_descs(tensors):
         keep += [shp, nm]
         arr[k] = ckpt_tensor_desc(nm, dtype, len(shape), C.cast(shp, C.POINTER(C.c_int64)), ptr, nbytes)
     return arr, keep
+
+
+def find_latest(directory):
+    """ckpt_find_latest: (iteration, path) of the newest whole checkpoint file in `directory`."""
+    it = _u64()
+    buf = C.create_string_buffer(4096)
+    _check(lib.ckpt_find_latest(os.fsencode(directory), C.byref(it), buf, 4096))
+    return it.value, os.fsdecode(buf.value)
 
 
 class Plan:

@@ -101,7 +101,54 @@ static int restore_body(ckpt_ctx *c, int fd, const char *path, hipStream_t strea
 }
 
 
+#include <dirent.h>
+
+// True if the file at `path` carries a consistent fixed header for iteration `iter` and has the size it states.
+static bool whole_checkpoint(const std::string &path, uint64_t iter) {
+    int fd = open(path.c_str(), O_RDONLY);
+    if (fd < 0) return false;
+    uint8_t h[kFixedHeader];
+    struct stat st;
+    std::string err;
+    bool ok = fstat(fd, &st) == 0 && uint64_t(st.st_size) >= kAlign && pread_all(fd, h, sizeof h, 0, &err);
+    close(fd);
+    if (!ok) return false;
+    auto le = [&](int off, int n) { uint64_t v = 0; for (int i = 0; i < n; i++) v |= uint64_t(h[off + i]) << (8 * i); return v; };
+    static const uint8_t magic[8] = {'D', 'S', 'L', 'L', 'M', 'C', 'K', 1};
+    if (memcmp(h, magic, 8) != 0 || le(8, 4) != 1 || le(12, 4) != kAlign || le(56, 8) != 0) return false;
+    const uint64_t hb = le(32, 8), db = le(40, 8), fb = le(48, 8);
+    return le(16, 8) == iter && hb >= kAlign && hb % kAlign == 0 && db % kAlign == 0 && fb == hb + db && fb == uint64_t(st.st_size);
+}
+
 extern "C" {
+
+int ckpt_find_latest(const char *dir, uint64_t *iter_out, char *path_buf, size_t cap) {
+    if (!dir || !*dir) return fail(CKPT_EINVAL, "null argument");
+    DIR *d = opendir(dir);
+    if (!d) return fail(CKPT_EIO, std::string(dir) + ": opendir: " + strerror(errno));
+    std::vector<uint64_t> iters;
+    while (struct dirent *e = readdir(d)) {
+        const char *n = e->d_name;   // "ckpt_iter" + 20 digits + ".dsl"
+        if (strlen(n) != 9 + 20 + 4 || strncmp(n, "ckpt_iter", 9) != 0 || strcmp(n + 29, ".dsl") != 0) continue;
+        uint64_t v = 0;
+        bool digits = true;
+        for (int i = 9; i < 29 && digits; i++) { digits = n[i] >= '0' && n[i] <= '9'; v = v * 10 + uint64_t(n[i] - '0'); }
+        if (digits) iters.push_back(v);
+    }
+    closedir(d);
+    std::sort(iters.begin(), iters.end());
+    for (auto it = iters.rbegin(); it != iters.rend(); ++it) {
+        const std::string path = file_name_for(dir, *it);
+        if (!whole_checkpoint(path, *it)) continue;
+        if (path_buf) {
+            if (path.size() + 1 > cap) return fail(CKPT_EINVAL, "buffer too small");
+            memcpy(path_buf, path.c_str(), path.size() + 1);
+        }
+        if (iter_out) *iter_out = *it;
+        return CKPT_OK;
+    }
+    return fail(CKPT_EINVAL, std::string(dir) + ": no whole checkpoint file found");
+}
 
 int ckpt_restore(ckpt_ctx *c, const char *path, void *stream, uint64_t *iter_out) {
     if (!c || !path) return fail(CKPT_EINVAL, "null argument");

@@ -256,3 +256,33 @@ def test_bad_descriptions_and_configs_are_rejected():
     p = B.Plan([("s", B.CKPT_I64, (), FAKE_BASE, 8)])
     assert p.layout()["data_bytes"] == 4096
     p.close()
+
+
+def test_find_latest_picks_the_newest_whole_file(tmp_path):
+    """Restart helper on a directory of oracle-written files: passes over truncated files, files whose
+    header names another iteration, temporary names and foreign files; no device involved."""
+    g = np.random.default_rng(5)
+    ts = [("a", B.CKPT_F32, (1000,), g.standard_normal(1000).astype(np.float32).view(np.uint8)),
+          ("b", B.CKPT_U8, (77,), g.integers(0, 256, 77, dtype=np.uint8))]
+    name = lambda it: os.path.join(tmp_path, "ckpt_iter%020d.dsl" % it)
+    with pytest.raises(B.CkptError) as e:
+        B.find_latest(str(tmp_path))
+    assert e.value.code == B.CKPT_EINVAL
+    for it in (3, 12, 40, 41, 50):
+        oracle.serialize_file(ts, it, name(it))
+    assert B.find_latest(str(tmp_path)) == (50, name(50))
+    with open(name(50), "r+b") as f:                     # truncated: size disagrees with the header
+        f.truncate(os.path.getsize(name(50)) - 4096)
+    assert B.find_latest(str(tmp_path)) == (41, name(41))
+    os.rename(name(41), name(60))                        # header says 41, name says 60
+    assert B.find_latest(str(tmp_path)) == (40, name(40))
+    oracle.serialize_file(ts, 70, name(70) + ".tmp")     # never committed
+    open(os.path.join(tmp_path, "ckpt_iter00000000000000000099.dsl"), "wb").write(b"not a checkpoint" * 512)
+    open(os.path.join(tmp_path, "notes.txt"), "w").write("x")
+    assert B.find_latest(str(tmp_path)) == (40, name(40))
+    with open(name(40), "r+b") as f:                     # damaged magic
+        f.write(b"X")
+    assert B.find_latest(str(tmp_path)) == (12, name(12))
+    with pytest.raises(B.CkptError) as e:
+        B.find_latest(str(tmp_path / "missing"))
+    assert e.value.code == B.CKPT_EIO
