@@ -92,10 +92,49 @@ __device__ __forceinline__ u32x4 keep_bytes(u32x4 v, uint32_t keep) {
 
 // ---------------------------------------------------------------- pack: tensors -> staging
 
+// The aligned source word that follows this lane's own: lane l takes `cur` of lane l+1, lane 63 takes
+// `nxt` of lane 0 (the first word of the next 64). A register exchange through the LDS crossbar
+// (ds_bpermute, no memory involved) instead of a second, overlapping load: each source word is then
+// fetched once and twice as many distinct words are in flight per wave. `same` points at that word
+// in memory; only the host build (kernel source run lane by lane on the CPU) reads it from there.
+__device__ __forceinline__ u32x4 next_lane_word(u32x4 cur, u32x4 nxt, uint32_t lane, const u32x4 *same) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    const int from = int(((lane + 1) & 63) << 2);
+    const bool first = lane == 0;
+    u32x4 o;
+    o.x = uint32_t(__builtin_amdgcn_ds_bpermute(from, int(first ? nxt.x : cur.x)));
+    o.y = uint32_t(__builtin_amdgcn_ds_bpermute(from, int(first ? nxt.y : cur.y)));
+    o.z = uint32_t(__builtin_amdgcn_ds_bpermute(from, int(first ? nxt.z : cur.z)));
+    o.w = uint32_t(__builtin_amdgcn_ds_bpermute(from, int(first ? nxt.w : cur.w)));
+    return o;
+#else
+    (void)cur; (void)nxt; (void)lane;
+    return *same;
+#endif
+}
+
 // Copies the full 16-byte words of a tile whose source is misaligned by 4*W+b bytes.
 template <int W>
 __device__ __forceinline__ void pack_shifted(const u32x4 *src_al, u32x4 *dst, uint32_t n_full, uint32_t b, uint32_t lane) {
-    uint32_t i = lane;
+    // whole groups of 64*kUnroll words, all lanes in step: one load per word, the neighbour's word by exchange.
+    // Output word j needs source words j and j+1; j+1 <= n_full always exists (it holds the tensor's tail
+    // bytes or, behind the last full word, bytes of the same 16-byte line as the tensor's last byte).
+    uint32_t g = 0;
+    for (; g + 64 * kUnroll <= n_full; g += 64 * kUnroll) {
+        u32x4 w[kUnroll], ex = {0, 0, 0, 0};
+#pragma unroll
+        for (int u = 0; u < kUnroll; u++) w[u] = ld16(src_al + g + 64 * u + lane);
+        if (lane == 0) ex = ld16(src_al + g + 64 * kUnroll);
+#pragma unroll
+        for (int u = 0; u < kUnroll; u++) DSLLM_KEEP_WHOLE(w[u]);
+#pragma unroll
+        for (int u = 0; u < kUnroll; u++) {
+            const u32x4 hi = next_lane_word(w[u], u + 1 < kUnroll ? w[u + 1] : ex, lane, src_al + g + 64 * u + lane + 1);
+            st16(dst + g + 64 * u + lane, funnel<W>(w[u], hi, b));
+        }
+    }
+    // the rest of the tile (fewer than 64*kUnroll words): lanes run out at different steps, so each loads both words
+    uint32_t i = g + lane;
     for (; i + 64 * (kUnrollShift - 1) < n_full; i += 64 * kUnrollShift) {
         u32x4 lo[kUnrollShift], hi[kUnrollShift];
 #pragma unroll
