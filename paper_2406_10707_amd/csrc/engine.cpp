@@ -322,6 +322,7 @@ int ckpt_snapshot_async(ckpt_ctx *c, uint64_t iter, void *stream) {
         std::lock_guard<std::mutex> lk(c->mu);
         auto old = c->snaps.find(iter);
         if (old != c->snaps.end() && old->second->ev_boundary) (void)hipEventDestroy(old->second->ev_boundary);
+        sp->policy = c->cfg.window_policy;
         c->snaps[iter] = sp;
         c->last_snap = sp;
         c->submit_q.push_back(sp);
@@ -340,12 +341,12 @@ int ckpt_wait_immutable_window_end(ckpt_ctx *c, void *stream, int32_t host_block
         if (!sp || sp->window_closed) return CKPT_OK;
         // a device-side wait means something only for events that have been recorded: every copy of the
         // pending snapshot must have been enqueued (policy D2H), or every pack launch (policy PACK)
-        const bool pack_only = c->cfg.window_policy == CKPT_WINDOW_PACK;
+        const bool pack_only = sp->policy == CKPT_WINDOW_PACK;
         c->cv_state.wait(lk, [&] { return sp->submitted || (pack_only && sp->packs_submitted); });
     }
     HIP_TRY(c, hipSetDevice(c->device));
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (c->cfg.window_policy == CKPT_WINDOW_PACK) {
+    if (sp->policy == CKPT_WINDOW_PACK) {
         hipEvent_t ev = c->ev_packed[c->plan.n_superchunks - 1];
         HIP_TRY(c, hipStreamWaitEvent(st, ev, 0));
         if (host_block) HIP_TRY(c, hipEventSynchronize(ev));

@@ -81,6 +81,7 @@ struct Snap {
     std::atomic<uint64_t> io_wait_us{0}, io_copy_us{0};   // summed over the I/O threads
     double pack_ms_sum = -1, req_to_d2h_end_ms = -1, d2h_span_ms = -1, req_to_pack_end_ms = -1;
     std::vector<uint8_t> host_capture;      // the host-resident objects as they were when the snapshot was requested
+    int policy = CKPT_WINDOW_D2H;           // window policy in force when the snapshot was requested
     int tier2_state = CKPT_TIER2_NONE;      // ckpt_tier2_state
     double tier2_ms = -1;                   // host: copy to the second tier, open to rename
 };

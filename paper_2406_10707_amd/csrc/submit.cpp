@@ -77,7 +77,7 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
     // super-chunk sc - ahead, which also frees its staging slot (ahead <= n_stage, copies are in order).
     // The copies further down may block this thread on ring back-pressure; pack launches are
     // therefore enqueued before the copies they do not depend on.
-    const uint64_t ahead = c->cfg.window_policy == CKPT_WINDOW_PACK ? c->n_stage : std::min<uint64_t>(c->n_stage, 2);
+    const uint64_t ahead = s->policy == CKPT_WINDOW_PACK ? c->n_stage : std::min<uint64_t>(c->n_stage, 2);
     auto enqueue_pack = [&](uint64_t sc) {
         const uint64_t stage = sc % c->n_stage;
         if (sc >= ahead)
