@@ -286,3 +286,10 @@ def test_find_latest_picks_the_newest_whole_file(tmp_path):
     with pytest.raises(B.CkptError) as e:
         B.find_latest(str(tmp_path / "missing"))
     assert e.value.code == B.CKPT_EIO
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr) and "{" not in r.stdout
