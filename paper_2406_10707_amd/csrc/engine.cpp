@@ -242,13 +242,24 @@ int ckpt_register_tensors(ckpt_ctx *c, const ckpt_tensor_desc *tensors, size_t n
     if (posix_memalign(reinterpret_cast<void **>(&c->hdr_buf), 4096, p.header_bytes) != 0) return fail(CKPT_ENOMEM, "header buffer");
     c->plan = std::move(p);
     c->registered = true;
-    for (int i = 0; i < c->cfg.prealloc_files; i++) {
+    // spare files side by side: page allocation is serialized per file, not across files
+    const int n_spare = c->cfg.prealloc_files;
+    std::vector<FileSlot> made(n_spare);
+    std::vector<std::string> errs(n_spare);
+    std::vector<char> ok(n_spare, 0);
+    std::vector<std::thread> workers;
+    for (int i = 0; i < n_spare; i++) {
         std::string spare = c->out_dir + "/.spare_" + std::to_string(getpid()) + "_" + std::to_string(c->spare_seq++) + ".dsl";
-        FileSlot fs;
-        if (!preallocate_file(spare, c->plan.file_bytes(), std::min(c->cfg.n_io_threads, 8), c->cfg.io_mode == CKPT_IO_MMAP, c->cfg.o_direct, &fs, &err))
-            return fail(CKPT_EIO, err);
-        c->spares.push_back(fs);
+        workers.emplace_back([&, i, spare] {
+            ok[i] = preallocate_file(spare, c->plan.file_bytes(), std::min(c->cfg.n_io_threads, 8), c->cfg.io_mode == CKPT_IO_MMAP, c->cfg.o_direct,
+                                     &made[i], &errs[i]);
+        });
     }
+    for (auto &w : workers) w.join();
+    for (int i = 0; i < n_spare; i++)
+        if (ok[i]) c->spares.push_back(made[i]);
+    for (int i = 0; i < n_spare; i++)
+        if (!ok[i]) return fail(CKPT_EIO, errs[i]);   // the spares that were made are removed by ckpt_destroy
     return CKPT_OK;
 }
 
