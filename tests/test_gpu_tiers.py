@@ -104,3 +104,40 @@ def test_second_tier_error_is_latched(tmp_path):
     ck.flush(2)
     with pytest.raises(B.CkptError):
         ck.destroy()                              # the second failure comes back from destroy
+
+
+def test_restart_from_the_newest_whole_file(tmp_path):
+    """A restart: the context that wrote the checkpoints is gone, a new one registers the same tensors,
+    finds the newest whole file (a torn newer file is passed over) and restores it."""
+    _say("restart via find_latest")
+    spec = shards.make_shard(1, tiny=True)
+    shard = harness.DeviceShard(spec)
+    shard.upload_host_values()
+    stream = harness.Stream()
+    ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), **SMALL))
+    ck.register_tensors(shard.descs())
+    states = {}
+    for it in (10, 20, 30):
+        ck.wait_immutable_window_end(stream.cuda_stream)
+        shard.update(it, stream)
+        ck.snapshot_async(it, stream.cuda_stream)
+        ck.wait_immutable_window_end(stream.cuda_stream, host_block=True)
+        states[it] = shard.readback_all()
+    ck.flush()
+    newest = ck.file_name(30)
+    ck.destroy()
+    assert B.find_latest(str(tmp_path)) == (30, newest)
+    with open(newest, "r+b") as f:            # the newest file is torn (as after a crash in mid-write without the rename protocol)
+        f.truncate(os.path.getsize(newest) // 2)
+    it, path = B.find_latest(str(tmp_path))
+    assert it == 20
+    shard.poison(0xA5)
+    ck2 = B.Checkpointer(B.make_config(out_dir=str(tmp_path), **SMALL))
+    ck2.register_tensors(shard.descs())
+    assert ck2.restore(path, stream.cuda_stream) == 20
+    stream.synchronize()
+    assert all(np.array_equal(g, w) for g, w in zip(shard.readback_all(), states[20]))
+    with pytest.raises(B.CkptError) as e:
+        ck2.restore(newest, stream.cuda_stream)
+    assert e.value.code == B.CKPT_EFORMAT
+    ck2.destroy()
