@@ -275,7 +275,8 @@ int ckpt_second_tier_file_name(ckpt_ctx *ctx, uint64_t iter, char *buf, size_t c
 int ckpt_find_latest(const char *dir, uint64_t *iter_out, char *path_buf, size_t cap);
 
 int ckpt_get_layout(ckpt_ctx *ctx, ckpt_layout *out);
-/* Measurements of one requested snapshot; CKPT_EINVAL if unknown. Device-timeline fields are filled
+/* Measurements of one requested snapshot; CKPT_EINVAL if unknown (records of the 1024 most recent
+ * requests are kept). Device-timeline fields are filled
  * once d2h_done is set. */
 int ckpt_get_stats(ckpt_ctx *ctx, uint64_t iter, ckpt_stats *out);
 /* Writes "<out_dir>/ckpt_iter<20 digits>.dsl" into buf. */

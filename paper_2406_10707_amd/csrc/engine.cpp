@@ -334,6 +334,13 @@ int ckpt_snapshot_async(ckpt_ctx *c, uint64_t iter, void *stream) {
         auto old = c->snaps.find(iter);
         if (old != c->snaps.end() && old->second->ev_boundary) (void)hipEventDestroy(old->second->ev_boundary);
         sp->policy = c->cfg.window_policy;
+        // records of long-finished snapshots are dropped, lowest iteration first (a long run takes thousands)
+        while (c->snaps.size() >= kMaxSnapRecords) {
+            auto oldest = c->snaps.begin();
+            const Snap &o = *oldest->second;
+            if (!o.committed || o.tier2_state == CKPT_TIER2_QUEUED || o.tier2_state == CKPT_TIER2_COPYING || oldest->second == c->last_snap) break;
+            c->snaps.erase(oldest);
+        }
         c->snaps[iter] = sp;
         c->last_snap = sp;
         c->submit_q.push_back(sp);

@@ -95,6 +95,8 @@ struct IoJob {
     uint64_t seq = 0;             // READ: chunk sequence number
 };
 
+constexpr size_t kMaxSnapRecords = 1024;   // per-snapshot records (measurements, states) kept per context
+
 enum SlotState : int { SLOT_FREE = 0, SLOT_BUSY = 1, SLOT_READ_DONE = 2 };
 
 }  // namespace dsllm
