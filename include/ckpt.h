@@ -249,8 +249,9 @@ int ckpt_restore(ckpt_ctx *ctx, const char *path, void *hip_stream, uint64_t *it
 /* The paper's multi-level flush, one level further: out_dir is the fast tier (host memory file system
  * or node-local NVMe) that absorbs checkpoints at the speed of the host link; every file committed
  * there is then copied, by a thread of its own and without holding up training or later snapshots,
- * to `dir` on slower, durable storage (n_threads writers, default 2, each moving 8 MiB blocks;
- * o_direct != 0 opens the copy with O_DIRECT; always fsync'ed before it gets its final name, the same
+ * to `dir` on slower, durable storage (n_threads writers, default 4, each moving 8 MiB blocks;
+ * o_direct != 0 opens the copy with O_DIRECT and writes straight out of the first tier's mapping when
+ * there is one; always fsync'ed before it gets its final name, the same
  * name as in out_dir). The slower tier takes the newest committed snapshot whenever it is free; one
  * that is still waiting when a newer one is committed is skipped (CKPT_TIER2_SKIPPED), so the second
  * tier lags by at most one copy. With retention in the fast tier (keep_last > 0) the file being

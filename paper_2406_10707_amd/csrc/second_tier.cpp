@@ -42,14 +42,18 @@ static void tier2_copy(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
     if (err.empty()) {
         std::atomic<uint64_t> next{0};
         std::mutex emu;
+        // direct I/O straight out of the first tier's mapping (page-aligned offsets, page-cache or tmpfs pages);
+        // if the kernel refuses those pages the block goes through an aligned buffer, as without a mapping
+        std::atomic<bool> from_map_ok{true};
         auto worker = [&] {
             uint8_t *buf = nullptr;
-            const bool need_buf = c->tier2_direct || !src_map;
-            if (need_buf && posix_memalign(reinterpret_cast<void **>(&buf), 4096, blk) != 0) {
+            auto need_buf = [&]() -> bool {
+                if (buf || posix_memalign(reinterpret_cast<void **>(&buf), 4096, blk) == 0) return true;
+                buf = nullptr;
                 std::lock_guard<std::mutex> lk(emu);
                 if (err.empty()) err = "no memory for a copy buffer";
-                return;
-            }
+                return false;
+            };
             for (;;) {
                 const uint64_t b = next.fetch_add(1);
                 if (b >= n_blk) break;
@@ -58,8 +62,17 @@ static void tier2_copy(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
                 std::string e;
                 const uint8_t *from;
                 if (src_map) {
-                    if (buf) { memcpy(buf, src_map + off, n); from = buf; } else from = src_map + off;
+                    if (!c->tier2_direct) from = src_map + off;
+                    else {
+                        if (from_map_ok && pwrite_all(dst_fd, src_map + off, n, off, &e)) continue;
+                        from_map_ok = false;
+                        e.clear();
+                        if (!need_buf()) break;
+                        memcpy(buf, src_map + off, n);
+                        from = buf;
+                    }
                 } else {
+                    if (!need_buf()) break;
                     if (!pread_all(src_fd, buf, n, off, &e)) { std::lock_guard<std::mutex> lk(emu); if (err.empty()) err = sp->final_path + ": " + e; break; }
                     from = buf;
                 }
@@ -138,7 +151,7 @@ int ckpt_enable_second_tier(ckpt_ctx *c, const char *dir, int32_t n_threads, int
     if (!c->snaps.empty()) return fail(CKPT_ESTATE, "second tier must be enabled before the first snapshot");
     if (std::string(dir) == c->out_dir) return fail(CKPT_EINVAL, "second tier must be another directory than out_dir");
     c->tier2_dir = dir;
-    c->tier2_threads = n_threads ? n_threads : 2;
+    c->tier2_threads = n_threads ? n_threads : 4;
     c->tier2_direct = o_direct != 0;
     c->tier2_keep = keep_last;
     c->tier2_on = true;
