@@ -114,37 +114,37 @@ __device__ __forceinline__ u32x4 next_lane_word(u32x4 cur, u32x4 nxt, uint32_t l
 }
 
 // Copies the full 16-byte words of a tile whose source is misaligned by 4*W+b bytes.
+// One group of 64*U consecutive output words starting at word g, all lanes in step: one load per
+// source word, the neighbour's word by exchange. Output word j needs source words j and j+1; j+1 <=
+// n_full always exists (it holds the tensor's tail bytes or, behind the last full word, bytes of the
+// same 16-byte line as the tensor's last byte).
+template <int W, int U>
+__device__ __forceinline__ void pack_shifted_group(const u32x4 *src_al, u32x4 *dst, uint32_t g, uint32_t b, uint32_t lane) {
+    u32x4 w[U], ex = {0, 0, 0, 0};
+#pragma unroll
+    for (int u = 0; u < U; u++) w[u] = ld16(src_al + g + 64 * u + lane);
+    if (lane == 0) ex = ld16(src_al + g + 64 * U);
+#pragma unroll
+    for (int u = 0; u < U; u++) DSLLM_KEEP_WHOLE(w[u]);
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+        const u32x4 hi = next_lane_word(w[u], u + 1 < U ? w[u + 1] : ex, lane, src_al + g + 64 * u + lane + 1);
+        st16(dst + g + 64 * u + lane, funnel<W>(w[u], hi, b));
+    }
+}
+
+// Copies the full 16-byte words of a tile whose source is misaligned by 4*W+b bytes.
 template <int W>
 __device__ __forceinline__ void pack_shifted(const u32x4 *src_al, u32x4 *dst, uint32_t n_full, uint32_t b, uint32_t lane) {
-    // whole groups of 64*kUnroll words, all lanes in step: one load per word, the neighbour's word by exchange.
-    // Output word j needs source words j and j+1; j+1 <= n_full always exists (it holds the tensor's tail
-    // bytes or, behind the last full word, bytes of the same 16-byte line as the tensor's last byte).
+    static_assert(kUnroll == 8, "the group cascade below is written for 8, 4, 2, 1");
     uint32_t g = 0;
-    for (; g + 64 * kUnroll <= n_full; g += 64 * kUnroll) {
-        u32x4 w[kUnroll], ex = {0, 0, 0, 0};
-#pragma unroll
-        for (int u = 0; u < kUnroll; u++) w[u] = ld16(src_al + g + 64 * u + lane);
-        if (lane == 0) ex = ld16(src_al + g + 64 * kUnroll);
-#pragma unroll
-        for (int u = 0; u < kUnroll; u++) DSLLM_KEEP_WHOLE(w[u]);
-#pragma unroll
-        for (int u = 0; u < kUnroll; u++) {
-            const u32x4 hi = next_lane_word(w[u], u + 1 < kUnroll ? w[u + 1] : ex, lane, src_al + g + 64 * u + lane + 1);
-            st16(dst + g + 64 * u + lane, funnel<W>(w[u], hi, b));
-        }
-    }
-    // the rest of the tile (fewer than 64*kUnroll words): lanes run out at different steps, so each loads both words
-    uint32_t i = g + lane;
-    for (; i + 64 * (kUnrollShift - 1) < n_full; i += 64 * kUnrollShift) {
-        u32x4 lo[kUnrollShift], hi[kUnrollShift];
-#pragma unroll
-        for (int u = 0; u < kUnrollShift; u++) { lo[u] = ld16(src_al + i + 64 * u); hi[u] = ld16(src_al + i + 64 * u + 1); }
-#pragma unroll
-        for (int u = 0; u < kUnrollShift; u++) { DSLLM_KEEP_WHOLE(lo[u]); DSLLM_KEEP_WHOLE(hi[u]); }
-#pragma unroll
-        for (int u = 0; u < kUnrollShift; u++) st16(dst + i + 64 * u, funnel<W>(lo[u], hi[u], b));
-    }
-    for (; i < n_full; i += 64) st16(dst + i, funnel<W>(ld16(src_al + i), ld16(src_al + i + 1), b));
+    for (; g + 64 * 8 <= n_full; g += 64 * 8) pack_shifted_group<W, 8>(src_al, dst, g, b, lane);
+    if (g + 64 * 4 <= n_full) { pack_shifted_group<W, 4>(src_al, dst, g, b, lane); g += 64 * 4; }
+    if (g + 64 * 2 <= n_full) { pack_shifted_group<W, 2>(src_al, dst, g, b, lane); g += 64 * 2; }
+    if (g + 64 <= n_full) { pack_shifted_group<W, 1>(src_al, dst, g, b, lane); g += 64; }
+    // the last words of the tile (fewer than 64): not every lane has one, so each loads both of its words
+    const uint32_t i = g + lane;
+    if (i < n_full) st16(dst + i, funnel<W>(ld16(src_al + i), ld16(src_al + i + 1), b));
 }
 
 __global__ __launch_bounds__(kBlock) void pack_kernel(const ckpt_tile *__restrict__ tiles, uint64_t n_tiles,
