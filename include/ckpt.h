@@ -208,8 +208,10 @@ void ckpt_plan_destroy(ckpt_plan *plan);
 int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out);
 
 /* Registers the shard's tensors, once per context: builds header, file offsets, the tile table
- * (uploaded to the device) and the chunk table, and allocates device staging. CKPT_ESTATE if
- * tensors are already registered. Overlapping device ranges are allowed (serialized twice). */
+ * (uploaded to the device) and the chunk and copy-segment tables, allocates device staging and
+ * pre-allocates the spare files the configuration asks for. Every device range is checked to be
+ * memory of this GPU (CKPT_EINVAL otherwise). CKPT_ESTATE if tensors are already registered.
+ * Overlapping device ranges are allowed (serialized twice). */
 int ckpt_register_tensors(ckpt_ctx *ctx, const ckpt_tensor_desc *tensors, size_t n);
 
 /* Requests the snapshot of iteration `iter`: the state captured is what the tensors hold once all
@@ -230,8 +232,9 @@ int ckpt_snapshot_async(ckpt_ctx *ctx, uint64_t iter, void *hip_stream_compute);
  * snapshot. Does not wait for file writes: those may overlap the update. */
 int ckpt_wait_immutable_window_end(ckpt_ctx *ctx, void *hip_stream_compute, int32_t host_block);
 
-/* Changes the window policy (ckpt_window_policy) for later snapshots. CKPT_ESTATE while a
- * snapshot's window is open. */
+/* Changes the window policy (ckpt_window_policy) for later snapshots (a snapshot keeps the policy
+ * that was in force when it was requested). CKPT_ESTATE while a snapshot's window is open;
+ * CKPT_EINVAL for CKPT_WINDOW_PACK on a context with direct_min_bytes set. */
 int ckpt_set_window_policy(ckpt_ctx *ctx, int32_t policy);
 
 /* Blocks until the file of `iter` (or of every requested snapshot, CKPT_ITER_ALL) is written,
@@ -241,9 +244,11 @@ int ckpt_flush(ckpt_ctx *ctx, uint64_t iter);
 
 /* Reads a checkpoint file back into the registered tensors: header checked against the
  * registration (CKPT_EFORMAT / CKPT_EMISMATCH), data read into ring slots by the I/O threads,
- * copied host-to-device into staging, scattered by a kernel. Returns when everything is enqueued
- * (the file has been read by then); `hip_stream` is made to wait for the last scatter kernel.
- * iter_out may be NULL. CKPT_ESTATE while a snapshot is in flight. */
+ * copied host-to-device into staging, scattered by a kernel (tensors that the hybrid path copies
+ * directly are written by the DMA engines straight from the ring slot; host-resident objects by
+ * the calling thread). Returns when everything is enqueued (the file has been read by then);
+ * `hip_stream` is made to wait for the last scatter kernel and the last copy. The path may lie in
+ * either storage tier. iter_out may be NULL. CKPT_ESTATE while a snapshot is in flight. */
 int ckpt_restore(ckpt_ctx *ctx, const char *path, void *hip_stream, uint64_t *iter_out);
 
 /* The paper's multi-level flush, one level further: out_dir is the fast tier (host memory file system
