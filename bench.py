@@ -216,7 +216,10 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     lay = ck.layout()
     S = lay["data_bytes"]
     requested, live_files = [], []
-    state = {"step": 0}
+    # the step counter starts so that the last warm-up step requests a snapshot: its copies then run in the
+    # first timed steps whatever K and W are (with the defaults, W = 10 and a checkpoint every 10 steps, it starts at 0);
+    # without warm-up the first timed step requests one
+    state = {"step": (-args.warmup) % every if args.warmup > 0 else every - 1}
 
     def iteration(step, with_ckpt, marks, snap=True):
         """One step on `stream`; marks gets (start, after-gemm, end) events."""
@@ -396,6 +399,8 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     in_region, stall, ref_gemm_ms = stall_report(main, base_iter_ms, base_gemm_ms)
     stats = [ck.stats(it) for it in in_region]
     all_stats = [ck.stats(it) for it in requested]
+    if not stats:      # a region too short to hold a snapshot's copies: the figures come from every snapshot of the run
+        stats = [s for s in all_stats if s["d2h_done"]]
     snap_gbps = gbps(S * len(stats), sum(s["request_to_d2h_end_ms"] for s in stats)) if stats else None
     link_gbps = gbps(S * len(stats), sum(s["d2h_span_ms"] for s in stats)) if stats else None
     pack_launches = sum(s["pack_launches"] for s in stats)
@@ -439,7 +444,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                      "avg_launch_ms": round(pack_ms / pack_launches, 4) if pack_launches else None,
                      "bytes_per_launch": round(pack_bytes_per_snapshot / (pack_launches / max(1, len(stats)))) if pack_launches else None,
                      "devcopy_ceiling_gbps": round(devcopy_gbps, 1)},
-        "snapshot": {"snapshots_in_timed_region": len(stats), "link_peak_d2h_gbps": round(link["d2h"], 2),
+        "snapshot": {"snapshots_in_timed_region": len(in_region), "link_peak_d2h_gbps": round(link["d2h"], 2),
                      "link_peak_h2d_gbps": round(link["h2d"], 2),
                      "d2h_gbps": round(link_gbps, 2) if link_gbps else None,
                      "d2h_frac_of_link_peak": round(link_gbps / link["d2h"], 4) if link_gbps else None,
