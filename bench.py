@@ -129,11 +129,13 @@ def cpu_baseline(harness, shard, sample_bytes, out_dir):
                       % (len(ks), total / 1e9, dt, os.cpu_count())}
 
 
-def traffic_ratio():
-    """HBM traffic of the pack kernel over its algorithmic bytes, as measured with rocprofv3 counters
-    (profiles/pack_kernel_hbm_traffic_gpt2small.txt); None when the summary is not there."""
+def traffic_ratio(workload=""):
+    """HBM traffic of the pack kernel over its algorithmic bytes, as measured with rocprofv3 counters: on the
+    benchmark's own workload (profiles/pack_kernel_hbm_traffic_llama7b.txt) when that is the one running,
+    else on the small one (profiles/pack_kernel_hbm_traffic_gpt2small.txt); None when the summary is not there."""
+    name = "pack_kernel_hbm_traffic_llama7b.txt" if workload.startswith("llama-7B") else "pack_kernel_hbm_traffic_gpt2small.txt"
     try:
-        for line in open(os.path.join(ROOT, "profiles", "pack_kernel_hbm_traffic_gpt2small.txt")):
+        for line in open(os.path.join(ROOT, "profiles", name)):
             if line.strip().startswith("traffic_over_algorithmic:"):
                 return float(line.split(":")[1].split()[0])
     except OSError:
@@ -439,7 +441,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                    "direct_bytes": lay["direct_bytes"], "copy_segments": lay["n_segments"]},
         "roofline": {"bound": "hbm", "kernel": "pack_kernel", "achieved": round(pack_gbps, 1) if pack_gbps else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(pack_gbps / HBM_PEAK_GBPS, 4) if pack_gbps else None,
-                     "traffic": None, "traffic_source": "rocprofv3 FETCH_SIZE+WRITE_SIZE ratio from profiles/ x algorithmic bytes per launch",
+                     "traffic": None, "traffic_source": "rocprofv3 FETCH_SIZE+WRITE_SIZE of this kernel on this workload, scaled by a copy kernel of known size (profiles/), as a ratio x algorithmic bytes per launch",
                      "launches": pack_launches,
                      "avg_launch_ms": round(pack_ms / pack_launches, 4) if pack_launches else None,
                      "bytes_per_launch": round(pack_bytes_per_snapshot / (pack_launches / max(1, len(stats)))) if pack_launches else None,
@@ -477,7 +479,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         iso = gbps(pack_bytes_per_snapshot, tail[0]["pack_ms_sum"])
         result["roofline"]["no_gemm_running"] = {"achieved": round(iso, 1), "frac": round(iso / HBM_PEAK_GBPS, 4),
                                                  "avg_launch_ms": round(tail[0]["pack_ms_sum"] / tail[0]["pack_launches"], 4)}
-    ratio = traffic_ratio()
+    ratio = traffic_ratio(spec.name)
     if ratio and pack_launches:
         result["roofline"]["traffic"] = round(ratio * result["roofline"]["bytes_per_launch"])
     if tier2_dir:
