@@ -59,7 +59,8 @@ def parse_args():
     ap.add_argument("--baseline-steps", type=int, default=6)
     ap.add_argument("--baseline-discard-s", type=float, default=4.0,
                     help="seconds of steps run and discarded at the start of each no-checkpoint baseline phase")
-    ap.add_argument("--oracle-sample-gb", type=float, default=8.0)
+    ap.add_argument("--oracle-sample-gb", type=float, default=32.0,
+                    help="bytes of the workload the CPU oracle serializes for the cpu_baseline figure (about 10 s on one core)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-restore", action="store_true")
     ap.add_argument("--variant-steps", type=int, default=20,
@@ -498,10 +499,13 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
             "wait_after_run_s": round(t2_wait, 2)}
     if restore_result:
         result["restore"] = restore_result
+    ck.destroy()
     if not args.no_cpu_baseline:
+        # the library's files go first: the sample's host arrays and its file need the memory (tmpfs is host memory)
+        for f in os.listdir(out_dir):
+            os.unlink(os.path.join(out_dir, f))
         say("oracle on the host cores (bounded sample)")
         result["cpu_baseline"] = cpu_baseline(harness, shard, int(args.oracle_sample_gb * 1e9), out_dir)
-    ck.destroy()
     if tier2_dir:
         shutil.rmtree(tier2_dir, ignore_errors=True)
     print(json.dumps(result), flush=True)
