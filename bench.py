@@ -54,6 +54,8 @@ def parse_args():
                          "memory, only smaller ones are packed (0: everything is packed)")
     ap.add_argument("--tier2-dir", default="", help="second, slower storage tier: committed files are copied on to this directory in the background")
     ap.add_argument("--tier2-threads", type=int, default=4)
+    ap.add_argument("--tier2-mode", choices=["newest", "every"], default="newest",
+                    help="newest: the slow tier takes the newest snapshot whenever it is free; every: no snapshot is skipped, training waits")
     ap.add_argument("--tier2-direct", type=int, default=1, help="1: second-tier files are written with O_DIRECT")
     ap.add_argument("--out-dir", default="")
     ap.add_argument("--baseline-steps", type=int, default=6)
@@ -214,7 +216,8 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     tier2_dir = ""
     if args.tier2_dir:
         tier2_dir = tempfile.mkdtemp(prefix="dsllm_tier2_", dir=args.tier2_dir)
-        ck.enable_second_tier(tier2_dir, n_threads=args.tier2_threads, o_direct=args.tier2_direct, keep_last=1)
+        ck.enable_second_tier(tier2_dir, n_threads=args.tier2_threads, o_direct=args.tier2_direct, keep_last=1,
+                              mode=B.CKPT_TIER2_EVERY if args.tier2_mode == "every" else B.CKPT_TIER2_NEWEST)
     init_s = time.perf_counter() - t0
     lay = ck.layout()
     S = lay["data_bytes"]
@@ -491,7 +494,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         t2 = [ck.stats(it) for it in requested]
         done = [s for s in t2 if s["tier2_state"] == B.CKPT_TIER2_DONE]
         result["second_tier"] = {
-            "dir": args.tier2_dir, "threads": args.tier2_threads, "o_direct": args.tier2_direct,
+            "dir": args.tier2_dir, "threads": args.tier2_threads, "o_direct": args.tier2_direct, "mode": args.tier2_mode,
             "snapshots": len(t2), "copied": len(done), "superseded": sum(s["tier2_state"] == B.CKPT_TIER2_SKIPPED for s in t2),
             "failed": sum(s["tier2_state"] == B.CKPT_TIER2_FAILED for s in t2),
             "copy_gbps": round(statistics.median(s["file_bytes"] / (s["host_tier2_ms"] * 1e-3) / 1e9 for s in done), 3) if done else None,

@@ -149,6 +149,13 @@ typedef struct {
     uint32_t tensor;     /* DIRECT, HOST, ZERO: registration index of the tensor; otherwise 0 */
 } ckpt_segment;
 
+/* What the second storage tier takes: the newest committed snapshot whenever it is free (a snapshot
+ * still waiting when a newer one is committed is skipped; training is never held back), or every
+ * snapshot (a new snapshot does not start before its predecessor is on its way to the second tier;
+ * when that tier is slower than the checkpoint rate, training waits for it at the window, which is
+ * the paper's behaviour for a full host cache). */
+typedef enum { CKPT_TIER2_NEWEST = 0, CKPT_TIER2_EVERY = 1 } ckpt_tier2_mode;
+
 /* Where a snapshot stands with respect to the second storage tier (ckpt_enable_second_tier). */
 typedef enum {
     CKPT_TIER2_NONE = 0,     /* no second tier, or not committed to the first tier yet */
@@ -257,12 +264,13 @@ int ckpt_restore(ckpt_ctx *ctx, const char *path, void *hip_stream, uint64_t *it
  * to `dir` on slower, durable storage (n_threads writers, default 4, each moving 8 MiB blocks;
  * o_direct != 0 opens the copy with O_DIRECT and writes straight out of the first tier's mapping when
  * there is one; always fsync'ed before it gets its final name, the same
- * name as in out_dir). The slower tier takes the newest committed snapshot whenever it is free; one
- * that is still waiting when a newer one is committed is skipped (CKPT_TIER2_SKIPPED), so the second
- * tier lags by at most one copy. With retention in the fast tier (keep_last > 0) the file being
+ * name as in out_dir). mode (ckpt_tier2_mode) NEWEST: the slower tier takes the newest committed
+ * snapshot whenever it is free; one that is still waiting when a newer one is committed is skipped
+ * (CKPT_TIER2_SKIPPED), so the second tier lags by at most one copy and never delays training. EVERY:
+ * no snapshot is skipped; the wait for the slower tier shows up in host_backpressure_ms. With retention in the fast tier (keep_last > 0) the file being
  * copied is exempt from recycling until the copy is over. keep_last here: second-tier files kept
  * (0: all). To be called after ckpt_init and before the first snapshot; CKPT_ESTATE otherwise. */
-int ckpt_enable_second_tier(ckpt_ctx *ctx, const char *dir, int32_t n_threads, int32_t o_direct, int32_t keep_last);
+int ckpt_enable_second_tier(ckpt_ctx *ctx, const char *dir, int32_t n_threads, int32_t o_direct, int32_t keep_last, int32_t mode);
 /* Blocks until the snapshot of `iter` is durable in the second tier (CKPT_OK), was skipped
  * (CKPT_ESTATE) or failed; with CKPT_ITER_ALL until the second tier has nothing left to do. Failures
  * of second-tier copies are kept apart from those of the snapshot path: the first one is returned

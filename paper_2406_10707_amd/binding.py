@@ -64,6 +64,7 @@ class ckpt_stats(C.Structure):
                 ("host_flush_span_ms", C.c_double), ("host_io_wait_ms_sum", C.c_double), ("host_io_copy_ms_sum", C.c_double),
                 ("host_tier2_ms", C.c_double)]
 
+CKPT_TIER2_NEWEST, CKPT_TIER2_EVERY = 0, 1
 CKPT_TIER2_NONE, CKPT_TIER2_QUEUED, CKPT_TIER2_COPYING, CKPT_TIER2_DONE, CKPT_TIER2_SKIPPED, CKPT_TIER2_FAILED = range(6)
 
 
@@ -98,7 +99,7 @@ _SIGS = {
     "ckpt_set_window_policy": (C.c_int, [_vp, _i32]),
     "ckpt_flush": (C.c_int, [_vp, _u64]),
     "ckpt_restore": (C.c_int, [_vp, C.c_char_p, _vp, C.POINTER(_u64)]),
-    "ckpt_enable_second_tier": (C.c_int, [_vp, C.c_char_p, _i32, _i32, _i32]),
+    "ckpt_enable_second_tier": (C.c_int, [_vp, C.c_char_p, _i32, _i32, _i32, _i32]),
     "ckpt_wait_second_tier": (C.c_int, [_vp, _u64]),
     "ckpt_second_tier_file_name": (C.c_int, [_vp, _u64, C.c_char_p, C.c_size_t]),
     "ckpt_find_latest": (C.c_int, [C.c_char_p, C.POINTER(_u64), C.c_char_p, C.c_size_t]),
@@ -293,8 +294,8 @@ class Checkpointer:
         _check(lib.ckpt_get_stats(self._h, it, C.byref(out)))
         return _struct_dict(out)
 
-    def enable_second_tier(self, directory, n_threads=0, o_direct=0, keep_last=1):
-        _check(lib.ckpt_enable_second_tier(self._h, os.fsencode(directory), n_threads, o_direct, keep_last))
+    def enable_second_tier(self, directory, n_threads=0, o_direct=0, keep_last=1, mode=CKPT_TIER2_NEWEST):
+        _check(lib.ckpt_enable_second_tier(self._h, os.fsencode(directory), n_threads, o_direct, keep_last, mode))
 
     def wait_second_tier(self, it=CKPT_ITER_ALL):
         _check(lib.ckpt_wait_second_tier(self._h, it))

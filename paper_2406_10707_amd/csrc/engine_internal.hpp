@@ -147,7 +147,7 @@ struct ckpt_ctx {
     // second tier: committed files are copied on to a slower, durable directory by a thread of their own
     bool tier2_on = false, tier2_direct = false, tier2_stop = false;
     std::string tier2_dir;
-    int tier2_threads = 2, tier2_keep = 1;
+    int tier2_threads = 4, tier2_keep = 1, tier2_mode = CKPT_TIER2_NEWEST;
     std::thread tier2_thread;
     std::condition_variable cv_tier2;
     std::shared_ptr<Snap> tier2_waiting;   // newest committed snapshot not yet picked up (latest wins)

@@ -126,6 +126,7 @@ void dsllm::tier2_thread_main(ckpt_ctx *c) {
             sp->tier2_state = CKPT_TIER2_COPYING;
             c->tier2_active = sp;
             c->tier2_retire_after = false;
+            c->cv_state.notify_all();   // the waiting place is free again (mode EVERY: the next snapshot may start)
         }
         tier2_copy(c, sp);
         {
@@ -141,8 +142,9 @@ void dsllm::tier2_thread_main(ckpt_ctx *c) {
 
 extern "C" {
 
-int ckpt_enable_second_tier(ckpt_ctx *c, const char *dir, int32_t n_threads, int32_t o_direct, int32_t keep_last) {
+int ckpt_enable_second_tier(ckpt_ctx *c, const char *dir, int32_t n_threads, int32_t o_direct, int32_t keep_last, int32_t mode) {
     if (!c || !dir || !*dir) return fail(CKPT_EINVAL, "null argument");
+    if (mode != CKPT_TIER2_NEWEST && mode != CKPT_TIER2_EVERY) return fail(CKPT_EINVAL, "second tier: unknown mode");
     if (n_threads < 0 || n_threads > 64 || keep_last < 0) return fail(CKPT_EINVAL, "second tier: n_threads must be 0..64 and keep_last >= 0");
     struct stat st;
     if (stat(dir, &st) != 0 || !S_ISDIR(st.st_mode)) return fail(CKPT_EIO, std::string(dir) + ": not a directory");
@@ -154,6 +156,7 @@ int ckpt_enable_second_tier(ckpt_ctx *c, const char *dir, int32_t n_threads, int
     c->tier2_threads = n_threads ? n_threads : 4;
     c->tier2_direct = o_direct != 0;
     c->tier2_keep = keep_last;
+    c->tier2_mode = mode;
     c->tier2_on = true;
     c->tier2_thread = std::thread(tier2_thread_main, c);
     return CKPT_OK;

@@ -11,6 +11,7 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
     const size_t nk = c->dma.size();
     auto hip_fail = [&](const char *what, hipError_t e) { c->latch(CKPT_EHIP, std::string(what) + ": " + hipGetErrorString(e)); };
     hipError_t e;
+    double tier2_wait_ms = 0;
 
     // one snapshot's copies at a time: the previous one's last copy is over before this one's
     // boundary on the device timeline anyway (the caller closed its window), so this costs nothing there
@@ -20,6 +21,14 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
         // with retention the previous commit is also what retires an older file into the spare pool this
         // snapshot is about to draw from: wait for it (it follows the last copy by one chunk write)
         c->cv_state.wait(lk, [&] { return c->prev_job->d2h_done && (c->cfg.keep_last == 0 || c->prev_job->committed); });
+        // a second tier that must receive every snapshot: the previous one has to be on its way there before
+        // this one may start (at most one file waits for the slower tier while another is being copied);
+        // this is where a slow tier holds training back, through the window wait
+        if (c->tier2_on && c->tier2_mode == CKPT_TIER2_EVERY) {
+            auto w0 = Clock::now();
+            c->cv_state.wait(lk, [&] { return c->prev_job->committed && !c->tier2_waiting; });
+            tier2_wait_ms = ms_between(w0, Clock::now());
+        }
     }
 
     // file and header
@@ -158,7 +167,7 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
     }
     std::vector<uint8_t>().swap(s->host_capture);   // every byte of it is in a ring slot by now
     std::lock_guard<std::mutex> lk(c->mu);
-    s->backpressure_ms = bp_ms;
+    s->backpressure_ms = bp_ms + tier2_wait_ms;
     s->t_submitted = Clock::now();
     s->submitted = true;
     c->prev_job = sp;

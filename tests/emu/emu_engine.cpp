@@ -47,9 +47,9 @@ static std::vector<uint8_t> read_file(const std::string &p) {
 }
 
 static int scenario(const std::string &dir, int policy, int keep_last, int io_mode, uint64_t ring_bytes, uint64_t staging_bytes, int n_tensors,
-                    uint64_t direct_min = 0, bool second_tier = false, bool host_objects = false) {
+                    uint64_t direct_min = 0, bool second_tier = false, bool host_objects = false, int tier2_mode = CKPT_TIER2_NEWEST) {
     std::string what = "policy " + std::to_string(policy) + " keep_last " + std::to_string(keep_last) + " io_mode " + std::to_string(io_mode) +
-                       " direct_min " + std::to_string(direct_min) + (second_tier ? " second tier" : "") + (host_objects ? " host objects" : "");
+                       " direct_min " + std::to_string(direct_min) + (second_tier ? (tier2_mode == CKPT_TIER2_EVERY ? " second tier (every snapshot)" : " second tier") : "") + (host_objects ? " host objects" : "");
     const std::string title = what;
     std::vector<Tensor> ts;
     for (int k = 0; k < n_tensors; k++) {
@@ -95,9 +95,10 @@ static int scenario(const std::string &dir, int policy, int keep_last, int io_mo
     if (second_tier) {
         mkdir(dir2.c_str(), 0755);
         REQUIRE(ckpt_wait_second_tier(ctx, CKPT_ITER_ALL) == CKPT_ESTATE);      // not enabled yet
-        REQUIRE(ckpt_enable_second_tier(ctx, dir.c_str(), 2, 0, 1) == CKPT_EINVAL);   // same directory as the first tier
-        REQUIRE(ckpt_enable_second_tier(ctx, dir2.c_str(), 2, 0, 1) == CKPT_OK);
-        REQUIRE(ckpt_enable_second_tier(ctx, dir2.c_str(), 2, 0, 1) == CKPT_ESTATE);
+        REQUIRE(ckpt_enable_second_tier(ctx, dir.c_str(), 2, 0, 1, tier2_mode) == CKPT_EINVAL);   // same directory as the first tier
+        REQUIRE(ckpt_enable_second_tier(ctx, dir2.c_str(), 2, 0, 1, 7) == CKPT_EINVAL);           // unknown mode
+        REQUIRE(ckpt_enable_second_tier(ctx, dir2.c_str(), 2, 0, tier2_mode == CKPT_TIER2_EVERY ? 0 : 1, tier2_mode) == CKPT_OK);
+        REQUIRE(ckpt_enable_second_tier(ctx, dir2.c_str(), 2, 0, 1, tier2_mode) == CKPT_ESTATE);
     }
     ckpt_layout lay;
     REQUIRE(ckpt_get_layout(ctx, &lay) == CKPT_OK);
@@ -154,7 +155,8 @@ static int scenario(const std::string &dir, int policy, int keep_last, int io_mo
             done += st.tier2_state == CKPT_TIER2_DONE;
             REQUIRE(ckpt_second_tier_file_name(ctx, uint64_t(it), name, sizeof name) == CKPT_OK);
             std::vector<uint8_t> got = read_file(name);
-            if (it == iters) { REQUIRE(st.tier2_state == CKPT_TIER2_DONE && got == expect[it]); }
+            if (tier2_mode == CKPT_TIER2_EVERY) { REQUIRE(st.tier2_state == CKPT_TIER2_DONE && got == expect[it]); }   // none skipped, all kept
+            else if (it == iters) { REQUIRE(st.tier2_state == CKPT_TIER2_DONE && got == expect[it]); }
             else REQUIRE(got.empty());      // second-tier retention keeps one file
         }
         printf("   second tier: %d of %d snapshots copied, the others superseded\n", done, iters);
@@ -211,6 +213,8 @@ int main(int argc, char **argv) {
     if (scenario(sub(), CKPT_WINDOW_D2H, 1, CKPT_IO_MMAP, 256 << 10, 0, 60, 0, true)) return 1;
     // second tier behind a first tier that keeps every file (read back by path)
     if (scenario(sub(), CKPT_WINDOW_D2H, 0, CKPT_IO_PWRITE, 256 << 10, 0, 40, 0, true)) return 1;
+    // a second tier that takes every snapshot, behind a first tier that recycles its files
+    if (scenario(sub(), CKPT_WINDOW_D2H, 1, CKPT_IO_MMAP, 256 << 10, 0, 60, 0, true, false, CKPT_TIER2_EVERY)) return 1;
     // host-resident objects among the tensors, changed by the caller right after each request; with direct copies too
     if (scenario(sub(), CKPT_WINDOW_D2H, 1, CKPT_IO_MMAP, 256 << 10, 0, 60, 0, false, true)) return 1;
     if (scenario(sub(), CKPT_WINDOW_PACK, 0, CKPT_IO_PWRITE, 128 << 10, 0, 60, 0, false, true)) return 1;

@@ -19,9 +19,12 @@ def _say(msg):
     print(msg, flush=True)
 
 
-@pytest.mark.parametrize("keep_last,io_mode,o_direct", [(1, B.CKPT_IO_MMAP, 0), (0, B.CKPT_IO_PWRITE, 0), (2, B.CKPT_IO_MMAP, 1)])
-def test_second_tier_receives_the_newest_snapshot(keep_last, io_mode, o_direct, tmp_path):
-    _say(f"second tier keep_last {keep_last} io_mode {io_mode} o_direct {o_direct}")
+@pytest.mark.parametrize("keep_last,io_mode,o_direct,mode", [(1, B.CKPT_IO_MMAP, 0, B.CKPT_TIER2_NEWEST), (0, B.CKPT_IO_PWRITE, 0, B.CKPT_TIER2_NEWEST),
+                                                             (2, B.CKPT_IO_MMAP, 1, B.CKPT_TIER2_NEWEST), (1, B.CKPT_IO_MMAP, 1, B.CKPT_TIER2_EVERY),
+                                                             (0, B.CKPT_IO_PWRITE, 0, B.CKPT_TIER2_EVERY)])
+def test_second_tier_receives_the_newest_snapshot(keep_last, io_mode, o_direct, mode, tmp_path):
+    """mode NEWEST: the newest snapshot always arrives, older ones are copied or skipped; mode EVERY: all arrive."""
+    _say(f"second tier keep_last {keep_last} io_mode {io_mode} o_direct {o_direct} mode {mode}")
     fast, slow = tmp_path / "fast", tmp_path / "slow"
     fast.mkdir()
     slow.mkdir()
@@ -33,7 +36,7 @@ def test_second_tier_receives_the_newest_snapshot(keep_last, io_mode, o_direct, 
     ck.register_tensors(shard.descs())
     with pytest.raises(B.CkptError):
         ck.wait_second_tier()                               # none enabled
-    ck.enable_second_tier(str(slow), n_threads=3, o_direct=o_direct, keep_last=2)
+    ck.enable_second_tier(str(slow), n_threads=3, o_direct=o_direct, keep_last=2, mode=mode)
     clones = {}
     n = 8
     for it in range(1, n + 1):
@@ -47,6 +50,8 @@ def test_second_tier_receives_the_newest_snapshot(keep_last, io_mode, o_direct, 
     states = {it: ck.stats(it)["tier2_state"] for it in range(1, n + 1)}
     assert states[n] == B.CKPT_TIER2_DONE, states
     assert set(states.values()) <= {B.CKPT_TIER2_DONE, B.CKPT_TIER2_SKIPPED}, states
+    if mode == B.CKPT_TIER2_EVERY:
+        assert set(states.values()) == {B.CKPT_TIER2_DONE}, states
     done = [it for it, s in states.items() if s == B.CKPT_TIER2_DONE]
     present = sorted(f for f in os.listdir(slow))
     assert present == [os.path.basename(ck.second_tier_file_name(it)) for it in done[-2:]], (present, states)   # second-tier retention: 2

@@ -59,7 +59,7 @@ def _run_scenarios(exe, seed, tmp_path, forbidden):
     r = subprocess.run([exe, str(tmp_path), str(seed)], capture_output=True, text=True, timeout=600)
     out = r.stdout + r.stderr
     assert r.returncode == 0 and "FAILED" not in out and not any(w in out for w in forbidden), out[-6000:]
-    assert out.count("ok policy") == 11 and out.count("snapshots copied") == 2
+    assert out.count("ok policy") == 12 and out.count("snapshots copied") == 3
 
 
 @pytest.mark.parametrize("seed", [1, 2, 3])
