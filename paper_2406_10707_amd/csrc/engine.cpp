@@ -480,6 +480,7 @@ int ckpt_destroy(ckpt_ctx *c) {
             }
             c->cv_tier2.notify_all();
             c->tier2_thread.join();
+            if (c->tier2_unlinker.joinable()) c->tier2_unlinker.join();
         }
         rc = take_async_error(c);
         if (rc == CKPT_OK && c->tier2_code) { rc = c->tier2_code; g_last_error = c->tier2_err; }

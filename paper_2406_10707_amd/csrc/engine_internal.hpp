@@ -148,10 +148,11 @@ struct ckpt_ctx {
     bool tier2_on = false, tier2_direct = false, tier2_stop = false;
     std::string tier2_dir;
     int tier2_threads = 4, tier2_keep = 1, tier2_mode = CKPT_TIER2_NEWEST;
-    std::thread tier2_thread;
+    std::thread tier2_thread, tier2_unlinker;   // the latter is touched by the second-tier thread only (and by destroy after joining it)
     std::condition_variable cv_tier2;
     std::shared_ptr<Snap> tier2_waiting;   // newest committed snapshot not yet picked up (latest wins)
     std::shared_ptr<Snap> tier2_active;    // being copied: its first-tier file must not be recycled
+    bool tier2_removals_pending = false;   // superseded second-tier files are still being unlinked
     bool tier2_retire_after = false;       // the active file fell out of the newest keep_last meanwhile
     std::deque<uint64_t> tier2_files;      // iterations present in the second tier, oldest first
     int tier2_code = 0;                    // first failure of a second-tier copy, reported by ckpt_wait_second_tier

@@ -104,7 +104,17 @@ static void tier2_copy(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
             }
         }
     }
-    for (uint64_t it : drop) unlink(file_name_for(c->tier2_dir, it).c_str());
+    // removing a file of tens of GB takes seconds on a disk file system: off this thread, which has the next copy to start
+    if (c->tier2_unlinker.joinable()) c->tier2_unlinker.join();
+    if (!drop.empty()) {
+        { std::lock_guard<std::mutex> lk(c->mu); c->tier2_removals_pending = true; }
+        c->tier2_unlinker = std::thread([c, drop] {
+            for (uint64_t it : drop) unlink(file_name_for(c->tier2_dir, it).c_str());
+            std::lock_guard<std::mutex> lk(c->mu);
+            c->tier2_removals_pending = false;
+            c->cv_state.notify_all();
+        });
+    }
 }
 
 void dsllm::tier2_thread_main(ckpt_ctx *c) {
@@ -170,7 +180,7 @@ int ckpt_wait_second_tier(ckpt_ctx *c, uint64_t iter) {
         if (iter == CKPT_ITER_ALL) {
             c->cv_state.wait(lk, [&] {
                 for (auto &kv : c->snaps) if (!kv.second->committed) return false;
-                return !c->tier2_waiting && !c->tier2_active;
+                return !c->tier2_waiting && !c->tier2_active && !c->tier2_removals_pending;
             });
         } else {
             auto it = c->snaps.find(iter);
