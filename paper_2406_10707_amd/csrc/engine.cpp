@@ -22,6 +22,41 @@ int dsllm::take_async_error(ckpt_ctx *c) {
     return code;
 }
 
+// Creates a file of `bytes` zero bytes with every page allocated, reopened (and mapped) the way the flush uses it.
+bool dsllm::preallocate_file(const std::string &path, uint64_t bytes, int n_threads, bool map_it, bool o_direct, FileSlot *out, std::string *err) {
+    int fd = open(path.c_str(), O_RDWR | O_CREAT | O_TRUNC, 0644);
+    if (fd < 0) { *err = path + ": open: " + strerror(errno); return false; }
+    const uint64_t piece = 16ull << 20;
+    std::vector<uint8_t> zeros(piece, 0);
+    std::atomic<uint64_t> next{0};
+    std::atomic<bool> ok{true};
+    std::mutex emu;
+    std::vector<std::thread> th;
+    for (int t = 0; t < n_threads; t++)
+        th.emplace_back([&] {
+            for (;;) {
+                uint64_t off = next.fetch_add(piece);
+                if (off >= bytes || !ok) return;
+                std::string e;
+                if (!pwrite_all(fd, zeros.data(), std::min(piece, bytes - off), off, &e)) { std::lock_guard<std::mutex> lk(emu); *err = path + ": " + e; ok = false; }
+            }
+        });
+    for (auto &t : th) t.join();
+    close(fd);
+    if (!ok) { unlink(path.c_str()); return false; }
+    // reopen the way the flush will use it; with a mapping, fault every page in now
+    out->path = path;
+    out->fd = open(path.c_str(), (map_it ? O_RDWR : O_WRONLY) | (o_direct ? O_DIRECT : 0));
+    if (out->fd < 0) { *err = path + ": open: " + strerror(errno); unlink(path.c_str()); return false; }
+    if (map_it) {
+        void *m = mmap(nullptr, bytes, PROT_READ | PROT_WRITE, MAP_SHARED | MAP_POPULATE, out->fd, 0);
+        if (m == MAP_FAILED) { *err = path + ": mmap: " + strerror(errno); close(out->fd); unlink(path.c_str()); return false; }
+        out->map = static_cast<uint8_t *>(m);
+        out->map_bytes = bytes;
+    }
+    return true;
+}
+
 // ------------------------------------------------------------------ C ABI
 
 extern "C" {
@@ -187,7 +222,6 @@ int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out) {
     return CKPT_OK;
 }
 
-static bool preallocate_file(const std::string &path, uint64_t bytes, int n_threads, bool map_it, bool o_direct, FileSlot *out, std::string *err);
 
 int ckpt_register_tensors(ckpt_ctx *c, const ckpt_tensor_desc *tensors, size_t n) {
     if (!c) return fail(CKPT_EINVAL, "null context");
@@ -243,7 +277,8 @@ int ckpt_register_tensors(ckpt_ctx *c, const ckpt_tensor_desc *tensors, size_t n
     c->plan = std::move(p);
     c->registered = true;
     // spare files side by side: page allocation is serialized per file, not across files
-    const int n_spare = c->cfg.prealloc_files;
+    // with a second tier the file under copy there is exempt from recycling: one more file is in rotation
+    const int n_spare = c->cfg.prealloc_files + (c->tier2_on && c->cfg.prealloc_files > 0 ? 1 : 0);
     std::vector<FileSlot> made(n_spare);
     std::vector<std::string> errs(n_spare);
     std::vector<char> ok(n_spare, 0);
@@ -264,39 +299,6 @@ int ckpt_register_tensors(ckpt_ctx *c, const ckpt_tensor_desc *tensors, size_t n
 }
 
 // Creates a file of `bytes` bytes with all its pages allocated (zero-filled), several threads writing.
-static bool preallocate_file(const std::string &path, uint64_t bytes, int n_threads, bool map_it, bool o_direct, FileSlot *out, std::string *err) {
-    int fd = open(path.c_str(), O_RDWR | O_CREAT | O_TRUNC, 0644);
-    if (fd < 0) { *err = path + ": open: " + strerror(errno); return false; }
-    const uint64_t piece = 16ull << 20;
-    std::vector<uint8_t> zeros(piece, 0);
-    std::atomic<uint64_t> next{0};
-    std::atomic<bool> ok{true};
-    std::mutex emu;
-    std::vector<std::thread> th;
-    for (int t = 0; t < n_threads; t++)
-        th.emplace_back([&] {
-            for (;;) {
-                uint64_t off = next.fetch_add(piece);
-                if (off >= bytes || !ok) return;
-                std::string e;
-                if (!pwrite_all(fd, zeros.data(), std::min(piece, bytes - off), off, &e)) { std::lock_guard<std::mutex> lk(emu); *err = path + ": " + e; ok = false; }
-            }
-        });
-    for (auto &t : th) t.join();
-    close(fd);
-    if (!ok) { unlink(path.c_str()); return false; }
-    // reopen the way the flush will use it; with a mapping, fault every page in now
-    out->path = path;
-    out->fd = open(path.c_str(), (map_it ? O_RDWR : O_WRONLY) | (o_direct ? O_DIRECT : 0));
-    if (out->fd < 0) { *err = path + ": open: " + strerror(errno); unlink(path.c_str()); return false; }
-    if (map_it) {
-        void *m = mmap(nullptr, bytes, PROT_READ | PROT_WRITE, MAP_SHARED | MAP_POPULATE, out->fd, 0);
-        if (m == MAP_FAILED) { *err = path + ": mmap: " + strerror(errno); close(out->fd); unlink(path.c_str()); return false; }
-        out->map = static_cast<uint8_t *>(m);
-        out->map_bytes = bytes;
-    }
-    return true;
-}
 
 
 int ckpt_snapshot_async(ckpt_ctx *c, uint64_t iter, void *stream) {

@@ -210,4 +210,6 @@ void tier2_thread_main(ckpt_ctx *c);
 void submit_thread_main(ckpt_ctx *c);
 // engine.cpp
 int take_async_error(ckpt_ctx *c);
+bool preallocate_file(const std::string &path, uint64_t bytes, int n_threads, bool map_it, bool o_direct, FileSlot *out, std::string *err);
 }  // namespace dsllm
+

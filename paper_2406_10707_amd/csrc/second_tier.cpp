@@ -167,6 +167,14 @@ int ckpt_enable_second_tier(ckpt_ctx *c, const char *dir, int32_t n_threads, int
     c->tier2_direct = o_direct != 0;
     c->tier2_keep = keep_last;
     c->tier2_mode = mode;
+    if (c->registered && c->cfg.prealloc_files > 0) {
+        // the file under copy to this tier is exempt from recycling: one more spare keeps page allocation off the write path
+        std::string spare = c->out_dir + "/.spare_" + std::to_string(getpid()) + "_" + std::to_string(c->spare_seq++) + ".dsl", err;
+        FileSlot fs;
+        if (!preallocate_file(spare, c->plan.file_bytes(), std::min(c->cfg.n_io_threads, 8), c->cfg.io_mode == CKPT_IO_MMAP, c->cfg.o_direct, &fs, &err))
+            return fail(CKPT_EIO, err);
+        c->spares.push_back(fs);
+    }
     c->tier2_on = true;
     c->tier2_thread = std::thread(tier2_thread_main, c);
     return CKPT_OK;
