@@ -211,6 +211,7 @@ void ckpt_plan_destroy(ckpt_plan *plan);
 /* ---- the snapshot path ---- */
 
 /* Allocates and pins the host ring once, touches every page, creates streams, events and threads.
+ * Hidden spare files (retention) that a process which no longer exists left in out_dir are removed.
  * The ring is reused by every later snapshot and restore (paper: pre-allocated, pre-pinned cache). */
 int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out);
 

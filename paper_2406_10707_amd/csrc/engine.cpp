@@ -57,6 +57,23 @@ bool dsllm::preallocate_file(const std::string &path, uint64_t bytes, int n_thre
     return true;
 }
 
+// Spare files carry the process id of their owner in their name. Those of processes that no longer exist
+// (a run that was killed) are removed: on a memory file system each of them holds a checkpoint's worth of RAM.
+static void remove_stale_spares(const std::string &dir) {
+    DIR *d = opendir(dir.c_str());
+    if (!d) return;
+    std::vector<std::string> stale;
+    while (struct dirent *e = readdir(d)) {
+        unsigned long pid = 0, seq = 0;
+        int used = 0;
+        if (sscanf(e->d_name, ".spare_%lu_%lu.dsl%n", &pid, &seq, &used) == 2 && used == int(strlen(e->d_name)) && pid > 0 &&
+            pid != (unsigned long)getpid() && kill(pid_t(pid), 0) != 0 && errno == ESRCH)
+            stale.push_back(dir + "/" + e->d_name);
+    }
+    closedir(d);
+    for (const auto &p : stale) unlink(p.c_str());
+}
+
 // ------------------------------------------------------------------ C ABI
 
 extern "C" {
@@ -172,6 +189,7 @@ int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out) {
     c->device = cfg->device;
     c->out_dir = cfg->out_dir;
     c->n_slots = rc.host_ring_bytes / rc.dma_chunk_bytes;
+    remove_stale_spares(c->out_dir);
     trace("init: creating streams and events");
     c->slot_state.assign(c->n_slots, SLOT_FREE);
     hipError_t e = hipSuccess;

@@ -18,7 +18,9 @@
 #include <thread>
 #include <vector>
 
+#include <dirent.h>
 #include <errno.h>
+#include <signal.h>
 #include <fcntl.h>
 #include <sys/mman.h>
 #include <sys/stat.h>

@@ -101,7 +101,6 @@ static int restore_body(ckpt_ctx *c, int fd, const char *path, hipStream_t strea
 }
 
 
-#include <dirent.h>
 
 // True if the file at `path` carries a consistent fixed header for iteration `iter` and has the size it states.
 static bool whole_checkpoint(const std::string &path, uint64_t iter) {

@@ -88,8 +88,13 @@ static int scenario(const std::string &dir, int policy, int keep_last, int io_mo
     cfg.keep_last = keep_last;
     cfg.prealloc_files = keep_last ? 1 : 0;
     cfg.direct_min_bytes = direct_min;
+    // leftovers of other runs in the directory: the spare of a process that is gone must disappear, that of a live one stay
+    const std::string stale = dir + "/.spare_4194000_7.dsl", alive = dir + "/.spare_1_0.dsl";
+    { FILE *f = fopen(stale.c_str(), "wb"); fputs("x", f); fclose(f); f = fopen(alive.c_str(), "wb"); fputs("x", f); fclose(f); }
     ckpt_ctx *ctx = nullptr;
     REQUIRE(ckpt_init(&cfg, &ctx) == CKPT_OK);
+    REQUIRE(access(stale.c_str(), F_OK) != 0 && access(alive.c_str(), F_OK) == 0);
+    unlink(alive.c_str());
     REQUIRE(ckpt_register_tensors(ctx, descs.data(), descs.size()) == CKPT_OK);
     const std::string dir2 = dir + "/tier2";
     if (second_tier) {
