@@ -78,7 +78,8 @@ typedef enum { CKPT_IO_AUTO = 0, CKPT_IO_PWRITE = 1, CKPT_IO_MMAP = 2 } ckpt_io_
 /* Zero in a size/count field selects the default given in the comment. */
 typedef struct {
     int32_t device;                 /* HIP device ordinal */
-    const char *out_dir;            /* directory of the checkpoint files; must exist */
+    const char *out_dir;            /* directory of the checkpoint files; must exist. File names carry the iteration
+                                       only: one directory per context (per GPU, per rank) */
     uint64_t host_ring_bytes;       /* pinned host ring; the paper's one knob. default 8 GiB; rounded down to
                                        whole DMA chunks, at least 2 chunks */
     uint64_t dma_chunk_bytes;       /* one device-to-host copy and one ring slot. default 64 MiB; multiple of 32 KiB */
