@@ -152,6 +152,8 @@ def main():
         print("bench.py: this build measures one GPU; --gpus %d is not supported (each box has one MI355X and the "
               "snapshot path of a shard needs no exchange between GPUs)" % args.gpus, file=sys.stderr)
         sys.exit(2)
+    from paper_2406_10707_amd import build as build_lib
+    build_lib.ensure_built()           # compiles only if no library is there at all
     from paper_2406_10707_amd import binding as B
     from paper_2406_10707_amd import harness, shards
 

@@ -43,5 +43,11 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """For tests, the smoke run and the benchmark: compile only when no library is there at all (they never
+    rebuild one that exists; after a change to a source, build explicitly). The binding itself never builds."""
+    return LIB if os.path.exists(LIB) else build(force=True)
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
