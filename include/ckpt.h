@@ -290,6 +290,15 @@ int ckpt_second_tier_file_name(ckpt_ctx *ctx, uint64_t iter, char *buf, size_t c
  * storage tier. */
 int ckpt_find_latest(const char *dir, uint64_t *iter_out, char *path_buf, size_t cap);
 
+/* The file describes itself: writes the tensor table of the checkpoint file at `path` into buf as text,
+ * one line "iter <n> tensors <n> header_bytes <n> data_bytes <n>" and then one line per tensor,
+ * "<name>\t<dtype>\t<d0>x<d1>...\t<file offset>\t<nbytes>" (dtype as in ckpt_dtype: bf16 f32 f16 u8 i32
+ * i64; a scalar's shape is "-"). No context and no device needed. *needed_out (may be NULL) receives the
+ * bytes the text takes including the terminating NUL; CKPT_EINVAL if cap is smaller (nothing is
+ * written then, so a first call with cap 0 sizes the buffer). CKPT_EFORMAT for a file that is not a
+ * whole checkpoint, CKPT_EIO if it cannot be read. */
+int ckpt_describe_file(const char *path, char *buf, size_t cap, size_t *needed_out);
+
 int ckpt_get_layout(ckpt_ctx *ctx, ckpt_layout *out);
 /* Measurements of one requested snapshot; CKPT_EINVAL if unknown (records of the 1024 most recent
  * requests are kept). Device-timeline fields are filled

@@ -102,6 +102,7 @@ _SIGS = {
     "ckpt_enable_second_tier": (C.c_int, [_vp, C.c_char_p, _i32, _i32, _i32, _i32]),
     "ckpt_wait_second_tier": (C.c_int, [_vp, _u64]),
     "ckpt_second_tier_file_name": (C.c_int, [_vp, _u64, C.c_char_p, C.c_size_t]),
+    "ckpt_describe_file": (C.c_int, [C.c_char_p, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)]),
     "ckpt_find_latest": (C.c_int, [C.c_char_p, C.POINTER(_u64), C.c_char_p, C.c_size_t]),
     "ckpt_get_layout": (C.c_int, [_vp, C.POINTER(ckpt_layout)]),
     "ckpt_get_stats": (C.c_int, [_vp, _u64, C.POINTER(ckpt_stats)]),
@@ -184,6 +185,17 @@ def make_descs(tensors):
         keep += [shp, nm]
         arr[k] = ckpt_tensor_desc(nm, dtype, len(shape), C.cast(shp, C.POINTER(C.c_int64)), ptr, nbytes)
     return arr, keep
+
+
+def describe_file(path):
+    """ckpt_describe_file: the tensor table of a checkpoint file as text."""
+    need = C.c_size_t(0)
+    rc = lib.ckpt_describe_file(os.fsencode(path), None, 0, C.byref(need))
+    if need.value == 0:
+        _check(rc)
+    buf = C.create_string_buffer(need.value)
+    _check(lib.ckpt_describe_file(os.fsencode(path), buf, need.value, None))
+    return buf.value.decode("utf-8", "replace")
 
 
 def find_latest(directory):

@@ -121,6 +121,57 @@ static bool whole_checkpoint(const std::string &path, uint64_t iter) {
 
 extern "C" {
 
+int ckpt_describe_file(const char *path, char *buf, size_t cap, size_t *needed_out) {
+    if (!path) return fail(CKPT_EINVAL, "null argument");
+    int fd = open(path, O_RDONLY);
+    if (fd < 0) return fail(CKPT_EIO, std::string(path) + ": open: " + strerror(errno));
+    struct stat st;
+    std::string err;
+    uint8_t fixed[kFixedHeader];
+    if (fstat(fd, &st) != 0 || uint64_t(st.st_size) < kAlign || !pread_all(fd, fixed, sizeof fixed, 0, &err)) {
+        close(fd);
+        return fail(CKPT_EFORMAT, std::string(path) + ": shorter than one header unit");
+    }
+    auto le = [](const uint8_t *q, int n) { uint64_t v = 0; for (int i = 0; i < n; i++) v |= uint64_t(q[i]) << (8 * i); return v; };
+    static const uint8_t magic[8] = {'D', 'S', 'L', 'L', 'M', 'C', 'K', 1};
+    const uint64_t iter = le(fixed + 16, 8), n = le(fixed + 24, 8), hb = le(fixed + 32, 8), db = le(fixed + 40, 8), fb = le(fixed + 48, 8);
+    if (memcmp(fixed, magic, 8) != 0 || le(fixed + 8, 4) != 1 || le(fixed + 12, 4) != kAlign || le(fixed + 56, 8) != 0 || hb < kAlign ||
+        hb % kAlign || db % kAlign || fb != hb + db || fb != uint64_t(st.st_size) || hb > (1ull << 32)) {
+        close(fd);
+        return fail(CKPT_EFORMAT, std::string(path) + ": not a whole checkpoint file");
+    }
+    std::vector<uint8_t> h(hb);
+    const bool got = pread_all(fd, h.data(), hb, 0, &err);
+    close(fd);
+    if (!got) return fail(CKPT_EIO, std::string(path) + ": " + err);
+    static const char *const dtype_name[] = {"?", "bf16", "f32", "f16", "u8", "i32", "i64"};
+    std::string text = "iter " + std::to_string(iter) + " tensors " + std::to_string(n) + " header_bytes " + std::to_string(hb) +
+                       " data_bytes " + std::to_string(db) + "\n";
+    uint64_t pos = kFixedHeader;
+    for (uint64_t k = 0; k < n; k++) {
+        if (pos + 2 > hb) return fail(CKPT_EFORMAT, "tensor table runs past the header");
+        const uint64_t len = le(&h[pos], 2);
+        pos += 2;
+        if (len == 0 || pos + len + 2 > hb) return fail(CKPT_EFORMAT, "tensor table runs past the header");
+        text.append(reinterpret_cast<const char *>(&h[pos]), len);
+        pos += len;
+        const unsigned dtype = h[pos], ndim = h[pos + 1];
+        pos += 2;
+        if (dtype < 1 || dtype > 6 || ndim > 8 || pos + 8ull * ndim + 16 > hb) return fail(CKPT_EFORMAT, "bad tensor table entry");
+        text += std::string("\t") + dtype_name[dtype] + "\t";
+        if (ndim == 0) text += "-";
+        for (unsigned i = 0; i < ndim; i++) { text += (i ? "x" : "") + std::to_string(le(&h[pos], 8)); pos += 8; }
+        const uint64_t off = le(&h[pos], 8), nb = le(&h[pos + 8], 8);
+        pos += 16;
+        if (off < hb || off % kAlign || off + nb > fb) return fail(CKPT_EFORMAT, "tensor lies outside the data region");
+        text += "\t" + std::to_string(off) + "\t" + std::to_string(nb) + "\n";
+    }
+    if (needed_out) *needed_out = text.size() + 1;
+    if (!buf || cap < text.size() + 1) return fail(CKPT_EINVAL, "buffer smaller than the description");
+    memcpy(buf, text.c_str(), text.size() + 1);
+    return CKPT_OK;
+}
+
 int ckpt_find_latest(const char *dir, uint64_t *iter_out, char *path_buf, size_t cap) {
     if (!dir || !*dir) return fail(CKPT_EINVAL, "null argument");
     DIR *d = opendir(dir);

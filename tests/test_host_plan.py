@@ -306,3 +306,32 @@ def test_headers_compile_as_plain_c(tmp_path):
     r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"), "-fsyntax-only", str(src)],
                        capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
+
+
+def test_describe_file_agrees_with_the_independent_reader(tmp_path):
+    """The library's own reading of a file's tensor table against the test suite's struct-based reader, on
+    an oracle-written file of the tiny fragmentation workload; damaged files are refused."""
+    from tests import format_reader as fr
+    spec = shards.make_shard(5, tiny=True)
+    ts = [(t.name, t.dtype, t.shape, shards.host_values(spec, k)) for k, t in enumerate(spec.tensors)]
+    ts.append(("scalar", B.CKPT_I64, (), np.arange(1, dtype=np.int64).view(np.uint8)))
+    path = os.path.join(tmp_path, "ckpt_iter%020d.dsl" % 123)
+    oracle.serialize_file(ts, 123, path)
+    text = B.describe_file(path)
+    lines = text.rstrip("\n").split("\n")
+    it, table = fr.parse(open(path, "rb").read())
+    head = lines[0].split()
+    assert head[:4] == ["iter", str(it), "tensors", str(len(table))] and it == 123 and len(lines) == len(table) + 1
+    names = {B.CKPT_BF16: "bf16", B.CKPT_F32: "f32", B.CKPT_F16: "f16", B.CKPT_U8: "u8", B.CKPT_I32: "i32", B.CKPT_I64: "i64"}
+    for line, e in zip(lines[1:], table):
+        name, dtype, shape, off, nb = line.split("\t")
+        assert name == e["name"] and dtype == names[e["dtype"]] and int(off) == e["offset"] and int(nb) == e["nbytes"]
+        assert shape == ("x".join(str(d) for d in e["shape"]) if e["shape"] else "-")
+    with open(path, "r+b") as f:
+        f.truncate(os.path.getsize(path) - 4096)
+    with pytest.raises(B.CkptError) as e:
+        B.describe_file(path)
+    assert e.value.code == B.CKPT_EFORMAT
+    with pytest.raises(B.CkptError) as e:
+        B.describe_file(os.path.join(tmp_path, "missing.dsl"))
+    assert e.value.code == B.CKPT_EIO
