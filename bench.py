@@ -67,6 +67,7 @@ def parse_args():
     ap.add_argument("--no-restore", action="store_true")
     ap.add_argument("--variant-steps", type=int, default=20,
                     help="extra steps measured under window policy PACK with full device staging (0: skip)")
+    ap.add_argument("--solo-snapshots", type=int, default=2, help="snapshots taken with no training proxy running, after the timed region (0: off)")
     ap.add_argument("--paired-blocks", type=int, default=3,
                     help="workloads that checkpoint every step: alternate this many blocks of checkpointed and quiet steps "
                          "after the timed region for a stall figure free of thermal drift (0: off)")
@@ -370,6 +371,20 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         ok = all((shard.readback(k) == want[k]).all() for k in probe) if last == state["step"] else None
         restore_result = {"gbps": round(S / dt / 1e9, 2), "seconds": round(dt, 2), "probe_tensors_bit_exact": ok if ok is None else bool(ok)}
 
+    # ---- snapshot-only: the same snapshots with nothing else on the card (the interference baseline)
+    solo_rows = []
+    if args.solo_snapshots > 0:
+        say(f"snapshot-only phase, {args.solo_snapshots} snapshots")
+        harness.synchronize()
+        for j in range(args.solo_snapshots):
+            it = 2000000 + j
+            ck.snapshot_async(it, stream.cuda_stream)
+            ck.wait_immutable_window_end(stream.cuda_stream)
+            ck.flush(it)
+            solo_rows.append(ck.stats(it))
+            if not args.keep_last:
+                os.unlink(ck.file_name(it))
+
     # ---- every-iteration workloads have no quiet steps inside the timed region: paired reference
     paired = None
     if every == 1 and args.paired_blocks > 0:
@@ -462,6 +477,13 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                      "drain_s": round(drain_s, 2), "init_s": round(init_s, 2)},
         "stall": stall,
     }
+    if solo_rows:
+        result["snapshot_only"] = {
+            "snapshots": len(solo_rows),
+            "d2h_gbps": round(gbps(S * len(solo_rows), sum(s["d2h_span_ms"] for s in solo_rows)), 2),
+            "snapshot_gbps": round(gbps(S * len(solo_rows), sum(s["request_to_d2h_end_ms"] for s in solo_rows)), 2),
+            "pack_gbps": round(gbps(pack_bytes_per_snapshot * len(solo_rows), sum(s["pack_ms_sum"] for s in solo_rows)), 1),
+            "note": "no training proxy running: what the GEMM loop costs the snapshot path is the difference to the timed region"}
     if variant:
         v_in, v_stall, _ = stall_report(variant, base_iter_ms, base_gemm_ms, drained_before=True)
         v_stats = [ck.stats(it) for it in v_in]
