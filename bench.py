@@ -113,7 +113,7 @@ def measure_devcopy(B, harness, s, nbytes=4 << 30, reps=5):
 def cpu_baseline(harness, shard, sample_bytes, out_dir):
     """The oracle as it stands: blocking per-tensor read-back into pageable memory, then the plain C
     serializer writing the same format to the same sink. One host thread."""
-    from oracle import oracle
+    from oracle import oracle, readback
     ks, total = [], 0
     for k, t in enumerate(shard.spec.tensors):
         ks.append(k)
@@ -123,7 +123,7 @@ def cpu_baseline(harness, shard, sample_bytes, out_dir):
     path = os.path.join(out_dir, "oracle_sample.dsl")
     harness.synchronize()
     t0 = time.perf_counter()
-    host = [shard.readback(k) for k in ks]
+    host = [readback.d2h(shard.ptrs[k], shard.spec.tensors[k].nbytes) for k in ks]
     tensors = [(shard.spec.tensors[k].name, shard.spec.tensors[k].dtype, shard.spec.tensors[k].shape, h) for k, h in zip(ks, host)]
     oracle.serialize_file(tensors, 0, path)
     dt = time.perf_counter() - t0

@@ -48,6 +48,8 @@ def lib():
         L.oracle_serialize_mem.argtypes = [P, C.c_size_t, C.c_uint64, C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64)]
         L.oracle_compare_file.restype = C.c_int
         L.oracle_compare_file.argtypes = [P, C.c_size_t, C.c_uint64, C.c_char_p, C.POINTER(C.c_uint64)]
+        L.oracle_compare_file_span.restype = C.c_int
+        L.oracle_compare_file_span.argtypes = [P, C.c_size_t, C.c_uint64, C.c_size_t, C.c_size_t, C.c_char_p, C.POINTER(C.c_uint64)]
         L.oracle_restore_file.restype = C.c_int
         L.oracle_restore_file.argtypes = [C.c_char_p, P, C.c_size_t, C.POINTER(C.c_uint64)]
         _lib = L
@@ -142,6 +144,36 @@ def compare_file(tensors, it, path):
     if rc == MISMATCH:
         return int(first.value)
     raise OracleError(rc, "compare_file")
+
+
+class SpanComparer:
+    """oracle_compare_file_span on a long tensor list, piece by piece: the list is marshalled once
+    (names, dtypes, shapes), and every call supplies the host bytes of one run of tensors only."""
+
+    def __init__(self, tensors):
+        self._n = len(tensors)
+        self._arr, self._keep = _marshal([(name, dtype, shape, None) for name, dtype, shape, _ in tensors])
+
+    def compare(self, it, first, arrays, path):
+        """arrays: host bytes of tensors first, first+1, ...; returns None or the first differing file offset."""
+        held = []
+        for j, data in enumerate(arrays):
+            a = np.ascontiguousarray(data).view(np.uint8).reshape(-1)
+            if a.nbytes != self._arr[first + j].nbytes:
+                raise ValueError(f"tensor {first + j}: {a.nbytes} bytes given, {self._arr[first + j].nbytes} expected")
+            held.append(a)
+            self._arr[first + j].host_bytes = a.ctypes.data
+        diff = C.c_uint64(0)
+        try:
+            rc = lib().oracle_compare_file_span(self._arr, self._n, it, first, len(held), os.fsencode(path), C.byref(diff))
+        finally:
+            for j in range(len(held)):
+                self._arr[first + j].host_bytes = None
+        if rc == OK:
+            return None
+        if rc == MISMATCH:
+            return int(diff.value)
+        raise OracleError(rc, "compare_file_span")
 
 
 def restore_file(path, tensors):

@@ -231,6 +231,71 @@ int oracle_compare_file(const oracle_tensor *ts, size_t n, uint64_t iter, const 
     return rc;
 }
 
+/* The same comparison for a run of tensors [first, first + count) only, so that a shard too large to be
+ * held on the host a second time can be checked piece by piece: host_bytes is needed for those tensors
+ * alone. Each piece also checks the file's size, and the piece that starts at tensor 0 the whole header.
+ * A tensor's piece of the file is its nbytes bytes at the oracle's offset followed by zero bytes up to
+ * the next alignment boundary. Pieces that together cover every tensor cover every byte of the file. */
+int oracle_compare_file_span(const oracle_tensor *ts, size_t n, uint64_t iter, size_t first, size_t count, const char *path,
+                             uint64_t *first_diff)
+{
+    if (first_diff) *first_diff = UINT64_MAX;
+    if (first > n || count > n - first) return ORACLE_BAD_ARG;
+    uint64_t hb = oracle_header_bytes(ts, n), db = oracle_data_bytes(ts, n);
+    int fd = open(path, O_RDONLY);
+    if (fd < 0) return ORACLE_IO;
+    struct stat st;
+    if (fstat(fd, &st) != 0) { close(fd); return ORACLE_IO; }
+    if ((uint64_t)st.st_size != hb + db) {
+        close(fd);
+        if (first_diff) *first_diff = (uint64_t)st.st_size < hb + db ? (uint64_t)st.st_size : hb + db;
+        return ORACLE_MISMATCH;
+    }
+    int rc = ORACLE_OK;
+    const uint64_t BUF = 8ull << 20;
+    uint8_t *buf = (uint8_t *)malloc(BUF);
+    if (!buf) { close(fd); return ORACLE_NOMEM; }
+    if (first == 0) {
+        uint8_t *hdr = (uint8_t *)malloc(hb);
+        if (!hdr) { free(buf); close(fd); return ORACLE_NOMEM; }
+        rc = oracle_build_header(ts, n, iter, hdr, hb);
+        for (uint64_t done = 0; done < hb && rc == ORACLE_OK; ) {
+            uint64_t m = hb - done < BUF ? hb - done : BUF;
+            rc = read_all(fd, buf, m);
+            if (rc == ORACLE_OK && memcmp(buf, hdr + done, m) != 0) {
+                uint64_t i = 0;
+                while (buf[i] == hdr[done + i]) i++;
+                if (first_diff) *first_diff = done + i;
+                rc = ORACLE_MISMATCH;
+            }
+            done += m;
+        }
+        free(hdr);
+    }
+    uint64_t pos = oracle_tensor_offset(ts, n, first);
+    if (rc == ORACLE_OK && lseek(fd, (off_t)pos, SEEK_SET) != (off_t)pos) rc = ORACLE_IO;
+    for (size_t k = first; k < first + count && rc == ORACLE_OK; k++) {
+        const uint8_t *src = (const uint8_t *)ts[k].host_bytes;
+        if (!src) { rc = ORACLE_BAD_ARG; break; }
+        uint64_t padded = round_up(ts[k].nbytes);
+        for (uint64_t done = 0; done < padded && rc == ORACLE_OK; ) {
+            uint64_t m = padded - done < BUF ? padded - done : BUF;
+            rc = read_all(fd, buf, m);
+            /* the first `live` bytes of this block are tensor bytes, the rest is padding */
+            uint64_t live = done >= ts[k].nbytes ? 0 : (ts[k].nbytes - done < m ? ts[k].nbytes - done : m);
+            if (rc == ORACLE_OK) {
+                uint64_t i = 0;
+                if (memcmp(buf, src + done, live) != 0) { while (buf[i] == src[done + i]) i++; rc = ORACLE_MISMATCH; }
+                else for (i = live; i < m; i++) if (buf[i] != 0) { rc = ORACLE_MISMATCH; break; }
+                if (rc == ORACLE_MISMATCH && first_diff) *first_diff = pos + i;
+            }
+            done += m; pos += m;
+        }
+    }
+    free(buf); close(fd);
+    return rc;
+}
+
 /* Restore: read the file, check it against FORMAT.md's reader checks and against the expected tensor
  * list (names, dtypes, shapes, sizes), then copy each tensor's bytes into host_bytes. The caller
  * moves them to the device with blocking copies. */

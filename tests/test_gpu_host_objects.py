@@ -8,6 +8,7 @@ import pytest
 from oracle import oracle
 from paper_2406_10707_amd import binding as B
 from paper_2406_10707_amd import harness, shards
+from tests import gpu_util as gu
 
 pytestmark = pytest.mark.gpu
 
@@ -70,7 +71,7 @@ def test_mixed_device_and_host_state(config, direct_min, policy, tmp_path):
     ck.flush()
     stream.synchronize()
     for it in range(1, 5):
-        devs = [c.download() for c in clones[it]]
+        devs = [gu.download(c) for c in clones[it]]
         assert oracle.compare_file(oracle_list(devs, host_then[it]), it, ck.file_name(it)) is None, f"iteration {it}"
     # restore iteration 2: device tensors and host objects return to their state of then
     shard.poison(0xA5)
@@ -80,8 +81,8 @@ def test_mixed_device_and_host_state(config, direct_min, policy, tmp_path):
     for j, o in enumerate(objs):                         # host objects are back when the call returns
         assert np.array_equal(_bytes(o[3]), host_then[2][j]), o[0]
     stream.synchronize()
-    for k, got in enumerate(shard.readback_all()):
-        assert np.array_equal(got, clones[2][k].download()), spec.tensors[k].name
+    for k, got in enumerate(gu.readback_all(shard)):
+        assert np.array_equal(got, gu.download(clones[2][k])), spec.tensors[k].name
     ck.destroy()
 
 

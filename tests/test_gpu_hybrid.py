@@ -12,6 +12,7 @@ import pytest
 from oracle import oracle
 from paper_2406_10707_amd import binding as B
 from paper_2406_10707_amd import harness, shards
+from tests import gpu_util as gu
 
 pytestmark = pytest.mark.gpu
 
@@ -54,14 +55,14 @@ def test_tiny_shard_file_equals_oracle(config, direct_min, tmp_path):
     shard.poison(0xA5)
     assert ck.restore(ck.file_name(3), stream.cuda_stream) == 3
     stream.synchronize()
-    for k, got in enumerate(shard.readback_all()):
+    for k, got in enumerate(gu.readback_all(shard)):
         assert np.array_equal(got, host[k]), spec.tensors[k].name
     if shard.flat:
         used = [np.zeros(n, dtype=bool) for n in spec.flat_buffers]
         for t in spec.tensors:
             used[t.buffer][t.offset:t.offset + t.nbytes] = True
         for f, u in zip(shard.flat, used):
-            assert np.all(f.download()[~u] == 0xA5)
+            assert np.all(gu.download(f)[~u] == 0xA5)
     with pytest.raises(B.CkptError):
         ck.set_window_policy(B.CKPT_WINDOW_PACK)        # direct copies read the tensors until the last one has landed
     ck.destroy()
@@ -91,7 +92,7 @@ def test_every_iteration_with_mutation(config, tmp_path):
     stream.synchronize()
     files = set()
     for it in range(1, 7):
-        host = [c.download() for c in clones[it]]
+        host = [gu.download(c) for c in clones[it]]
         assert oracle.compare_file(shard.oracle_tensors(host), it, ck.file_name(it)) is None, f"iteration {it}"
         files.add(open(ck.file_name(it), "rb").read())
     assert len(files) == 6
@@ -120,11 +121,11 @@ def test_gpt2_full_size_hybrid_equals_plain_and_oracle(big_dir):
         if direct_min:
             lay = ck.layout()
             assert 0 < lay["n_direct_tensors"] < len(spec.tensors) and lay["n_tiles"] < lay["data_bytes"] // lay["tile_bytes"]
-            want = shard.readback_all()
+            want = gu.readback_all(shard)
             shard.poison(0x5A)
             assert ck.restore(ck.file_name(9), stream.cuda_stream) == 9
             stream.synchronize()
-            assert all(np.array_equal(g, w) for g, w in zip(shard.readback_all(), want))
+            assert all(np.array_equal(g, w) for g, w in zip(gu.readback_all(shard), want))
         ck.destroy()
     assert images[0] == images[1]
-    assert oracle.compare_file(shard.oracle_tensors(shard.readback_all()), 9, names[0]) is None
+    assert oracle.compare_file(shard.oracle_tensors(gu.readback_all(shard)), 9, names[0]) is None

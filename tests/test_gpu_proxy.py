@@ -7,12 +7,13 @@ import pytest
 from oracle import proxy_oracle as po
 from paper_2406_10707_amd import binding as B
 from paper_2406_10707_amd import harness
+from tests import gpu_util as gu
 
 pytestmark = pytest.mark.gpu
 
 
 def _dl(buf, dtype):
-    return buf.download().view(dtype)
+    return gu.download(buf).view(dtype)
 
 
 @pytest.mark.parametrize("numel", [1, 3, 1000, 65537, (1 << 20) + 5])
@@ -74,7 +75,7 @@ def test_devcopy_exact_with_ragged_size():
     B.proxy_device_fill_async(b.ptr, 0xEE, n + 64, 0)
     B.proxy_devcopy(b.ptr, a.ptr, n, 0)
     harness.synchronize()
-    out = b.download()
+    out = gu.download(b)
     assert np.array_equal(out[:n], src) and np.all(out[n:] == 0xEE)
 
 

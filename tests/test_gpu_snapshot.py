@@ -11,6 +11,7 @@ import pytest
 from oracle import oracle
 from paper_2406_10707_amd import binding as B
 from paper_2406_10707_amd import harness, shards
+from tests import gpu_util as gu
 from tests import format_reader as fr
 
 pytestmark = pytest.mark.gpu
@@ -52,7 +53,7 @@ def test_tiny_shard_file_equals_oracle(config, policy, tmp_path):
     data = open(ck.file_name(3), "rb").read()
     host = [shards.host_values(spec, k) for k in range(len(spec.tensors))]
     assert data == oracle.serialize_bytes(shard.oracle_tensors(host), 3)           # oracle on the generator's bytes
-    assert oracle.compare_file(shard.oracle_tensors(shard.readback_all()), 3, ck.file_name(3)) is None   # and on the read-back
+    assert oracle.compare_file(shard.oracle_tensors(gu.readback_all(shard)), 3, ck.file_name(3)) is None   # and on the read-back
     it, table = fr.parse(data)                                                     # third opinion on the structure
     assert it == 3 and len(table) == len(spec.tensors)
     assert not os.path.exists(ck.file_name(3) + ".tmp")
@@ -82,7 +83,7 @@ def test_sink_modes_write_the_same_file(mode, tmp_path):
     shard.poison()
     assert ck.restore(ck.file_name(2), stream.cuda_stream) == 2
     stream.synchronize()
-    assert all(np.array_equal(g, h) for g, h in zip(shard.readback_all(), host))
+    assert all(np.array_equal(g, h) for g, h in zip(gu.readback_all(shard), host))
     ck.destroy()
 
 
@@ -104,7 +105,7 @@ def test_retention_recycles_files_in_place(io_mode, tmp_path):
         shard.update(it, stream)
         ck.snapshot_async(it, stream.cuda_stream)
         ck.wait_immutable_window_end(stream.cuda_stream, host_block=True)
-        want[it] = oracle.serialize_bytes(shard.oracle_tensors(shard.readback_all()), it)
+        want[it] = oracle.serialize_bytes(shard.oracle_tensors(gu.readback_all(shard)), it)
         ck.flush(it)
         names = sorted(f for f in os.listdir(tmp_path) if not f.startswith("."))
         assert names == [os.path.basename(ck.file_name(j)) for j in range(max(1, it - 1), it + 1)], names
@@ -140,7 +141,7 @@ def test_every_iteration_with_mutation(config, tmp_path):
     stream.synchronize()
     files = {}
     for it in range(1, 7):
-        host = [c.download() for c in clones[it]]
+        host = [gu.download(c) for c in clones[it]]
         assert oracle.compare_file(shard.oracle_tensors(host), it, ck.file_name(it)) is None, f"iteration {it}"
         files[it] = open(ck.file_name(it), "rb").read()
     assert len(set(files.values())) == 6          # the update really changed the state every time
@@ -165,7 +166,7 @@ def test_update_inside_the_window_is_detected(big_dir):
     ck.wait_immutable_window_end(stream.cuda_stream)
     ck.flush(1)
     stream.synchronize()
-    host = [c.download() for c in clones]
+    host = [gu.download(c) for c in clones]
     assert oracle.compare_file(shard.oracle_tensors(host), 1, ck.file_name(1)) is not None
     ck.destroy()
 
@@ -186,14 +187,14 @@ def test_restore_and_resnapshot_round_trip(config, tmp_path):
     shard.poison(0xA5)
     assert ck.restore(ck.file_name(10), stream.cuda_stream) == 10
     stream.synchronize()
-    for k, got in enumerate(shard.readback_all()):
+    for k, got in enumerate(gu.readback_all(shard)):
         assert np.array_equal(got, shards.host_values(spec, k)), spec.tensors[k].name
     if shard.flat:
         used = [np.zeros(n, dtype=bool) for n in spec.flat_buffers]
         for t in spec.tensors:
             used[t.buffer][t.offset:t.offset + t.nbytes] = True
         for f, u in zip(shard.flat, used):
-            assert np.all(f.download()[~u] == 0xA5)
+            assert np.all(gu.download(f)[~u] == 0xA5)
     # the oracle's restore agrees (file -> host arrays)
     blank = [np.zeros(t.nbytes, dtype=np.uint8) for t in spec.tensors]
     assert oracle.restore_file(ck.file_name(10), shard.oracle_tensors(blank)) == 10
@@ -246,7 +247,7 @@ def test_restore_rejects_bad_files(tmp_path):
     shard.poison()
     assert ck.restore(ck.file_name(1), stream.cuda_stream) == 1
     stream.synchronize()
-    assert all(np.array_equal(g, shards.host_values(spec, k)) for k, g in enumerate(shard.readback_all()))
+    assert all(np.array_equal(g, shards.host_values(spec, k)) for k, g in enumerate(gu.readback_all(shard)))
     ck.snapshot_async(2, stream.cuda_stream)
     ck.flush(2)
     assert open(ck.file_name(2), "rb").read()[24:] == good[24:]
@@ -329,7 +330,7 @@ def test_default_stream_and_default_config(big_dir):
     shard.update(1, harness.NullStream())
     ck.snapshot_async(1, 0)
     ck.wait_immutable_window_end(0, host_block=True)
-    host = shard.readback_all()
+    host = gu.readback_all(shard)
     ck.flush(1)
     assert os.path.getsize(ck.file_name(1)) == ck.layout()["file_bytes"] == 1_742_157_312 + 600_576 + ck.layout()["header_bytes"]
     assert oracle.compare_file(shard.oracle_tensors(host), 1, ck.file_name(1)) is None
@@ -360,14 +361,14 @@ def test_edge_sizes_and_a_tensor_beyond_4_gib(big_dir):
     assert lay["n_superchunks"] >= 9 and lay["data_bytes"] > (4 << 30)
     ck.snapshot_async(7, stream.cuda_stream)
     ck.wait_immutable_window_end(stream.cuda_stream)
-    host = shard.readback_all()
+    host = gu.readback_all(shard)
     ck.flush(7)
     assert oracle.compare_file(shard.oracle_tensors(host), 7, ck.file_name(7)) is None
-    whole = shard.flat[0].download()
+    whole = gu.download(shard.flat[0])
     shard.poison(0x5A)
     assert ck.restore(ck.file_name(7), stream.cuda_stream) == 7
     stream.synchronize()
-    after = shard.flat[0].download()
+    after = gu.download(shard.flat[0])
     used = np.zeros(spec.flat_buffers[0], dtype=bool)
     for t in tensors:
         used[t.offset:t.offset + t.nbytes] = True

@@ -9,6 +9,7 @@ import pytest
 from oracle import oracle
 from paper_2406_10707_amd import binding as B
 from paper_2406_10707_amd import harness, shards
+from tests import gpu_util as gu
 
 pytestmark = pytest.mark.gpu
 
@@ -56,7 +57,7 @@ def test_second_tier_receives_the_newest_snapshot(keep_last, io_mode, o_direct, 
     present = sorted(f for f in os.listdir(slow))
     assert present == [os.path.basename(ck.second_tier_file_name(it)) for it in done[-2:]], (present, states)   # second-tier retention: 2
     for it in done[-2:]:
-        host = [c.download() for c in clones[it]]
+        host = [gu.download(c) for c in clones[it]]
         assert oracle.compare_file(shard.oracle_tensors(host), it, ck.second_tier_file_name(it)) is None, f"iteration {it}"
         assert ck.stats(it)["host_tier2_ms"] > 0
     for it in range(1, n + 1):
@@ -71,11 +72,11 @@ def test_second_tier_receives_the_newest_snapshot(keep_last, io_mode, o_direct, 
     keep = range(n - keep_last + 1, n + 1) if keep_last else range(1, n + 1)
     assert names == [os.path.basename(ck.file_name(it)) for it in keep]
     # restore from the slower tier
-    want = [c.download() for c in clones[n]]
+    want = [gu.download(c) for c in clones[n]]
     shard.poison(0xA5)
     assert ck.restore(ck.second_tier_file_name(n), stream.cuda_stream) == n
     stream.synchronize()
-    assert all(np.array_equal(g, w) for g, w in zip(shard.readback_all(), want))
+    assert all(np.array_equal(g, w) for g, w in zip(gu.readback_all(shard), want))
     ck.destroy()
 
 
@@ -127,7 +128,7 @@ def test_restart_from_the_newest_whole_file(tmp_path):
         shard.update(it, stream)
         ck.snapshot_async(it, stream.cuda_stream)
         ck.wait_immutable_window_end(stream.cuda_stream, host_block=True)
-        states[it] = shard.readback_all()
+        states[it] = gu.readback_all(shard)
     ck.flush()
     newest = ck.file_name(30)
     ck.destroy()
@@ -141,7 +142,7 @@ def test_restart_from_the_newest_whole_file(tmp_path):
     ck2.register_tensors(shard.descs())
     assert ck2.restore(path, stream.cuda_stream) == 20
     stream.synchronize()
-    assert all(np.array_equal(g, w) for g, w in zip(shard.readback_all(), states[20]))
+    assert all(np.array_equal(g, w) for g, w in zip(gu.readback_all(shard), states[20]))
     with pytest.raises(B.CkptError) as e:
         ck2.restore(newest, stream.cuda_stream)
     assert e.value.code == B.CKPT_EFORMAT

@@ -158,6 +158,49 @@ def test_compare_reports_first_differing_offset(tmp_path):
     assert oracle.compare_file(ts, 1, p) == len(whole)
 
 
+@pytest.mark.parametrize("config", [1, 5])
+def test_span_comparison_covers_the_file_piece_by_piece(config, tmp_path):
+    """The piecewise comparison used on shards too large to hold twice: every single-byte change anywhere in
+    the file (header, payload, padding) is reported by exactly the piece that owns the byte, at its offset,
+    and by no other piece; pieces fed only their own tensors' bytes accept the independent writer's file."""
+    spec = shards.make_shard(config, tiny=True)
+    ts = [(t.name, t.dtype, t.shape, shards.host_values(spec, k)) for k, t in enumerate(spec.tensors)]
+    whole = bytearray(fr.expected_file([(n, d, s, x.tobytes()) for n, d, s, x in ts], 9))    # not the oracle's own writer
+    p = str(tmp_path / "f.dsl")
+    open(p, "wb").write(whole)
+    cmp = oracle.SpanComparer(ts)
+    n = len(ts)
+    cuts = [0, 1, 2, n // 3, n // 2, n - 1, n]
+    pieces = [(a, b) for a, b in zip(cuts, cuts[1:]) if b > a]
+
+    def run():
+        return [cmp.compare(9, a, [ts[k][3] for k in range(a, b)], p) for a, b in pieces]
+
+    assert run() == [None] * len(pieces)
+    _, table = fr.parse(bytes(whole))
+    hb = table[0]["offset"]
+    rng = np.random.default_rng(config)
+    picks = [0, 20, hb - 1, hb, len(whole) - 1]                                    # header, first data byte, last pad byte
+    for e in (table[1], table[n // 2], table[-1]):
+        picks += [e["offset"], e["offset"] + e["nbytes"] - 1]                      # first and last payload byte of a tensor
+        if e["nbytes"] % 4096:
+            picks.append(e["offset"] + e["nbytes"])                                # first padding byte behind it
+    picks += [int(x) for x in rng.integers(0, len(whole), 12)]
+    starts = [table[a]["offset"] if a < n else len(whole) for a, _ in pieces]
+    for off in picks:
+        bad = bytearray(whole)
+        bad[off] ^= 0x21
+        open(p, "wb").write(bad)
+        owner = 0 if off < hb else max(i for i, s in enumerate(starts) if s <= off)
+        assert run() == [off if i == owner else None for i in range(len(pieces))], off
+    open(p, "wb").write(whole[:-4096])                                             # wrong size: every piece says so
+    assert all(r == len(whole) - 4096 for r in run())
+    open(p, "wb").write(whole)
+    assert cmp.compare(10, 0, [ts[0][3]], p) == 16                                  # the iteration field belongs to piece 0
+    with pytest.raises(ValueError):
+        cmp.compare(9, 0, [ts[0][3][:-1]], p)
+
+
 def test_rejects_bad_descriptions():
     good = np.zeros(8, dtype=np.uint8)
     with pytest.raises(oracle.OracleError):
