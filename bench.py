@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--policy", choices=["d2h", "pack"], default="d2h")
     ap.add_argument("--io-mode", choices=["auto", "pwrite", "mmap"], default="auto")
     ap.add_argument("--o-direct", type=int, default=0, help="1: checkpoint files are written with O_DIRECT and fsync'ed (a real disk as the sink)")
+    ap.add_argument("--fsync", type=int, default=1, help="1: every file is fsync'ed before and its directory after the commit (the library's "
+                                                         "default: a file ckpt_flush reports is durable, as far as the sink can be); 0: no fsync")
     ap.add_argument("--keep-last", type=int, default=1, help="checkpoint files kept; older ones are recycled in place (0: keep all)")
     ap.add_argument("--prealloc", type=int, default=2, help="spare files pre-allocated at registration")
     ap.add_argument("--direct-min-mib", type=float, default=0.0,
@@ -154,7 +156,7 @@ def main():
               "snapshot path of a shard needs no exchange between GPUs)" % args.gpus, file=sys.stderr)
         sys.exit(2)
     from paper_2406_10707_amd import build as build_lib
-    build_lib.ensure_built()           # compiles only if no library is there at all
+    build_lib.ensure_built()           # loads what is built; rebuilds only a missing or outdated library
     from paper_2406_10707_amd import binding as B
     from paper_2406_10707_amd import harness, shards
 
@@ -210,7 +212,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                         dev_staging_bytes=staging_bytes, n_dma_streams=args.dma_streams, n_io_threads=args.io_threads,
                         window_policy=policy, direct_min_bytes=int(args.direct_min_mib * (1 << 20)),
                         io_mode={"auto": B.CKPT_IO_AUTO, "pwrite": B.CKPT_IO_PWRITE, "mmap": B.CKPT_IO_MMAP}[args.io_mode],
-                        o_direct=args.o_direct, fsync_on_commit=args.o_direct,
+                        o_direct=args.o_direct, fsync_on_commit=1 if args.fsync else -1,
                         keep_last=args.keep_last, prealloc_files=args.prealloc if args.keep_last else 0)
     say("ckpt_init + ckpt_register_tensors (ring pinned and touched, spare files pre-allocated)")
     t0 = time.perf_counter()
@@ -456,7 +458,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                    "ring_gib": args.ring_gib, "dma_chunk_mib": args.chunk_mib, "pack_superchunk_mib": args.superchunk_mib,
                    "staging_gib": staging_gib, "dma_streams": args.dma_streams, "io_threads": args.io_threads,
                    "hw_queues": int(os.environ["GPU_MAX_HW_QUEUES"]), "device": info["name"],
-                   "hip_runtime": info["hip_runtime_version"], "io_mode": args.io_mode, "o_direct": args.o_direct, "keep_last": args.keep_last,
+                   "hip_runtime": info["hip_runtime_version"], "io_mode": args.io_mode, "o_direct": args.o_direct, "fsync_on_commit": args.fsync, "keep_last": args.keep_last,
                    "prealloc_files": args.prealloc, "sink": out_dir.rsplit("/", 1)[0],
                    "direct_min_mib": args.direct_min_mib, "direct_tensors": lay["n_direct_tensors"],
                    "direct_bytes": lay["direct_bytes"], "copy_segments": lay["n_segments"]},

@@ -92,7 +92,10 @@ typedef struct {
     int32_t o_direct;               /* 1: open files with O_DIRECT (all offsets and sizes are 4 KiB multiples); data then
                                        passes through a 4 MiB bounce buffer per I/O thread, because the kernel does not
                                        accept the pinned ring's pages for direct I/O */
-    int32_t fsync_on_commit;        /* 1: fsync (and msync) before the rename that commits a file */
+    int32_t fsync_on_commit;        /* 0 (default) or 1: the file is fsync'ed (and its mapping msync'ed) before the rename that
+                                       commits it, and the directory is fsync'ed after it, so that a file ckpt_flush has
+                                       reported survives a power loss. -1: no fsync at all (a memory file system as the
+                                       sink, or measurements that must not include the disk's flush) */
     int32_t io_mode;                /* ckpt_io_mode */
     int32_t keep_last;              /* 0: every checkpoint file stays. K > 0: once a snapshot is committed only the K
                                        newest files keep their names; older ones are retired to hidden spare files whose
@@ -216,14 +219,20 @@ void ckpt_plan_destroy(ckpt_plan *plan);
  * The ring is reused by every later snapshot and restore (paper: pre-allocated, pre-pinned cache). */
 int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out);
 
-/* Registers the shard's tensors, once per context: builds header, file offsets, the tile table
+/* The first two phases of the paper's three-phase save (Implementation section: list the tensors, compute
+ * the header with a file offset for each), done once instead of at every checkpoint, plus the set-up of the
+ * "coalescing of shards" design principle on the device side.
+ * Registers the shard's tensors, once per context: builds header, file offsets, the tile table
  * (uploaded to the device) and the chunk and copy-segment tables, allocates device staging and
  * pre-allocates the spare files the configuration asks for. Every device range is checked to be
  * memory of this GPU (CKPT_EINVAL otherwise). CKPT_ESTATE if tensors are already registered.
  * Overlapping device ranges are allowed (serialized twice). */
 int ckpt_register_tensors(ckpt_ctx *ctx, const ckpt_tensor_desc *tensors, size_t n);
 
-/* Requests the snapshot of iteration `iter`: the state captured is what the tensors hold once all
+/* A checkpoint request as the "lazy non-blocking copies" design principle defines it: it returns at once,
+ * the copies run while the next forward and backward passes leave the state untouched (the paper's section on
+ * the immutability of parameters and optimizer state), and a full host cache delays the copies, not the caller.
+ * Requests the snapshot of iteration `iter`: the state captured is what the tensors hold once all
  * work already enqueued on `hip_stream_compute` has run. Returns without waiting for any copy; the
  * caller goes on with the next forward/backward pass. Pack kernels, copies and file writes are
  * issued by library threads; if the ring is full they wait for flushed slots (never for the
@@ -246,12 +255,19 @@ int ckpt_wait_immutable_window_end(ckpt_ctx *ctx, void *hip_stream_compute, int3
  * CKPT_EINVAL for CKPT_WINDOW_PACK on a context with direct_min_bytes set. */
 int ckpt_set_window_policy(ckpt_ctx *ctx, int32_t policy);
 
-/* Blocks until the file of `iter` (or of every requested snapshot, CKPT_ITER_ALL) is written,
- * optionally fsync'ed, and renamed to its final name. Returns the latched asynchronous error, if
- * any, and clears it. CKPT_EINVAL if `iter` was never requested. */
+/* The end of the "streamlined multi-level flushing" design principle (every piece goes from the host cache to
+ * storage as soon as it has arrived) and the single-participant form of the paper's asynchronous distributed
+ * consolidation: a checkpoint counts once all of it is on storage under its final name.
+ * Blocks until the file of `iter` (or of every requested snapshot, CKPT_ITER_ALL) is written, fsync'ed
+ * (unless fsync_on_commit is -1) and renamed to its final name. Returns the latched asynchronous error, if
+ * any, and clears it; a snapshot that failed (its file then never gets its final name and is removed) also
+ * reports its own failure whenever it is asked about by `iter`, even after another call has taken the
+ * latched error. CKPT_EINVAL if `iter` was never requested. */
 int ckpt_flush(ckpt_ctx *ctx, uint64_t iter);
 
-/* Reads a checkpoint file back into the registered tensors: header checked against the
+/* The way back, which the paper names only as the purpose of a checkpoint (Background: resuming after a
+ * failure); it runs the snapshot path in reverse through the same host cache.
+ * Reads a checkpoint file back into the registered tensors: header checked against the
  * registration (CKPT_EFORMAT / CKPT_EMISMATCH), data read into ring slots by the I/O threads,
  * copied host-to-device into staging, scattered by a kernel (tensors that the hybrid path copies
  * directly are written by the DMA engines straight from the ring slot; host-resident objects by
@@ -298,6 +314,20 @@ int ckpt_find_latest(const char *dir, uint64_t *iter_out, char *path_buf, size_t
  * written then, so a first call with cap 0 sizes the buffer). CKPT_EFORMAT for a file that is not a
  * whole checkpoint, CKPT_EIO if it cannot be read. */
 int ckpt_describe_file(const char *path, char *buf, size_t cap, size_t *needed_out);
+
+/* The pack step on its own, without a context (the paper's coalescing of a shard's many tensors into one
+ * contiguous region, done here on the device instead of in host memory): gathers the n tensors, in order,
+ * into the image of their checkpoint data region at device address dev_dst: tensor k's bytes at
+ * sum over j < k of align_up(nbytes_j, 4096), zero bytes up to the next multiple of 4096 behind each, i.e.
+ * the bytes a checkpoint file of these tensors holds from header_bytes on (docs/FORMAT.md). Of a descriptor
+ * only dev_ptr (any byte alignment) and nbytes (> 0) are read; name, dtype and shape are ignored. Tensors
+ * and destination must be device memory of the CURRENT device (hipSetDevice), inside their allocations;
+ * dev_dst 16-byte aligned, dst_bytes at least the size of the data region; source and destination must
+ * not overlap. The tile table the kernel walks is built on the device by a kernel of its own, in a
+ * temporary device allocation: the call allocates, enqueues on hip_stream (after whatever is already
+ * there), waits for the stream, and frees. CKPT_EINVAL for a bad argument (nothing is launched then),
+ * CKPT_ENOMEM, CKPT_EHIP. */
+int ckpt_pack_image(const ckpt_tensor_desc *tensors, size_t n, void *dev_dst, uint64_t dst_bytes, void *hip_stream);
 
 int ckpt_get_layout(ckpt_ctx *ctx, ckpt_layout *out);
 /* Measurements of one requested snapshot; CKPT_EINVAL if unknown (records of the 1024 most recent

@@ -104,6 +104,7 @@ _SIGS = {
     "ckpt_second_tier_file_name": (C.c_int, [_vp, _u64, C.c_char_p, C.c_size_t]),
     "ckpt_describe_file": (C.c_int, [C.c_char_p, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)]),
     "ckpt_find_latest": (C.c_int, [C.c_char_p, C.POINTER(_u64), C.c_char_p, C.c_size_t]),
+    "ckpt_pack_image": (C.c_int, [C.POINTER(ckpt_tensor_desc), C.c_size_t, _vp, _u64, _vp]),
     "ckpt_get_layout": (C.c_int, [_vp, C.POINTER(ckpt_layout)]),
     "ckpt_get_stats": (C.c_int, [_vp, _u64, C.POINTER(ckpt_stats)]),
     "ckpt_file_name": (C.c_int, [_vp, _u64, C.c_char_p, C.c_size_t]),
@@ -204,6 +205,13 @@ def find_latest(directory):
     buf = C.create_string_buffer(4096)
     _check(lib.ckpt_find_latest(os.fsencode(directory), C.byref(it), buf, 4096))
     return it.value, os.fsdecode(buf.value)
+
+
+def pack_image(tensors, dev_dst, dst_bytes, stream):
+    """ckpt_pack_image: tensors as for register_tensors; the data-region image lands at device address dev_dst."""
+    tensors = list(tensors)
+    arr, keep = make_descs(tensors)
+    _check(lib.ckpt_pack_image(arr, len(tensors), dev_dst, dst_bytes, stream))
 
 
 class Plan:

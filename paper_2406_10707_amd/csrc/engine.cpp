@@ -212,6 +212,11 @@ int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out) {
         if ((e = hipEventCreateWithFlags(&ev, hipEventBlockingSync)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
         c->ev_job_tail.push_back(ev);
     }
+    for (int k = 0; k < kBoundaryEvents; k++) {   // one per snapshot in flight; none is created on the per-iteration path
+        hipEvent_t ev;
+        if ((e = hipEventCreate(&ev)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
+        c->ev_boundary_free.push_back(ev);
+    }
     if ((e = hipEventCreate(&c->ev_first_copy)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
     if ((e = hipEventCreate(&c->ev_user)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
     void *ring = nullptr;
@@ -316,9 +321,6 @@ int ckpt_register_tensors(ckpt_ctx *c, const ckpt_tensor_desc *tensors, size_t n
     return CKPT_OK;
 }
 
-// Creates a file of `bytes` bytes with all its pages allocated (zero-filled), several threads writing.
-
-
 int ckpt_snapshot_async(ckpt_ctx *c, uint64_t iter, void *stream) {
     auto t0 = Clock::now();
     if (!c) return fail(CKPT_EINVAL, "null context");
@@ -329,6 +331,7 @@ int ckpt_snapshot_async(ckpt_ctx *c, uint64_t iter, void *stream) {
     {
         std::lock_guard<std::mutex> lk(c->mu);
         if (c->restoring) return fail(CKPT_ESTATE, "restore in progress");
+        if (c->tier2_enabling) return fail(CKPT_ESTATE, "the second tier is still being set up");
         if (c->last_snap && !c->last_snap->window_closed)
             return fail(CKPT_ESTATE, "previous snapshot's window was not closed (call ckpt_wait_immutable_window_end before the update)");
         auto it = c->snaps.find(iter);
@@ -346,13 +349,19 @@ int ckpt_snapshot_async(ckpt_ctx *c, uint64_t iter, void *stream) {
         for (const auto &t : c->plan.tensors)
             if (t.host) memcpy(sp->host_capture.data() + t.capture_off, reinterpret_cast<const void *>(t.dev_addr), t.nbytes);
     }
-    HIP_TRY(c, hipEventCreate(&sp->ev_boundary));
+    {   // a boundary event from the pool made at set-up (it comes back when the snapshot's last copy has landed)
+        std::lock_guard<std::mutex> lk(c->mu);
+        if (!c->ev_boundary_free.empty()) { sp->ev_boundary = c->ev_boundary_free.back(); c->ev_boundary_free.pop_back(); }
+    }
+    if (!sp->ev_boundary) HIP_TRY(c, hipEventCreate(&sp->ev_boundary));   // more snapshots in flight than the pool foresaw
     hipError_t e = hipEventRecord(sp->ev_boundary, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) { (void)hipEventDestroy(sp->ev_boundary); return fail(CKPT_EHIP, std::string("record boundary: ") + hipGetErrorString(e)); }
+    if (e != hipSuccess) {
+        std::lock_guard<std::mutex> lk(c->mu);
+        c->ev_boundary_free.push_back(sp->ev_boundary);
+        return fail(CKPT_EHIP, std::string("record boundary: ") + hipGetErrorString(e));
+    }
     {
         std::lock_guard<std::mutex> lk(c->mu);
-        auto old = c->snaps.find(iter);
-        if (old != c->snaps.end() && old->second->ev_boundary) (void)hipEventDestroy(old->second->ev_boundary);
         sp->policy = c->cfg.window_policy;
         // records of long-finished snapshots are dropped, lowest iteration first (a long run takes thousands)
         while (c->snaps.size() >= kMaxSnapRecords) {
@@ -410,6 +419,7 @@ int ckpt_set_window_policy(ckpt_ctx *c, int32_t policy) {
 
 int ckpt_flush(ckpt_ctx *c, uint64_t iter) {
     if (!c) return fail(CKPT_EINVAL, "null context");
+    std::shared_ptr<Snap> failed;
     {
         std::unique_lock<std::mutex> lk(c->mu);
         if (iter == CKPT_ITER_ALL) {
@@ -424,9 +434,17 @@ int ckpt_flush(ckpt_ctx *c, uint64_t iter) {
             auto sp = it->second;
             c->cv_state.wait(lk, [&] { return sp->committed; });
             sp->window_closed = true;   // its copies are over, so its window is closed too
+            failed = sp;
         }
     }
-    return take_async_error(c);
+    int r = take_async_error(c);
+    if (r) return r;
+    // the latch may have been taken by an earlier call; a snapshot that failed still says so when asked about
+    if (failed) {
+        std::lock_guard<std::mutex> lk(c->mu);
+        if (failed->failed) return fail(failed->fail_code, failed->fail_msg);
+    }
+    return CKPT_OK;
 }
 
 int ckpt_get_layout(ckpt_ctx *c, ckpt_layout *out) {
@@ -474,7 +492,6 @@ int ckpt_file_name(ckpt_ctx *c, uint64_t iter, char *buf, size_t cap) {
     return CKPT_OK;
 }
 
-// Everything of a restore that can fail half-way; the caller cleans up the ring afterwards.
 int ckpt_destroy(ckpt_ctx *c) {
     if (!c) return CKPT_OK;
     int rc = CKPT_OK;
@@ -509,6 +526,7 @@ int ckpt_destroy(ckpt_ctx *c) {
     if (c->pack_stream) (void)hipStreamSynchronize(c->pack_stream);
     for (auto s : c->dma) (void)hipStreamSynchronize(s);
     for (auto &kv : c->snaps) if (kv.second->ev_boundary) (void)hipEventDestroy(kv.second->ev_boundary);
+    for (auto ev : c->ev_boundary_free) (void)hipEventDestroy(ev);
     for (auto ev : c->ev_slot) (void)hipEventDestroy(ev);
     for (auto ev : c->ev_pack_start) (void)hipEventDestroy(ev);
     for (auto ev : c->ev_packed) (void)hipEventDestroy(ev);

@@ -86,6 +86,11 @@ struct Snap {
     int policy = CKPT_WINDOW_D2H;           // window policy in force when the snapshot was requested
     int tier2_state = CKPT_TIER2_NONE;      // ckpt_tier2_state
     double tier2_ms = -1;                   // host: copy to the second tier, open to rename
+    // A failure of THIS snapshot (open, header, copy, event, chunk write, sync): its file never gets a final
+    // name, whatever happens to the context-wide latch in the meantime. Guarded by the context mutex.
+    bool failed = false;
+    int fail_code = 0;
+    std::string fail_msg;
 };
 
 struct IoJob {
@@ -97,6 +102,7 @@ struct IoJob {
     uint64_t seq = 0;             // READ: chunk sequence number
 };
 
+constexpr int kBoundaryEvents = 8;          // boundary events created at set-up (snapshots in flight at a time)
 constexpr size_t kMaxSnapRecords = 1024;   // per-snapshot records (measurements, states) kept per context
 
 enum SlotState : int { SLOT_FREE = 0, SLOT_BUSY = 1, SLOT_READ_DONE = 2 };
@@ -147,7 +153,7 @@ struct ckpt_ctx {
     std::map<uint64_t, FileSlot> kept;     // committed files that still carry their names
     uint64_t spare_seq = 0;
     // second tier: committed files are copied on to a slower, durable directory by a thread of their own
-    bool tier2_on = false, tier2_direct = false, tier2_stop = false;
+    bool tier2_on = false, tier2_enabling = false, tier2_direct = false, tier2_stop = false;
     std::string tier2_dir;
     int tier2_threads = 4, tier2_keep = 1, tier2_mode = CKPT_TIER2_NEWEST;
     std::thread tier2_thread, tier2_unlinker;   // the latter is touched by the second-tier thread only (and by destroy after joining it)
@@ -160,8 +166,17 @@ struct ckpt_ctx {
     int tier2_code = 0;                    // first failure of a second-tier copy, reported by ckpt_wait_second_tier
     std::string tier2_err;
 
+    std::vector<hipEvent_t> ev_boundary_free;             // boundary events, created at set-up, handed out per request
+
     void latch(int code, const std::string &msg) {
         std::lock_guard<std::mutex> lk(mu);
+        if (async_code == 0) { async_code = code; async_err = msg; }
+        cv_state.notify_all();
+    }
+    // Marks one snapshot as failed (first failure wins) and latches the error for the caller's next call.
+    void fail_snapshot(dsllm::Snap *s, int code, const std::string &msg) {
+        std::lock_guard<std::mutex> lk(mu);
+        if (!s->failed) { s->failed = true; s->fail_code = code; s->fail_msg = msg; }
         if (async_code == 0) { async_code = code; async_err = msg; }
         cv_state.notify_all();
     }
@@ -178,6 +193,16 @@ inline std::string file_name_for(const std::string &dir, uint64_t iter) {
     char buf[64];
     snprintf(buf, sizeof buf, "/ckpt_iter%020llu.dsl", (unsigned long long)iter);
     return dir + buf;
+}
+
+// Makes a rename in `dir` durable: the directory entry itself has to reach the disk.
+inline bool fsync_dir(const std::string &dir, std::string *err) {
+    int fd = open(dir.c_str(), O_RDONLY | O_DIRECTORY);
+    if (fd < 0) { *err = dir + ": open: " + strerror(errno); return false; }
+    const bool ok = fsync(fd) == 0;
+    if (!ok) *err = dir + ": fsync: " + strerror(errno);
+    close(fd);
+    return ok;
 }
 
 inline bool pwrite_all(int fd, const uint8_t *p, uint64_t n, uint64_t off, std::string *err) {

@@ -16,8 +16,8 @@ static void finish_d2h_stats(ckpt_ctx *c, Snap *s) {
         if (hipEventElapsedTime(&ms, c->ev_first_copy, c->ev_job_tail[k]) == hipSuccess && ms > span) span = ms;
     }
     if (hipEventElapsedTime(&ms, s->ev_boundary, c->ev_packed[c->plan.n_superchunks - 1]) == hipSuccess) req_pack = ms;
-    (void)hipEventDestroy(s->ev_boundary);
     std::lock_guard<std::mutex> lk(c->mu);
+    c->ev_boundary_free.push_back(s->ev_boundary);   // back to the pool
     s->ev_boundary = nullptr;
     s->pack_ms_sum = pack_sum;
     s->req_to_d2h_end_ms = req_d2h;
@@ -94,7 +94,7 @@ void dsllm::io_thread_main(ckpt_ctx *c) {
         hipError_t he = hipEventSynchronize(c->ev_slot[job.slot]);
         auto tw1 = Clock::now();
         s->io_wait_us += uint64_t(ms_between(tw0, tw1) * 1000.0);
-        if (he != hipSuccess) c->latch(CKPT_EHIP, std::string("copy event: ") + hipGetErrorString(he));
+        if (he != hipSuccess) c->fail_snapshot(s, CKPT_EHIP, std::string("copy event: ") + hipGetErrorString(he));
         if (job.file_off == c->plan.header_bytes) {
             std::lock_guard<std::mutex> lk(c->mu);
             s->t_first_chunk = Clock::now();
@@ -103,7 +103,7 @@ void dsllm::io_thread_main(ckpt_ctx *c) {
         if (job.last) {
             for (size_t k = 0; k < c->dma.size(); k++) {
                 he = hipEventSynchronize(c->ev_job_tail[k]);
-                if (he != hipSuccess) c->latch(CKPT_EHIP, std::string("tail event: ") + hipGetErrorString(he));
+                if (he != hipSuccess) c->fail_snapshot(s, CKPT_EHIP, std::string("tail event: ") + hipGetErrorString(he));
             }
             finish_d2h_stats(c, s);
         }
@@ -111,7 +111,7 @@ void dsllm::io_thread_main(ckpt_ctx *c) {
         else if (s->fd >= 0) {
             bool ok = c->cfg.o_direct ? (bounce ? direct_write(s->fd, bounce, slot_ptr, job.nbytes, job.file_off, &err) : (err = "no bounce buffer", false))
                                       : pwrite_all(s->fd, slot_ptr, job.nbytes, job.file_off, &err);
-            if (!ok) c->latch(CKPT_EIO, s->tmp_path + ": " + err);
+            if (!ok) c->fail_snapshot(s, CKPT_EIO, s->tmp_path + ": " + err);
         }
         {
             std::lock_guard<std::mutex> lk(c->mu);
@@ -120,22 +120,26 @@ void dsllm::io_thread_main(ckpt_ctx *c) {
         }
         s->io_copy_us += uint64_t(ms_between(tw1, Clock::now()) * 1000.0);
         if (s->chunks_left.fetch_sub(1) == 1) {
-            // last chunk written: commit
+            // last chunk written: commit. Whether the file gets its final name depends on this snapshot's own
+            // record of failures, not on the context-wide latch (a call in between may have taken and cleared that).
             if (s->fd >= 0) {
                 const bool retain = c->cfg.keep_last > 0;
-                if (s->map && c->cfg.fsync_on_commit && msync(s->map, c->plan.file_bytes(), MS_SYNC) != 0)
-                    c->latch(CKPT_EIO, s->tmp_path + ": msync: " + strerror(errno));
-                if (c->cfg.fsync_on_commit && fsync(s->fd) != 0) c->latch(CKPT_EIO, s->tmp_path + ": fsync: " + strerror(errno));
+                const bool sync = c->cfg.fsync_on_commit != 0;
+                if (s->map && sync && msync(s->map, c->plan.file_bytes(), MS_SYNC) != 0)
+                    c->fail_snapshot(s, CKPT_EIO, s->tmp_path + ": msync: " + strerror(errno));
+                if (sync && fsync(s->fd) != 0) c->fail_snapshot(s, CKPT_EIO, s->tmp_path + ": fsync: " + strerror(errno));
                 FileSlot fs;
                 fs.path = s->final_path; fs.fd = s->fd; fs.map = s->map; fs.map_bytes = c->plan.file_bytes();
                 s->fd = -1; s->map = nullptr;
                 bool had_error;
-                { std::lock_guard<std::mutex> lk(c->mu); had_error = c->async_code != 0; }
+                { std::lock_guard<std::mutex> lk(c->mu); had_error = s->failed; }
                 // a file gets its final name only when whole
                 if (!had_error && rename(s->tmp_path.c_str(), s->final_path.c_str()) != 0) {
-                    c->latch(CKPT_EIO, s->final_path + ": rename: " + strerror(errno));
+                    c->fail_snapshot(s, CKPT_EIO, s->final_path + ": rename: " + strerror(errno));
                     had_error = true;
                 }
+                std::string derr;
+                if (!had_error && sync && !fsync_dir(c->out_dir, &derr)) c->fail_snapshot(s, CKPT_EIO, derr);   // the name is there, its durability is not
                 if (retain && !had_error) {
                     // files older than the newest keep_last become spares, overwritten in place later
                     std::lock_guard<std::mutex> lk(c->mu);
@@ -152,13 +156,13 @@ void dsllm::io_thread_main(ckpt_ctx *c) {
                     }
                 } else {
                     fs.close_all();
-                    if (had_error) unlink(s->tmp_path.c_str());
+                    if (had_error) unlink(s->tmp_path.c_str());   // a torn file, under its temporary (or spare) name: gone
                 }
             }
             std::lock_guard<std::mutex> lk(c->mu);
             s->t_committed = Clock::now();
             s->committed = true;
-            if (c->async_code == 0) tier2_offer_locked(c, job.snap);
+            if (!s->failed) tier2_offer_locked(c, job.snap);
             c->cv_state.notify_all();
         }
     }

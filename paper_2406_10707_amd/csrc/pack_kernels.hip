@@ -14,6 +14,7 @@
 #include <stdint.h>
 
 #include "../../include/ckpt.h"
+#include "tile_batch.hpp"
 
 namespace dsllm {
 
@@ -36,6 +37,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #ifndef DSLLM_PACK_UNROLL_SHIFT
 #define DSLLM_PACK_UNROLL_SHIFT 4
 #endif
+constexpr uint64_t kPackTileBytes = 32 * 1024;   // the planner's tile size (plan.hpp: kTileBytes)
 constexpr int kWavesPerBlock = DSLLM_PACK_WAVES_PER_BLOCK;
 constexpr int kBlock = 64 * kWavesPerBlock;
 constexpr int kUnroll = DSLLM_PACK_UNROLL;             // aligned path: 16-byte words per lane in flight
@@ -289,7 +291,44 @@ __global__ __launch_bounds__(kBlock) void scatter_kernel(const ckpt_tile *__rest
     if (lane < tail) dst[done + lane] = src[done + lane];
 }
 
+// ---------------------------------------------------------------- tile table built on the device
+
+// The tile table of a tensor list, written by the device itself: one block per tensor, one thread per
+// tile. The descriptors travel in the kernel arguments (a batch of up to kTileBatch tensors per
+// launch), so nothing is copied from host memory and the launch can be recorded like any other.
+// Tile i of a tensor whose padded extent is [d0, dend) of the data region: the extent is cut at its
+// start and at every multiple of the tile size, exactly as the host planner cuts it.
+__global__ __launch_bounds__(256) void build_tiles_kernel(TileBatch bt, ckpt_tile *__restrict__ table) {
+    const uint32_t k = blockIdx.x;
+    if (k >= bt.count) return;
+    const uint64_t T = kPackTileBytes;
+    const uint64_t d0 = bt.data_off[k], nbytes = bt.nbytes[k], src = bt.src[k];
+    const uint64_t dend = d0 + (nbytes + 4095) / 4096 * 4096;
+    const uint32_t n = bt.first_tile[k + 1] - bt.first_tile[k];
+    ckpt_tile *out = table + bt.first_tile[k];
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) {
+        const uint64_t start = i == 0 ? d0 : (d0 / T + i) * T;
+        uint64_t stop = (d0 / T + i + 1) * T;
+        if (stop > dend) stop = dend;
+        const uint64_t rel = start - d0;
+        const uint64_t left = rel >= nbytes ? 0 : nbytes - rel;
+        ckpt_tile t;
+        t.src = src + rel;
+        t.dst_off = start;
+        t.copy_bytes = uint32_t(left < stop - start ? left : stop - start);
+        t.total_bytes = uint32_t(stop - start);
+        t.reserved = 0;
+        out[i] = t;
+    }
+}
+
 // ---------------------------------------------------------------- launchers (host)
+
+hipError_t launch_build_tiles(const TileBatch &bt, ckpt_tile *dev_table, hipStream_t stream) {
+    if (bt.count == 0) return hipSuccess;
+    hipLaunchKernelGGL(build_tiles_kernel, dim3(bt.count), dim3(256), 0, stream, bt, dev_table);
+    return hipGetLastError();
+}
 
 static inline unsigned grid_for(uint64_t n_tiles) { return unsigned((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock); }
 

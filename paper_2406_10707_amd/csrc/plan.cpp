@@ -26,7 +26,7 @@ int resolve_config(const ckpt_config *in, ResolvedConfig *out, std::string *err)
     c.n_io_threads = in->n_io_threads ? in->n_io_threads : 4;
     c.window_policy = in->window_policy;
     c.o_direct = in->o_direct;
-    c.fsync_on_commit = in->fsync_on_commit;
+    c.fsync_on_commit = in->fsync_on_commit < 0 ? 0 : 1;   // durable unless the caller opts out
     c.io_mode = in->io_mode;
     c.keep_last = in->keep_last;
     c.prealloc_files = in->prealloc_files;

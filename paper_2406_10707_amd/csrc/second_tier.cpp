@@ -90,6 +90,7 @@ static void tier2_copy(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
     if (src_fd >= 0) close(src_fd);
     if (err.empty() && rename(dst_tmp.c_str(), dst_final.c_str()) != 0) err = dst_final + ": rename: " + strerror(errno);
     if (!err.empty()) unlink(dst_tmp.c_str());
+    else fsync_dir(c->tier2_dir, &err);   // this tier is the durable one: the new name has to be on the disk too
     std::vector<uint64_t> drop;
     {
         std::lock_guard<std::mutex> lk(c->mu);
@@ -158,23 +159,32 @@ int ckpt_enable_second_tier(ckpt_ctx *c, const char *dir, int32_t n_threads, int
     if (n_threads < 0 || n_threads > 64 || keep_last < 0) return fail(CKPT_EINVAL, "second tier: n_threads must be 0..64 and keep_last >= 0");
     struct stat st;
     if (stat(dir, &st) != 0 || !S_ISDIR(st.st_mode)) return fail(CKPT_EIO, std::string(dir) + ": not a directory");
+    bool want_spare = false;
+    std::string spare;
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        if (c->tier2_on || c->tier2_enabling) return fail(CKPT_ESTATE, "second tier already enabled");
+        if (!c->snaps.empty()) return fail(CKPT_ESTATE, "second tier must be enabled before the first snapshot");
+        if (std::string(dir) == c->out_dir) return fail(CKPT_EINVAL, "second tier must be another directory than out_dir");
+        c->tier2_enabling = true;   // snapshots are refused until the tier is ready (ckpt_snapshot_async checks this)
+        want_spare = c->registered && c->cfg.prealloc_files > 0;
+        if (want_spare) spare = c->out_dir + "/.spare_" + std::to_string(getpid()) + "_" + std::to_string(c->spare_seq++) + ".dsl";
+    }
+    // the file under copy to this tier is exempt from recycling: one more spare keeps page allocation off the
+    // write path. Writing a whole file of zeros takes seconds to minutes: not under the context's mutex.
+    FileSlot fs;
+    std::string err;
+    const bool spare_ok = !want_spare || preallocate_file(spare, c->plan.file_bytes(), std::min(c->cfg.n_io_threads, 8),
+                                                          c->cfg.io_mode == CKPT_IO_MMAP, c->cfg.o_direct, &fs, &err);
     std::lock_guard<std::mutex> lk(c->mu);
-    if (c->tier2_on) return fail(CKPT_ESTATE, "second tier already enabled");
-    if (!c->snaps.empty()) return fail(CKPT_ESTATE, "second tier must be enabled before the first snapshot");
-    if (std::string(dir) == c->out_dir) return fail(CKPT_EINVAL, "second tier must be another directory than out_dir");
+    c->tier2_enabling = false;
+    if (!spare_ok) return fail(CKPT_EIO, err);
+    if (want_spare) c->spares.push_back(fs);
     c->tier2_dir = dir;
     c->tier2_threads = n_threads ? n_threads : 4;
     c->tier2_direct = o_direct != 0;
     c->tier2_keep = keep_last;
     c->tier2_mode = mode;
-    if (c->registered && c->cfg.prealloc_files > 0) {
-        // the file under copy to this tier is exempt from recycling: one more spare keeps page allocation off the write path
-        std::string spare = c->out_dir + "/.spare_" + std::to_string(getpid()) + "_" + std::to_string(c->spare_seq++) + ".dsl", err;
-        FileSlot fs;
-        if (!preallocate_file(spare, c->plan.file_bytes(), std::min(c->cfg.n_io_threads, 8), c->cfg.io_mode == CKPT_IO_MMAP, c->cfg.o_direct, &fs, &err))
-            return fail(CKPT_EIO, err);
-        c->spares.push_back(fs);
-    }
     c->tier2_on = true;
     c->tier2_thread = std::thread(tier2_thread_main, c);
     return CKPT_OK;

@@ -9,7 +9,7 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
     const Plan &p = c->plan;
     const uint64_t CH = c->cfg.dma_chunk_bytes, SC = c->cfg.pack_superchunk_bytes;
     const size_t nk = c->dma.size();
-    auto hip_fail = [&](const char *what, hipError_t e) { c->latch(CKPT_EHIP, std::string(what) + ": " + hipGetErrorString(e)); };
+    auto hip_fail = [&](const char *what, hipError_t e) { c->fail_snapshot(s, CKPT_EHIP, std::string(what) + ": " + hipGetErrorString(e)); };
     hipError_t e;
     double tier2_wait_ms = 0;
 
@@ -68,9 +68,9 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
         else if (!pwrite_all(s->fd, c->hdr_buf, p.header_bytes, 0, &ferr)) {}
     }
     if (!ferr.empty()) {
-        c->latch(CKPT_EIO, s->tmp_path + ": " + ferr);
+        c->fail_snapshot(s, CKPT_EIO, s->tmp_path + ": " + ferr);
         if (s->map) munmap(s->map, p.file_bytes());
-        if (s->fd >= 0) close(s->fd);
+        if (s->fd >= 0) { close(s->fd); unlink(s->tmp_path.c_str()); }
         s->map = nullptr; s->fd = -1;
     }
 

@@ -10,7 +10,7 @@ if ROOT not in sys.path:
 
 from paper_2406_10707_amd import build as _build_lib  # noqa: E402
 
-_build_lib.ensure_built()      # compiles only if no library is there at all
+_build_lib.ensure_built()      # loads what is built; rebuilds only a missing or outdated library
 
 
 def pytest_configure(config):

@@ -9,13 +9,31 @@
 #include <string>
 #include <vector>
 
+#include <atomic>
+#include <functional>
+
+#include <errno.h>
+#include <signal.h>
 #include <sys/stat.h>
+#include <sys/uio.h>
 #include <unistd.h>
 
 #include "../../include/ckpt.h"
 #include "hip/hip_runtime.h"
 
 thread_local dim3 threadIdx, blockIdx, blockDim, gridDim;
+
+// Every pwrite of the engine comes through here (hip/hip_runtime.h redirects the name). The hook sees
+// (fd, offset, size) and returns 0 to let the write happen or an errno value to make it fail.
+static std::function<int(int, off_t, size_t)> g_pwrite_hook;
+ssize_t emu_pwrite(int fd, const void *buf, size_t n, off_t off) {
+    if (g_pwrite_hook) {
+        const int e = g_pwrite_hook(fd, off, n);
+        if (e) { errno = e; return -1; }
+    }
+    struct iovec iov = {const_cast<void *>(buf), n};
+    return pwritev(fd, &iov, 1, off);
+}
 
 static uint64_t rng_state;
 static uint64_t rnd() {
@@ -198,8 +216,178 @@ static int scenario(const std::string &dir, int policy, int keep_last, int io_mo
     return 0;
 }
 
+// ---- a chunk write fails, the caller takes the latched error through a call about ANOTHER iteration,
+// then the failed snapshot's last chunk is written: its file must never get a final name.
+static int failed_chunk_scenario(const std::string &dir, int keep_last) {
+    std::string what = "failed chunk, keep_last " + std::to_string(keep_last);
+    const int n_tensors = 24;
+    std::vector<Tensor> ts;
+    for (int k = 0; k < n_tensors; k++) {
+        Tensor t;
+        t.lead = k % 16;
+        t.nbytes = 20000 + 7919 * k;
+        t.base = static_cast<uint8_t *>(aligned_alloc(16, (t.lead + t.nbytes + 15) / 16 * 16));
+        for (uint64_t i = 0; i < t.lead + t.nbytes; i++) t.base[i] = uint8_t(rnd());
+        t.name = "t" + std::to_string(k);
+        t.shape = int64_t(t.nbytes);
+        ts.push_back(t);
+    }
+    std::vector<ckpt_tensor_desc> descs;
+    for (auto &t : ts) {
+        ckpt_tensor_desc d{};
+        d.name = t.name.c_str(); d.dtype = CKPT_U8; d.ndim = 1; d.shape = &t.shape; d.dev_ptr = t.base + t.lead; d.nbytes = t.nbytes;
+        descs.push_back(d);
+    }
+    ckpt_config cfg{};
+    cfg.out_dir = dir.c_str();
+    cfg.host_ring_bytes = 256 << 10;
+    cfg.dma_chunk_bytes = 64 << 10;
+    cfg.pack_superchunk_bytes = 256 << 10;
+    cfg.n_dma_streams = 2;
+    cfg.n_io_threads = 3;
+    cfg.io_mode = CKPT_IO_PWRITE;
+    cfg.keep_last = keep_last;
+    cfg.prealloc_files = keep_last ? 1 : 0;
+    ckpt_ctx *ctx = nullptr;
+    REQUIRE(ckpt_init(&cfg, &ctx) == CKPT_OK);
+    REQUIRE(ckpt_register_tensors(ctx, descs.data(), descs.size()) == CKPT_OK);
+    ckpt_layout lay;
+    REQUIRE(ckpt_get_layout(ctx, &lay) == CKPT_OK && lay.n_chunks >= 6);
+    hipStream_t compute;
+    hipStreamCreateWithFlags(&compute, hipStreamNonBlocking);
+    auto update = [&](int it) { emu_submit(compute, [&ts, it] { for (auto &t : ts) for (uint64_t i = 0; i < t.nbytes; i++) t.base[t.lead + i] = uint8_t(t.base[t.lead + i] * 31 + it); }); };
+    char name[4096];
+    for (int it = 1; it <= 2; it++) {
+        update(it);
+        REQUIRE(ckpt_snapshot_async(ctx, uint64_t(it), compute) == CKPT_OK);
+        REQUIRE(ckpt_flush(ctx, uint64_t(it)) == CKPT_OK);
+    }
+    // snapshot 3: the write of chunk 1 fails; the write of the last chunk is held back until told to go
+    std::mutex m;
+    std::condition_variable cv;
+    bool failed_seen = false, go = false;
+    const off_t bad_off = off_t(lay.header_bytes + 1 * lay.dma_chunk_bytes), last_off = off_t(lay.header_bytes + (lay.n_chunks - 1) * lay.dma_chunk_bytes);
+    g_pwrite_hook = [&](int, off_t off, size_t) -> int {
+        std::unique_lock<std::mutex> lk(m);
+        if (off == bad_off) { failed_seen = true; cv.notify_all(); return ENOSPC; }
+        if (off == last_off) cv.wait(lk, [&] { return go; });
+        return 0;
+    };
+    update(3);
+    REQUIRE(ckpt_snapshot_async(ctx, 3, compute) == CKPT_OK);
+    { std::unique_lock<std::mutex> lk(m); cv.wait(lk, [&] { return failed_seen; }); }
+    // the caller asks about iteration 2 (committed long ago): it is handed the latched error, which clears the latch
+    int r = ckpt_flush(ctx, 2);
+    for (int spin = 0; r == CKPT_OK && spin < 2000; spin++) { usleep(1000); r = ckpt_flush(ctx, 2); }   // the latch follows the failed write by a moment
+    REQUIRE(r == CKPT_EIO);
+    { std::lock_guard<std::mutex> lk(m); go = true; cv.notify_all(); }
+    REQUIRE(ckpt_flush(ctx, 3) == CKPT_EIO);          // the failed snapshot still says so itself
+    REQUIRE(ckpt_flush(ctx, 3) == CKPT_EIO);          // ... every time it is asked about
+    g_pwrite_hook = nullptr;
+    REQUIRE(ckpt_file_name(ctx, 3, name, sizeof name) == CKPT_OK);
+    REQUIRE(access(name, F_OK) != 0);                  // no file under the final name
+    REQUIRE(access((std::string(name) + ".tmp").c_str(), F_OK) != 0);
+    uint64_t latest = 0;
+    REQUIRE(ckpt_find_latest(dir.c_str(), &latest, nullptr, 0) == CKPT_OK && latest == 2);
+    // the context goes on working, and with retention the spare pool is not poisoned by the torn file
+    for (int it = 4; it <= 6; it++) {
+        update(it);
+        std::vector<uint8_t> img(lay.file_bytes, 0);
+        ckpt_plan *plan = nullptr;
+        REQUIRE(ckpt_plan_create(descs.data(), descs.size(), &cfg, &plan) == CKPT_OK);
+        std::vector<uint64_t> offs(descs.size());
+        REQUIRE(ckpt_plan_offsets(plan, offs.data(), offs.size()) == CKPT_OK);
+        emu_submit(compute, [&, it] {
+            ckpt_plan_header(plan, uint64_t(it), img.data(), lay.header_bytes);
+            for (size_t k = 0; k < ts.size(); k++) memcpy(img.data() + offs[k], ts[k].base + ts[k].lead, ts[k].nbytes);
+        });
+        REQUIRE(ckpt_snapshot_async(ctx, uint64_t(it), compute) == CKPT_OK);
+        REQUIRE(ckpt_flush(ctx, uint64_t(it)) == CKPT_OK);
+        hipStreamSynchronize(compute);
+        REQUIRE(ckpt_file_name(ctx, uint64_t(it), name, sizeof name) == CKPT_OK);
+        REQUIRE(read_file(name) == img);
+        ckpt_plan_destroy(plan);
+    }
+    REQUIRE(ckpt_destroy(ctx) == CKPT_OK);
+    hipStreamDestroy(compute);
+    for (auto &t : ts) free(t.base);
+    printf("ok %s\n", what.c_str());
+    return 0;
+}
+
+// ---- crash consistency: the process ends itself (SIGKILL) at its kill_at-th file write, somewhere in the
+// middle of a flush. Tensor bytes are a closed form of (tensor, byte, iteration), so the parent can tell what
+// every file that carries a final name must hold. variant 0: plain files; 1: retention with recycled files;
+// 2: second tier that takes every snapshot.
+static uint8_t crash_byte(uint64_t k, uint64_t j, uint64_t it) { return uint8_t((j * 2654435761ull + k * 40503ull + it * 97ull) >> 8); }
+
+static int crash_child(const std::string &dir, int variant, long kill_at) {
+    std::string what = "crash child";
+    const int n_tensors = 12, iters = 5;
+    std::vector<Tensor> ts;
+    for (int k = 0; k < n_tensors; k++) {
+        Tensor t;
+        t.lead = 0;
+        t.nbytes = 30000 + 9973 * k;
+        t.base = static_cast<uint8_t *>(aligned_alloc(16, (t.nbytes + 15) / 16 * 16));
+        t.name = "t" + std::to_string(k);
+        t.shape = int64_t(t.nbytes);
+        ts.push_back(t);
+    }
+    std::vector<ckpt_tensor_desc> descs;
+    for (auto &t : ts) {
+        ckpt_tensor_desc d{};
+        d.name = t.name.c_str(); d.dtype = CKPT_U8; d.ndim = 1; d.shape = &t.shape; d.dev_ptr = t.base; d.nbytes = t.nbytes;
+        descs.push_back(d);
+    }
+    const std::string dir2 = dir + "/tier2";
+    ckpt_config cfg{};
+    cfg.out_dir = dir.c_str();
+    cfg.host_ring_bytes = 256 << 10;
+    cfg.dma_chunk_bytes = 64 << 10;
+    cfg.pack_superchunk_bytes = 256 << 10;
+    cfg.n_io_threads = 3;
+    cfg.io_mode = CKPT_IO_PWRITE;
+    cfg.keep_last = variant == 1 ? 1 : 0;
+    cfg.prealloc_files = variant == 1 ? 1 : 0;
+    ckpt_ctx *ctx = nullptr;
+    REQUIRE(ckpt_init(&cfg, &ctx) == CKPT_OK);
+    REQUIRE(ckpt_register_tensors(ctx, descs.data(), descs.size()) == CKPT_OK);
+    if (variant == 2) { mkdir(dir2.c_str(), 0755); REQUIRE(ckpt_enable_second_tier(ctx, dir2.c_str(), 2, 0, 0, CKPT_TIER2_EVERY) == CKPT_OK); }
+    std::atomic<long> writes{0};
+    g_pwrite_hook = [&](int, off_t, size_t) -> int {
+        if (++writes == kill_at) raise(SIGKILL);
+        return 0;
+    };
+    hipStream_t compute;
+    hipStreamCreateWithFlags(&compute, hipStreamNonBlocking);
+    for (int it = 1; it <= iters; it++) {
+        REQUIRE(ckpt_wait_immutable_window_end(ctx, compute, 0) == CKPT_OK);
+        emu_submit(compute, [&ts, it] { for (size_t k = 0; k < ts.size(); k++) for (uint64_t j = 0; j < ts[k].nbytes; j++) ts[k].base[j] = crash_byte(k, j, uint64_t(it)); });
+        REQUIRE(ckpt_snapshot_async(ctx, uint64_t(it), compute) == CKPT_OK);
+    }
+    REQUIRE(ckpt_flush(ctx, CKPT_ITER_ALL) == CKPT_OK);
+    if (variant == 2) REQUIRE(ckpt_wait_second_tier(ctx, CKPT_ITER_ALL) == CKPT_OK);
+    hipStreamSynchronize(compute);
+    REQUIRE(ckpt_destroy(ctx) == CKPT_OK);
+    hipStreamDestroy(compute);
+    printf("survived with %ld writes\n", writes.load());
+    return 0;
+}
+
 int main(int argc, char **argv) {
-    if (argc < 2) { printf("usage: emu_engine <scratch dir> [seed]\n"); return 2; }
+    if (argc < 2) { printf("usage: emu_engine <scratch dir> [seed] | --failed-chunk <dir> | --crash <dir> <variant> <kill at write>\n"); return 2; }
+    if (std::string(argv[1]) == "--failed-chunk" && argc >= 3) {
+        rng_state = 11;
+        const std::string root = argv[2];
+        for (int keep : {0, 1}) {
+            const std::string d = root + "/k" + std::to_string(keep);
+            mkdir(d.c_str(), 0755);
+            if (failed_chunk_scenario(d, keep)) return 1;
+        }
+        return 0;
+    }
+    if (std::string(argv[1]) == "--crash" && argc >= 5) return crash_child(argv[2], atoi(argv[3]), atol(argv[4]));
     rng_state = argc > 2 ? strtoull(argv[2], 0, 10) : 1;
     std::string root = argv[1];
     int n = 0;

@@ -13,6 +13,7 @@
 #include "../../paper_2406_10707_amd/csrc/plan.hpp"
 
 thread_local dim3 threadIdx, blockIdx, blockDim, gridDim;
+ssize_t emu_pwrite(int, const void *, size_t, off_t) { return -1; }   // no file is written here
 
 static uint64_t rng_state;
 static uint64_t rnd() {
@@ -69,6 +70,31 @@ int main(int argc, char **argv) {
     Plan p;
     if (build_plan(descs.data(), descs.size(), rc, &p, &err)) { printf("plan: %s\n", err.c_str()); return 2; }
     const uint64_t SC = rc.pack_superchunk_bytes;
+
+    // the tile table as the device builds it (batches of descriptors in the kernel arguments) must be the planner's
+    {
+        std::vector<ckpt_tile> table(p.tiles.size());
+        TileBatch bt;
+        bt.count = 0;
+        uint64_t off = 0, tile = 0;
+        for (size_t k = 0; k < descs.size(); k++) {
+            const uint32_t j = bt.count++;
+            bt.src[j] = uint64_t(descs[k].dev_ptr); bt.data_off[j] = off; bt.nbytes[j] = descs[k].nbytes; bt.first_tile[j] = uint32_t(tile);
+            tile += tiles_of(off, descs[k].nbytes, kTileBytes);
+            off += (descs[k].nbytes + 4095) / 4096 * 4096;
+            bt.first_tile[j + 1] = uint32_t(tile);
+            if (tile > table.size()) { printf("tiles_of counts %llu tiles, the planner %zu\n", (unsigned long long)tile, table.size()); return 1; }
+            if (bt.count == uint32_t(kTileBatch) || k + 1 == descs.size()) { launch_build_tiles(bt, table.data(), nullptr); bt.count = 0; }
+        }
+        if (tile != p.tiles.size() || off != p.data_bytes) { printf("tile count or data size differs from the planner's\n"); return 1; }
+        for (size_t i = 0; i < table.size(); i++) {
+            const ckpt_tile &a = table[i], &b = p.tiles[i];
+            if (a.src != b.src || a.dst_off != b.dst_off || a.copy_bytes != b.copy_bytes || a.total_bytes != b.total_bytes || a.reserved != 0) {
+                printf("device-built tile %zu differs from the planner's\n", i);
+                return 1;
+            }
+        }
+    }
 
     // expected packed image
     std::vector<uint8_t> want(p.data_bytes, 0);

@@ -18,6 +18,14 @@
 #include <mutex>
 #include <thread>
 
+#include <unistd.h>
+
+// File writes of the engine go through a function the test program owns, so that a test can make one
+// particular write fail, hold it back, or end the process in the middle of a flush. (unistd.h is included
+// above, so its own declaration of pwrite is already past when the name is redirected.)
+ssize_t emu_pwrite(int fd, const void *buf, size_t n, off_t off);
+#define pwrite emu_pwrite
+
 struct dim3 {
     unsigned x, y, z;
     dim3(unsigned x_ = 1, unsigned y_ = 1, unsigned z_ = 1) : x(x_), y(y_), z(z_) {}

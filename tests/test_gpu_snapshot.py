@@ -117,19 +117,26 @@ def test_retention_recycles_files_in_place(io_mode, tmp_path):
     assert not [f for f in os.listdir(tmp_path) if f.startswith(".spare_")]
 
 
+@pytest.mark.parametrize("policy,staging", [(B.CKPT_WINDOW_D2H, 0), (B.CKPT_WINDOW_PACK, 0), (B.CKPT_WINDOW_PACK, 64 << 20)],
+                         ids=["d2h", "pack-2-staging-slots", "pack-full-staging"])
 @pytest.mark.parametrize("config", [1, 5])
-def test_every_iteration_with_mutation(config, tmp_path):
+def test_every_iteration_with_mutation(config, policy, staging, tmp_path):
     """Snapshot every iteration while the update keeps mutating everything, with nothing but stream
     order between the phases (no host synchronisation inside the loop). The oracle's input for
-    iteration i is a device-side clone taken right after update i on the compute stream."""
-    _say(f"every-iteration config {config}")
+    iteration i is a device-side clone taken right after update i on the compute stream. Under the
+    paper's rule the update waits for the last copy; under policy PACK only for the last pack kernel,
+    while the copies drain from staging behind it: with two staging slots (fewer than super-chunks, so
+    packs depend on copies) and with staging that holds the whole data region (consecutive snapshots
+    reuse it while the previous one's copies may still be reading it)."""
+    _say(f"every-iteration config {config} policy {policy} staging {staging}")
     spec = shards.make_shard(config, tiny=True)
     shard = harness.DeviceShard(spec)
     shard.upload_host_values()
     gemm = harness.GemmProxy(1024)
     stream = harness.Stream()
-    ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), **SMALL))
+    ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), window_policy=policy, dev_staging_bytes=staging, **SMALL))
     ck.register_tensors(shard.descs())
+    assert ck.layout()["n_superchunks"] > 2
     clones = {}
     for it in range(1, 7):
         gemm.run(4, stream)                                  # forward/backward stand-in
