@@ -50,6 +50,21 @@ def lib():
         L.oracle_compare_file.argtypes = [P, C.c_size_t, C.c_uint64, C.c_char_p, C.POINTER(C.c_uint64)]
         L.oracle_compare_file_span.restype = C.c_int
         L.oracle_compare_file_span.argtypes = [P, C.c_size_t, C.c_uint64, C.c_size_t, C.c_size_t, C.c_char_p, C.POINTER(C.c_uint64)]
+        U32P = C.POINTER(C.c_uint32)
+        L.oracle_bf16_rne.restype = C.c_uint16
+        L.oracle_bf16_rne.argtypes = [C.c_uint32]
+        L.oracle_pairs_hold.restype = C.c_int
+        L.oracle_pairs_hold.argtypes = [P, C.c_size_t, U32P, U32P, C.c_size_t]
+        L.oracle_v2_sizes.restype = C.c_int
+        L.oracle_v2_sizes.argtypes = [P, C.c_size_t, U32P, U32P, C.c_size_t, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
+        L.oracle_v2_serialize_mem.restype = C.c_int
+        L.oracle_v2_serialize_mem.argtypes = [P, C.c_size_t, U32P, U32P, C.c_size_t, C.c_uint64, C.c_void_p, C.c_uint64,
+                                              C.POINTER(C.c_uint64), U32P]
+        L.oracle_v2_compare_file_span.restype = C.c_int
+        L.oracle_v2_compare_file_span.argtypes = [P, C.c_size_t, U32P, U32P, C.c_size_t, C.c_uint32, C.c_uint64, C.c_size_t, C.c_size_t,
+                                                  C.c_char_p, C.POINTER(C.c_uint64)]
+        L.oracle_v2_restore_file.restype = C.c_int
+        L.oracle_v2_restore_file.argtypes = [C.c_char_p, P, C.c_size_t, U32P, U32P, C.c_size_t, C.POINTER(C.c_uint64), U32P]
         L.oracle_restore_file.restype = C.c_int
         L.oracle_restore_file.argtypes = [C.c_char_p, P, C.c_size_t, C.POINTER(C.c_uint64)]
         _lib = L
@@ -146,18 +161,82 @@ def compare_file(tensors, it, path):
     raise OracleError(rc, "compare_file")
 
 
+def _pairs(pairs):
+    """pairs: list of (derived index, source index) -> two ctypes uint32 arrays and their length."""
+    pairs = list(pairs or [])
+    d = (C.c_uint32 * max(1, len(pairs)))(*[p[0] for p in pairs])
+    s = (C.c_uint32 * max(1, len(pairs)))(*[p[1] for p in pairs])
+    return d, s, len(pairs)
+
+
+def bf16_rne(u):
+    """The format's bf16 rounding of one f32 bit pattern (an int)."""
+    return int(lib().oracle_bf16_rne(int(u) & 0xFFFFFFFF))
+
+
+def pairs_hold(tensors, pairs):
+    """True when every declared derived tensor is, element for element, bf16_rne of its source in the given bytes."""
+    arr, keep = _marshal(tensors)
+    d, s, n = _pairs(pairs)
+    rc = lib().oracle_pairs_hold(arr, len(tensors), d, s, n)
+    if rc < 0:
+        raise OracleError(-rc, "pairs_hold")
+    return bool(rc)
+
+
+def v2_sizes(tensors, pairs):
+    """(header_bytes, data_bytes) of the version-2 file of this tensor list and these pairs."""
+    arr, keep = _marshal(tensors)
+    d, s, n = _pairs(pairs)
+    hb, db = C.c_uint64(0), C.c_uint64(0)
+    rc = lib().oracle_v2_sizes(arr, len(tensors), d, s, n, C.byref(hb), C.byref(db))
+    if rc:
+        raise OracleError(rc, "v2_sizes")
+    return int(hb.value), int(db.value)
+
+
+def serialize_bytes_v2(tensors, it, pairs):
+    """The file for a tensor list with declared (derived, source) pairs: (bytes, version). Version 2 when every
+    pair holds in the given bytes, else the version-1 file."""
+    arr, keep = _marshal(tensors)
+    d, s, n = _pairs(pairs)
+    total = int(lib().oracle_header_bytes(arr, len(tensors))) + int(lib().oracle_data_bytes(arr, len(tensors)))
+    out = np.empty(total + 8 * len(tensors) + 4096, dtype=np.uint8)     # the version-2 header is a little longer, its data shorter
+    written, version = C.c_uint64(0), C.c_uint32(0)
+    rc = lib().oracle_v2_serialize_mem(arr, len(tensors), d, s, n, it, out.ctypes.data, out.nbytes, C.byref(written), C.byref(version))
+    if rc:
+        raise OracleError(rc, "v2_serialize_mem")
+    return out[:written.value].tobytes(), int(version.value)
+
+
+def restore_file_v2(path, tensors, pairs):
+    """Restore with declared pairs; tensors carry writable host arrays. Returns (iter, version of the file)."""
+    arr, keep = _marshal(tensors)
+    d, s, n = _pairs(pairs)
+    it, version = C.c_uint64(0), C.c_uint32(0)
+    rc = lib().oracle_v2_restore_file(os.fsencode(path), arr, len(tensors), d, s, n, C.byref(it), C.byref(version))
+    if rc:
+        raise OracleError(rc, "v2_restore_file")
+    return int(it.value), int(version.value)
+
+
 class SpanComparer:
     """oracle_compare_file_span on a long tensor list, piece by piece: the list is marshalled once
-    (names, dtypes, shapes), and every call supplies the host bytes of one run of tensors only."""
+    (names, dtypes, shapes), and every call supplies the host bytes of one run of tensors only.
+    With pairs (format version 2) a derived tensor's bytes may be given as None when the expected version is 2."""
 
-    def __init__(self, tensors):
+    def __init__(self, tensors, pairs=None):
         self._n = len(tensors)
         self._arr, self._keep = _marshal([(name, dtype, shape, None) for name, dtype, shape, _ in tensors])
+        self._d, self._s, self._np = _pairs(pairs)
 
-    def compare(self, it, first, arrays, path):
+    def compare(self, it, first, arrays, path, version=1):
         """arrays: host bytes of tensors first, first+1, ...; returns None or the first differing file offset."""
         held = []
         for j, data in enumerate(arrays):
+            if data is None:
+                held.append(None)
+                continue
             a = np.ascontiguousarray(data).view(np.uint8).reshape(-1)
             if a.nbytes != self._arr[first + j].nbytes:
                 raise ValueError(f"tensor {first + j}: {a.nbytes} bytes given, {self._arr[first + j].nbytes} expected")
@@ -165,7 +244,8 @@ class SpanComparer:
             self._arr[first + j].host_bytes = a.ctypes.data
         diff = C.c_uint64(0)
         try:
-            rc = lib().oracle_compare_file_span(self._arr, self._n, it, first, len(held), os.fsencode(path), C.byref(diff))
+            rc = lib().oracle_v2_compare_file_span(self._arr, self._n, self._d, self._s, self._np, version, it, first, len(held),
+                                                   os.fsencode(path), C.byref(diff))
         finally:
             for j in range(len(held)):
                 self._arr[first + j].host_bytes = None

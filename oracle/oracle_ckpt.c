@@ -346,3 +346,288 @@ int oracle_restore_file(const char *path, oracle_tensor *ts, size_t n, uint64_t 
     free(hdr); close(fd);
     return rc;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Format version 2 (FORMAT.md, "derived tensors"): the data reduction the paper leaves as future work
+ * (Conclusions), in its first lossless form. A declared pair (derived d, source s) says: tensor d is the
+ * bf16 round-to-nearest-even of f32 tensor s. If every declared pair holds in the captured bytes the file
+ * is version 2 and the derived tensors are described but not stored; otherwise it is version 1, as above.
+ * ------------------------------------------------------------------------------------------------ */
+
+/* bf16 round-to-nearest-even of an f32 bit pattern, on integers (FORMAT.md). */
+uint16_t oracle_bf16_rne(uint32_t u)
+{
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);   /* NaN stays NaN, made quiet */
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+static uint32_t load_u32(const uint8_t *p) { return (uint32_t)p[0] | (uint32_t)p[1] << 8 | (uint32_t)p[2] << 16 | (uint32_t)p[3] << 24; }
+static uint16_t load_u16(const uint8_t *p) { return (uint16_t)(p[0] | p[1] << 8); }
+
+static int same_shape(const oracle_tensor *a, const oracle_tensor *b)
+{
+    if (a->ndim != b->ndim) return 0;
+    for (uint32_t d = 0; d < a->ndim; d++) if (a->shape[d] != b->shape[d]) return 0;
+    return 1;
+}
+
+/* A pair list is well formed when every derived tensor is bf16, its source f32 of the same shape, no tensor
+ * is derived twice and no source is itself derived. */
+static int pairs_ok(const oracle_tensor *ts, size_t n, const uint32_t *derived, const uint32_t *source, size_t n_pairs)
+{
+    for (size_t i = 0; i < n_pairs; i++) {
+        if (derived[i] >= n || source[i] >= n || derived[i] == source[i]) return 0;
+        if (ts[derived[i]].dtype != 1 || ts[source[i]].dtype != 2 || !same_shape(&ts[derived[i]], &ts[source[i]])) return 0;
+        for (size_t j = 0; j < n_pairs; j++) {
+            if (j != i && derived[j] == derived[i]) return 0;
+            if (source[j] == derived[i]) return 0;
+        }
+    }
+    return 1;
+}
+
+/* 1 when every element of every declared derived tensor equals bf16_rne of its source element, 0 when not;
+ * -ORACLE_BAD_ARG for a malformed pair list or missing bytes. Only the tensors named by the pairs need bytes. */
+int oracle_pairs_hold(const oracle_tensor *ts, size_t n, const uint32_t *derived, const uint32_t *source, size_t n_pairs)
+{
+    if (!pairs_ok(ts, n, derived, source, n_pairs)) return -ORACLE_BAD_ARG;
+    for (size_t i = 0; i < n_pairs; i++) {
+        const uint8_t *p = (const uint8_t *)ts[derived[i]].host_bytes, *m = (const uint8_t *)ts[source[i]].host_bytes;
+        if (!p || !m) return -ORACLE_BAD_ARG;
+        uint64_t numel = ts[derived[i]].nbytes / 2;
+        for (uint64_t e = 0; e < numel; e++)
+            if (load_u16(p + 2 * e) != oracle_bf16_rne(load_u32(m + 4 * e))) return 0;
+    }
+    return 1;
+}
+
+/* enc[k] / ref[k] of every tensor for a pair list (caller provides n entries each). */
+static void encodings(size_t n, const uint32_t *derived, const uint32_t *source, size_t n_pairs, uint8_t *enc, uint32_t *ref)
+{
+    for (size_t k = 0; k < n; k++) { enc[k] = 0; ref[k] = 0; }
+    for (size_t i = 0; i < n_pairs; i++) { enc[derived[i]] = 1; ref[derived[i]] = source[i]; }
+}
+
+static uint64_t v2_header_bytes(const oracle_tensor *ts, size_t n)
+{
+    uint64_t used = ORACLE_FIXED;
+    for (size_t k = 0; k < n; k++) used += entry_len(&ts[k]) + 1 + 4;
+    return round_up(used);
+}
+
+static uint64_t v2_data_bytes(const oracle_tensor *ts, size_t n, const uint8_t *enc)
+{
+    uint64_t total = 0;
+    for (size_t k = 0; k < n; k++) if (!enc[k]) total += round_up(ts[k].nbytes);
+    return total;
+}
+
+/* Sizes of the version-2 file of a tensor list with the given pairs (header, data). */
+int oracle_v2_sizes(const oracle_tensor *ts, size_t n, const uint32_t *derived, const uint32_t *source, size_t n_pairs,
+                    uint64_t *header_bytes, uint64_t *data_bytes)
+{
+    if (!pairs_ok(ts, n, derived, source, n_pairs)) return ORACLE_BAD_ARG;
+    uint8_t *enc = (uint8_t *)malloc(n ? n : 1);
+    uint32_t *ref = (uint32_t *)malloc((n ? n : 1) * sizeof *ref);
+    if (!enc || !ref) { free(enc); free(ref); return ORACLE_NOMEM; }
+    encodings(n, derived, source, n_pairs, enc, ref);
+    if (header_bytes) *header_bytes = v2_header_bytes(ts, n);
+    if (data_bytes) *data_bytes = v2_data_bytes(ts, n, enc);
+    free(enc); free(ref);
+    return ORACLE_OK;
+}
+
+static int v2_build_header(const oracle_tensor *ts, size_t n, const uint8_t *enc, const uint32_t *ref, uint64_t iter, uint8_t *out, uint64_t cap)
+{
+    for (size_t k = 0; k < n; k++) if (!tensor_ok(&ts[k])) return ORACLE_BAD_ARG;
+    uint64_t hb = v2_header_bytes(ts, n), db = v2_data_bytes(ts, n, enc);
+    if (cap < hb) return ORACLE_BAD_ARG;
+    memset(out, 0, hb);
+    memcpy(out, MAGIC, 8);
+    put_le(out + 8, 2, 4);
+    put_le(out + 12, ORACLE_ALIGN, 4);
+    put_le(out + 16, iter, 8);
+    put_le(out + 24, n, 8);
+    put_le(out + 32, hb, 8);
+    put_le(out + 40, db, 8);
+    put_le(out + 48, hb + db, 8);
+    uint8_t *p = out + ORACLE_FIXED;
+    uint64_t off = hb;
+    for (size_t k = 0; k < n; k++) {
+        size_t len = strlen(ts[k].name);
+        put_le(p, len, 2); p += 2;
+        memcpy(p, ts[k].name, len); p += len;
+        *p++ = (uint8_t)ts[k].dtype;
+        *p++ = (uint8_t)ts[k].ndim;
+        for (uint32_t d = 0; d < ts[k].ndim; d++) { put_le(p, (uint64_t)ts[k].shape[d], 8); p += 8; }
+        put_le(p, enc[k] ? 0 : off, 8); p += 8;
+        put_le(p, ts[k].nbytes, 8); p += 8;
+        *p++ = enc[k];
+        put_le(p, ref[k], 4); p += 4;
+        if (!enc[k]) off += round_up(ts[k].nbytes);
+    }
+    return ORACLE_OK;
+}
+
+/* The serializer with declared pairs, into memory: version 2 when the pairs hold, else exactly the version-1
+ * file. *version_out says which; *written its size. cap must cover the version-1 size (the larger one). */
+int oracle_v2_serialize_mem(const oracle_tensor *ts, size_t n, const uint32_t *derived, const uint32_t *source, size_t n_pairs,
+                            uint64_t iter, uint8_t *out, uint64_t cap, uint64_t *written, uint32_t *version_out)
+{
+    int hold = oracle_pairs_hold(ts, n, derived, source, n_pairs);
+    if (hold < 0) return -hold;
+    if (!hold || n_pairs == 0) {
+        if (version_out) *version_out = 1;
+        return oracle_serialize_mem(ts, n, iter, out, cap, written);
+    }
+    uint8_t *enc = (uint8_t *)malloc(n);
+    uint32_t *ref = (uint32_t *)malloc(n * sizeof *ref);
+    if (!enc || !ref) { free(enc); free(ref); return ORACLE_NOMEM; }
+    encodings(n, derived, source, n_pairs, enc, ref);
+    uint64_t hb = v2_header_bytes(ts, n), db = v2_data_bytes(ts, n, enc);
+    int rc = cap < hb + db ? ORACLE_BAD_ARG : v2_build_header(ts, n, enc, ref, iter, out, cap);
+    uint8_t *p = out + hb;
+    for (size_t k = 0; k < n && rc == ORACLE_OK; k++) {
+        if (enc[k]) continue;
+        if (!ts[k].host_bytes) { rc = ORACLE_BAD_ARG; break; }
+        uint64_t padded = round_up(ts[k].nbytes);
+        memcpy(p, ts[k].host_bytes, ts[k].nbytes);
+        memset(p + ts[k].nbytes, 0, padded - ts[k].nbytes);
+        p += padded;
+    }
+    if (rc == ORACLE_OK) { if (written) *written = hb + db; if (version_out) *version_out = 2; }
+    free(enc); free(ref);
+    return rc;
+}
+
+/* Piecewise comparison of a file that is expected to be version `version` (1: oracle_compare_file_span on the
+ * same arguments; 2: derived tensors occupy no bytes). Tensors [first, first+count) need bytes unless derived. */
+int oracle_v2_compare_file_span(const oracle_tensor *ts, size_t n, const uint32_t *derived, const uint32_t *source, size_t n_pairs,
+                                uint32_t version, uint64_t iter, size_t first, size_t count, const char *path, uint64_t *first_diff)
+{
+    if (version == 1) return oracle_compare_file_span(ts, n, iter, first, count, path, first_diff);
+    if (first_diff) *first_diff = UINT64_MAX;
+    if (version != 2 || first > n || count > n - first || !pairs_ok(ts, n, derived, source, n_pairs)) return ORACLE_BAD_ARG;
+    uint8_t *enc = (uint8_t *)malloc(n ? n : 1);
+    uint32_t *ref = (uint32_t *)malloc((n ? n : 1) * sizeof *ref);
+    const uint64_t BUF = 8ull << 20;
+    uint8_t *buf = (uint8_t *)malloc(BUF);
+    if (!enc || !ref || !buf) { free(enc); free(ref); free(buf); return ORACLE_NOMEM; }
+    encodings(n, derived, source, n_pairs, enc, ref);
+    uint64_t hb = v2_header_bytes(ts, n), db = v2_data_bytes(ts, n, enc);
+    int rc = ORACLE_OK;
+    int fd = open(path, O_RDONLY);
+    struct stat st;
+    if (fd < 0 || fstat(fd, &st) != 0) rc = ORACLE_IO;
+    else if ((uint64_t)st.st_size != hb + db) {
+        if (first_diff) *first_diff = (uint64_t)st.st_size < hb + db ? (uint64_t)st.st_size : hb + db;
+        rc = ORACLE_MISMATCH;
+    }
+    if (rc == ORACLE_OK && first == 0) {
+        uint8_t *hdr = (uint8_t *)malloc(hb), *got = (uint8_t *)malloc(hb);
+        if (!hdr || !got) rc = ORACLE_NOMEM;
+        if (rc == ORACLE_OK) rc = v2_build_header(ts, n, enc, ref, iter, hdr, hb);
+        if (rc == ORACLE_OK) rc = read_all(fd, got, hb);
+        if (rc == ORACLE_OK && memcmp(got, hdr, hb) != 0) {
+            uint64_t i = 0;
+            while (got[i] == hdr[i]) i++;
+            if (first_diff) *first_diff = i;
+            rc = ORACLE_MISMATCH;
+        }
+        free(hdr); free(got);
+    }
+    uint64_t pos = hb;
+    for (size_t k = 0; k < first; k++) if (!enc[k]) pos += round_up(ts[k].nbytes);
+    if (rc == ORACLE_OK && lseek(fd, (off_t)pos, SEEK_SET) != (off_t)pos) rc = ORACLE_IO;
+    for (size_t k = first; k < first + count && rc == ORACLE_OK; k++) {
+        if (enc[k]) continue;
+        const uint8_t *src = (const uint8_t *)ts[k].host_bytes;
+        if (!src) { rc = ORACLE_BAD_ARG; break; }
+        uint64_t padded = round_up(ts[k].nbytes);
+        for (uint64_t done = 0; done < padded && rc == ORACLE_OK; ) {
+            uint64_t m = padded - done < BUF ? padded - done : BUF;
+            rc = read_all(fd, buf, m);
+            uint64_t live = done >= ts[k].nbytes ? 0 : (ts[k].nbytes - done < m ? ts[k].nbytes - done : m);
+            if (rc == ORACLE_OK) {
+                uint64_t i = 0;
+                if (memcmp(buf, src + done, live) != 0) { while (buf[i] == src[done + i]) i++; rc = ORACLE_MISMATCH; }
+                else for (i = live; i < m; i++) if (buf[i] != 0) { rc = ORACLE_MISMATCH; break; }
+                if (rc == ORACLE_MISMATCH && first_diff) *first_diff = pos + i;
+            }
+            done += m; pos += m;
+        }
+    }
+    if (fd >= 0) close(fd);
+    free(enc); free(ref); free(buf);
+    return rc;
+}
+
+/* Restore with declared pairs: a version-1 file goes through oracle_restore_file; a version-2 file must carry
+ * exactly the declared pairs as derived entries, its stored tensors are read in order and every derived tensor
+ * is recomputed from its restored source. All n tensors need writable host_bytes. */
+int oracle_v2_restore_file(const char *path, oracle_tensor *ts, size_t n, const uint32_t *derived, const uint32_t *source, size_t n_pairs,
+                           uint64_t *iter_out, uint32_t *version_out)
+{
+    if (!pairs_ok(ts, n, derived, source, n_pairs)) return ORACLE_BAD_ARG;
+    int fd = open(path, O_RDONLY);
+    if (fd < 0) return ORACLE_IO;
+    struct stat st;
+    uint8_t fixed[ORACLE_FIXED];
+    if (fstat(fd, &st) != 0 || (uint64_t)st.st_size < ORACLE_FIXED || read_all(fd, fixed, ORACLE_FIXED) != ORACLE_OK) { close(fd); return ORACLE_BAD_FILE; }
+    if (memcmp(fixed, MAGIC, 8) == 0 && get_le(fixed + 8, 4) == 1) {
+        close(fd);
+        if (version_out) *version_out = 1;
+        return oracle_restore_file(path, ts, n, iter_out);
+    }
+    uint64_t hb = get_le(fixed + 32, 8), db = get_le(fixed + 40, 8), fb = get_le(fixed + 48, 8);
+    if (memcmp(fixed, MAGIC, 8) != 0 || get_le(fixed + 8, 4) != 2 || get_le(fixed + 12, 4) != ORACLE_ALIGN || hb % ORACLE_ALIGN != 0 ||
+        hb < ORACLE_FIXED || fb != hb + db || fb != (uint64_t)st.st_size || get_le(fixed + 56, 8) != 0) { close(fd); return ORACLE_BAD_FILE; }
+    if (get_le(fixed + 24, 8) != n) { close(fd); return ORACLE_MISMATCH; }
+    uint8_t *hdr = (uint8_t *)malloc(hb), *enc = (uint8_t *)malloc(n ? n : 1);
+    uint32_t *ref = (uint32_t *)malloc((n ? n : 1) * sizeof *ref);
+    if (!hdr || !enc || !ref) { free(hdr); free(enc); free(ref); close(fd); return ORACLE_NOMEM; }
+    encodings(n, derived, source, n_pairs, enc, ref);
+    int rc = read_all(fd, hdr + ORACLE_FIXED, hb - ORACLE_FIXED);
+    const uint8_t *p = hdr + ORACLE_FIXED, *end = hdr + hb;
+    uint64_t expect_off = hb;
+    for (size_t k = 0; k < n && rc == ORACLE_OK; k++) {
+        if (end - p < 2) { rc = ORACLE_BAD_FILE; break; }
+        uint64_t len = get_le(p, 2); p += 2;
+        if ((uint64_t)(end - p) < len + 2) { rc = ORACLE_BAD_FILE; break; }
+        const uint8_t *name = p; p += len;
+        int32_t dtype = *p++; uint32_t ndim = *p++;
+        if (ndim > 8 || (uint64_t)(end - p) < 8ull * ndim + 16 + 5) { rc = ORACLE_BAD_FILE; break; }
+        uint64_t numel = 1; int64_t shape[8];
+        for (uint32_t d = 0; d < ndim; d++) { shape[d] = (int64_t)get_le(p, 8); p += 8; if (shape[d] < 0) rc = ORACLE_BAD_FILE; else numel *= (uint64_t)shape[d]; }
+        uint64_t off = get_le(p, 8); p += 8;
+        uint64_t nb = get_le(p, 8); p += 8;
+        uint32_t e = *p++;
+        uint32_t r = (uint32_t)get_le(p, 4); p += 4;
+        if (rc != ORACLE_OK) break;
+        if (e > 1 || nb == 0 || nb != elsize(dtype) * numel) { rc = ORACLE_BAD_FILE; break; }
+        if (e == 0 && (off != expect_off || off + nb > fb || r != 0)) { rc = ORACLE_BAD_FILE; break; }
+        if (e == 1 && (off != 0 || dtype != 1 || r >= n)) { rc = ORACLE_BAD_FILE; break; }
+        if (len != strlen(ts[k].name) || memcmp(name, ts[k].name, len) != 0 || dtype != ts[k].dtype || ndim != ts[k].ndim || nb != ts[k].nbytes ||
+            e != enc[k] || r != ref[k]) { rc = ORACLE_MISMATCH; break; }
+        for (uint32_t d = 0; d < ndim; d++) if (shape[d] != ts[k].shape[d]) rc = ORACLE_MISMATCH;
+        if (e == 0) expect_off += round_up(nb);
+    }
+    if (rc == ORACLE_OK && expect_off != fb) rc = ORACLE_BAD_FILE;
+    for (size_t k = 0; k < n && rc == ORACLE_OK; k++) {
+        if (!ts[k].host_bytes) { rc = ORACLE_BAD_ARG; break; }
+        if (enc[k]) continue;
+        rc = read_all(fd, ts[k].host_bytes, ts[k].nbytes);
+        uint64_t pad = round_up(ts[k].nbytes) - ts[k].nbytes;
+        if (rc == ORACLE_OK && pad) { uint8_t skip[ORACLE_ALIGN]; rc = read_all(fd, skip, pad); }
+    }
+    for (size_t i = 0; i < n_pairs && rc == ORACLE_OK; i++) {
+        uint8_t *d = (uint8_t *)ts[derived[i]].host_bytes;
+        const uint8_t *m = (const uint8_t *)ts[source[i]].host_bytes;
+        uint64_t numel = ts[derived[i]].nbytes / 2;
+        for (uint64_t e = 0; e < numel; e++) put_le(d + 2 * e, oracle_bf16_rne(load_u32(m + 4 * e)), 2);
+    }
+    if (rc == ORACLE_OK && iter_out) *iter_out = get_le(fixed + 16, 8);
+    if (rc == ORACLE_OK && version_out) *version_out = 2;
+    free(hdr); free(enc); free(ref); close(fd);
+    return rc;
+}

@@ -19,33 +19,31 @@ int check_pack_arguments(const ckpt_tensor_desc *tensors, size_t n, const void *
     if (!tensors || n == 0 || !dev_dst) return fail(CKPT_EINVAL, "null argument or empty tensor list");
     int dev = 0;
     HIP_TRY(nullptr, hipGetDevice(&dev));
-    auto on_this_gpu = [&](const void *p, uint64_t nbytes, const std::string &what) -> int {
+    // 0: fine; 1: not device memory of this GPU; 2: runs past its allocation (queries only, nothing is allocated;
+    // texts are put together on the failing path alone)
+    auto on_this_gpu = [&](const void *p, uint64_t nbytes) -> int {
         hipPointerAttribute_t attr;
         hipError_t e = hipPointerGetAttributes(&attr, p);
-        if (e != hipSuccess || attr.type != hipMemoryTypeDevice || attr.device != dev) {
-            (void)hipGetLastError();
-            return fail(CKPT_EINVAL, what + ": not device memory of the current GPU");
-        }
+        if (e != hipSuccess || attr.type != hipMemoryTypeDevice || attr.device != dev) { (void)hipGetLastError(); return 1; }
         void *base = nullptr; size_t span = 0;
         e = hipMemGetAddressRange(reinterpret_cast<hipDeviceptr_t *>(&base), &span, reinterpret_cast<hipDeviceptr_t>(const_cast<void *>(p)));
-        if (e == hipSuccess && uint64_t(p) + nbytes > uint64_t(base) + span) return fail(CKPT_EINVAL, what + ": range runs past its allocation");
+        if (e == hipSuccess && uint64_t(p) + nbytes > uint64_t(base) + span) return 2;
         if (e != hipSuccess) (void)hipGetLastError();
-        return CKPT_OK;
+        return 0;
     };
+    static const char *const why[] = {"", ": not device memory of the current GPU", ": range runs past its allocation"};
     uint64_t off = 0, tiles = 0;
     for (size_t k = 0; k < n; k++) {
         const ckpt_tensor_desc &d = tensors[k];
         if (d.dtype & CKPT_PLACE_HOST) return fail(CKPT_EINVAL, "tensor " + std::to_string(k) + ": host-resident objects cannot be packed on the device");
         if (!d.dev_ptr || d.nbytes == 0) return fail(CKPT_EINVAL, "tensor " + std::to_string(k) + ": null pointer or zero bytes");
-        int r = on_this_gpu(d.dev_ptr, d.nbytes, "tensor " + std::to_string(k));
-        if (r) return r;
+        if (int bad = on_this_gpu(d.dev_ptr, d.nbytes)) return fail(CKPT_EINVAL, "tensor " + std::to_string(k) + why[bad]);
         tiles += tiles_of(off, d.nbytes, kTileBytes);
         off += (d.nbytes + kAlign - 1) / kAlign * kAlign;
     }
     if (uint64_t(dev_dst) % 16 != 0) return fail(CKPT_EINVAL, "destination must be 16-byte aligned");
     if (dst_bytes < off) return fail(CKPT_EINVAL, "destination smaller than the data region (" + std::to_string(off) + " bytes)");
-    int r = on_this_gpu(dev_dst, off, "destination");
-    if (r) return r;
+    if (int bad = on_this_gpu(dev_dst, off)) return fail(CKPT_EINVAL, std::string("destination") + why[bad]);
     if (tiles > 0xFFFFFFFFull) return fail(CKPT_EINVAL, "more than 2^32 tiles");
     *data_bytes_out = off;
     *n_tiles_out = tiles;

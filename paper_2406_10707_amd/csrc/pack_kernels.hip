@@ -37,6 +37,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #ifndef DSLLM_PACK_UNROLL_SHIFT
 #define DSLLM_PACK_UNROLL_SHIFT 4
 #endif
+// How the pack kernel reads a source that is not 16-byte aligned. 0: aligned 16-byte loads, the neighbour
+// lane's word by register exchange, byte funnel. 1: one 16-byte load per lane at the tensor's own (unaligned)
+// address; the memory pipeline splits what straddles a line. The target allows unaligned vector loads (the
+// compiler itself emits a single global_load_dwordx4 for an under-aligned 16-byte access).
+#ifndef DSLLM_PACK_MISALIGNED
+#define DSLLM_PACK_MISALIGNED 0
+#endif
 constexpr uint64_t kPackTileBytes = 32 * 1024;   // the planner's tile size (plan.hpp: kTileBytes)
 constexpr int kWavesPerBlock = DSLLM_PACK_WAVES_PER_BLOCK;
 constexpr int kBlock = 64 * kWavesPerBlock;
@@ -57,6 +64,9 @@ constexpr int kUnrollShift = DSLLM_PACK_UNROLL_SHIFT;  // misaligned path: pairs
 #define DSLLM_KEEP_WHOLE(v) (void)0
 #endif
 __device__ __forceinline__ u32x4 ld16(const u32x4 *p) { return __builtin_nontemporal_load((const u32x4 DSLLM_GLOBAL *)p); }
+typedef u32x4 u32x4_bytealigned __attribute__((aligned(1)));
+// 16 bytes from any byte address; all 16 must lie inside the tensor
+__device__ __forceinline__ u32x4 ld16_unaligned(const uint8_t *p) { return __builtin_nontemporal_load((const u32x4_bytealigned DSLLM_GLOBAL *)p); }
 __device__ __forceinline__ void st16(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, (u32x4 DSLLM_GLOBAL *)p); }
 
 // A value that is the same in every lane of the wavefront, moved to scalar registers. The builtin
@@ -187,12 +197,27 @@ __global__ __launch_bounds__(kBlock) void pack_kernel(const ckpt_tile *__restric
     } else {
         const u32x4 *s = reinterpret_cast<const u32x4 *>(src - sh);
         const uint32_t b = sh & 3;
+#if DSLLM_PACK_MISALIGNED == 1
+        {   // output word j = source bytes [16 j, 16 j + 16): inside the tensor for every j < n_full
+            const uint8_t *su = reinterpret_cast<const uint8_t *>(src);
+            uint32_t i = lane;
+            for (; i + 64 * (kUnroll - 1) < n_full; i += 64 * kUnroll) {
+                u32x4 v[kUnroll];
+#pragma unroll
+                for (int u = 0; u < kUnroll; u++) v[u] = ld16_unaligned(su + 16ull * (i + 64 * u));
+#pragma unroll
+                for (int u = 0; u < kUnroll; u++) st16(dst + i + 64 * u, v[u]);
+            }
+            for (; i < n_full; i += 64) st16(dst + i, ld16_unaligned(su + 16ull * i));
+        }
+#else
         switch (sh >> 2) {
             case 0: pack_shifted<0>(s, dst, n_full, b, lane); break;
             case 1: pack_shifted<1>(s, dst, n_full, b, lane); break;
             case 2: pack_shifted<2>(s, dst, n_full, b, lane); break;
             default: pack_shifted<3>(s, dst, n_full, b, lane); break;
         }
+#endif
         if (tail && lane == 0) {
             // word n_full of the aligned source holds source bytes; word n_full+1 only if sh + tail > 16
             u32x4 lo = ld16(s + n_full);

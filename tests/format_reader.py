@@ -39,6 +39,41 @@ def expected_file(tensors, it):
     return bytes(out)
 
 
+def bf16_rne(u):
+    """FORMAT.md, version 2: bf16 rounding of an f32 bit pattern, on Python integers."""
+    if (u & 0x7FFFFFFF) > 0x7F800000:
+        return ((u >> 16) | 0x0040) & 0xFFFF
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) & 0xFFFF
+
+
+def expected_file_v2(tensors, it, pairs):
+    """Version 2: tensors as above, pairs = list of (derived index, source index); derived tensors are described, not stored."""
+    ref = {d: s for d, s in pairs}
+    entries = [2 + len(name.encode("utf-8")) + 1 + 1 + 8 * len(shape) + 8 + 8 + 1 + 4 for name, dtype, shape, data in tensors]
+    header_bytes = up(64 + sum(entries))
+    data_bytes = sum(up(len(d)) for k, (_, _, _, d) in enumerate(tensors) if k not in ref)
+    out = bytearray()
+    out += MAGIC
+    out += struct.pack("<IIQQQQQQ", 2, A, it, len(tensors), header_bytes, data_bytes, header_bytes + data_bytes, 0)
+    off = header_bytes
+    for k, (name, dtype, shape, data) in enumerate(tensors):
+        nm = name.encode("utf-8")
+        out += struct.pack("<H", len(nm)) + nm + struct.pack("<BB", dtype, len(shape))
+        for s in shape:
+            out += struct.pack("<q", s)
+        if k in ref:
+            out += struct.pack("<QQBI", 0, len(data), 1, ref[k])
+        else:
+            out += struct.pack("<QQBI", off, len(data), 0, 0)
+            off += up(len(data))
+    out += b"\x00" * (header_bytes - len(out))
+    for k, (name, dtype, shape, data) in enumerate(tensors):
+        if k not in ref:
+            out += bytes(data) + b"\x00" * (up(len(data)) - len(data))
+    assert len(out) == header_bytes + data_bytes
+    return bytes(out)
+
+
 class FormatError(Exception):
     pass
 
