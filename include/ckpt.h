@@ -329,6 +329,19 @@ int ckpt_describe_file(const char *path, char *buf, size_t cap, size_t *needed_o
  * CKPT_ENOMEM, CKPT_EHIP. */
 int ckpt_pack_image(const ckpt_tensor_desc *tensors, size_t n, void *dev_dst, uint64_t dst_bytes, void *hip_stream);
 
+/* ckpt_pack_image for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation. Same arguments, same image, same checks, but the tile table lives in a
+ * static device array of the library (4 MiB per GPU, held until the process ends) instead of a temporary
+ * allocation: the call makes no hipMalloc, hipFree or other allocating call, enqueues its kernels on
+ * hip_stream and returns WITHOUT waiting for them (the image is complete when the stream gets there).
+ * Limit: 131,072 tiles, i.e. about 4 GiB of data region (a tensor takes one tile per 32 KiB boundary it
+ * touches, at least one); beyond it CKPT_EINVAL, nothing launched. Every call on a GPU shares that GPU's
+ * table: calls on one stream are ordered and safe, calls that overlap on one GPU (different streams, or
+ * threads) race and must be serialized by the caller. The table's address on a device is looked up on the
+ * first call there, or by ckpt_init for its device: make that first call (or ckpt_init) outside any region
+ * in which the runtime must not load code. */
+int ckpt_pack_image_noalloc(const ckpt_tensor_desc *tensors, size_t n, void *dev_dst, uint64_t dst_bytes, void *hip_stream);
+
 int ckpt_get_layout(ckpt_ctx *ctx, ckpt_layout *out);
 /* Measurements of one requested snapshot; CKPT_EINVAL if unknown (records of the 1024 most recent
  * requests are kept). Device-timeline fields are filled

@@ -105,6 +105,7 @@ _SIGS = {
     "ckpt_describe_file": (C.c_int, [C.c_char_p, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)]),
     "ckpt_find_latest": (C.c_int, [C.c_char_p, C.POINTER(_u64), C.c_char_p, C.c_size_t]),
     "ckpt_pack_image": (C.c_int, [C.POINTER(ckpt_tensor_desc), C.c_size_t, _vp, _u64, _vp]),
+    "ckpt_pack_image_noalloc": (C.c_int, [C.POINTER(ckpt_tensor_desc), C.c_size_t, _vp, _u64, _vp]),
     "ckpt_get_layout": (C.c_int, [_vp, C.POINTER(ckpt_layout)]),
     "ckpt_get_stats": (C.c_int, [_vp, _u64, C.POINTER(ckpt_stats)]),
     "ckpt_file_name": (C.c_int, [_vp, _u64, C.c_char_p, C.c_size_t]),
@@ -212,6 +213,13 @@ def pack_image(tensors, dev_dst, dst_bytes, stream):
     tensors = list(tensors)
     arr, keep = make_descs(tensors)
     _check(lib.ckpt_pack_image(arr, len(tensors), dev_dst, dst_bytes, stream))
+
+
+def pack_image_noalloc(tensors, dev_dst, dst_bytes, stream):
+    """ckpt_pack_image_noalloc: as pack_image, no allocation, returns without waiting for the stream."""
+    tensors = list(tensors)
+    arr, keep = make_descs(tensors)
+    _check(lib.ckpt_pack_image_noalloc(arr, len(tensors), dev_dst, dst_bytes, stream))
 
 
 class Plan:

@@ -183,6 +183,7 @@ int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out) {
     HIP_TRY(nullptr, hipGetDeviceCount(&ndev));
     if (cfg->device < 0 || cfg->device >= ndev) return fail(CKPT_EINVAL, "config: no such device");
     HIP_TRY(nullptr, hipSetDevice(cfg->device));
+    if ((r = pack_scratch_setup()) != CKPT_OK) return r;   // the static table of ckpt_pack_image_noalloc on this device
 
     std::unique_ptr<ckpt_ctx> c(new ckpt_ctx);
     c->cfg = rc;

@@ -235,6 +235,8 @@ void tier2_offer_locked(ckpt_ctx *c, const std::shared_ptr<Snap> &sp);
 void tier2_thread_main(ckpt_ctx *c);
 // submit.cpp
 void submit_thread_main(ckpt_ctx *c);
+// pack_image.hip
+int pack_scratch_setup();
 // engine.cpp
 int take_async_error(ckpt_ctx *c);
 bool preallocate_file(const std::string &path, uint64_t bytes, int n_threads, bool map_it, bool o_direct, FileSlot *out, std::string *err);

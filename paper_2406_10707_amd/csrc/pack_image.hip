@@ -1,7 +1,16 @@
 // ckpt_pack_image: the pack step on its own. A list of tensors is gathered into the image of its
 // checkpoint data region in device memory, without a context: no ring, no threads, no file.
+// ckpt_pack_image_noalloc: the same for callers that cannot allocate; its tile table lives in a static
+// device array of this file.
 #include "engine_internal.hpp"
 #include "tile_batch.hpp"
+
+// The tile table of ckpt_pack_image_noalloc: room for kScratchTiles tiles (4 MiB), held by every GPU the
+// library runs on until the process ends. In host code this name is only a stand-in for the symbol: the
+// array's address on a device comes from hipGetSymbolAddress (scratch_on_current_device below) and only
+// that address is ever handed to a kernel.
+constexpr uint64_t kScratchTiles = 131072;
+static __device__ __align__(256) unsigned char scratch[kScratchTiles * sizeof(ckpt_tile)];
 
 namespace dsllm {
 hipError_t launch_build_tiles(const TileBatch &bt, ckpt_tile *dev_table, hipStream_t stream);
@@ -75,9 +84,52 @@ int enqueue_pack_image(const ckpt_tensor_desc *tensors, size_t n, void *dev_dst,
     return CKPT_OK;
 }
 
+// Where each device keeps its copy of `scratch` (every GPU has its own, at its own address): looked up once
+// per device, with that device current, and kept.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices];
+
+int scratch_on_current_device(void **out) {
+    int dev = 0;
+    HIP_TRY(nullptr, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(CKPT_EINVAL, "device ordinal beyond what the scratch table foresees");
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(CKPT_EHIP, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return CKPT_OK;
+}
+
 }  // namespace
 
+// Called by ckpt_init for its device, so that a caller who has a context never meets the first-use lookup
+// (which may load the code object) inside a region where nothing may be allocated.
+int dsllm::pack_scratch_setup() {
+    void *p = nullptr;
+    return scratch_on_current_device(&p);
+}
+
 extern "C" {
+
+int ckpt_pack_image_noalloc(const ckpt_tensor_desc *tensors, size_t n, void *dev_dst, uint64_t dst_bytes, void *hip_stream) {
+    uint64_t data_bytes = 0, n_tiles = 0;
+    int r = check_pack_arguments(tensors, n, dev_dst, dst_bytes, &data_bytes, &n_tiles);
+    if (r) return r;
+    if (n_tiles > kScratchTiles)
+        return fail(CKPT_EINVAL, "tensor list needs " + std::to_string(n_tiles) + " tiles, the static table holds " + std::to_string(kScratchTiles) +
+                                     " (about 4 GiB of data region): use ckpt_pack_image");
+    void *table = nullptr;
+    r = scratch_on_current_device(&table);
+    if (r) return r;
+    // every entry the pack kernel reads is written by the table kernels just before it, on the same stream:
+    // nothing of the previous call's table has to be cleared
+    return enqueue_pack_image(tensors, n, dev_dst, static_cast<ckpt_tile *>(table), n_tiles, static_cast<hipStream_t>(hip_stream));
+}
 
 int ckpt_pack_image(const ckpt_tensor_desc *tensors, size_t n, void *dev_dst, uint64_t dst_bytes, void *hip_stream) {
     uint64_t data_bytes = 0, n_tiles = 0;

@@ -37,6 +37,8 @@ extern thread_local dim3 threadIdx, blockIdx, blockDim, gridDim;
 #define __host__
 #define __forceinline__ inline __attribute__((always_inline))
 #define __launch_bounds__(...)
+#define __align__(n) __attribute__((aligned(n)))
+#define HIP_SYMBOL(x) x
 
 typedef int hipError_t;
 static const hipError_t hipSuccess = 0, hipErrorInvalidValue = 1, hipErrorOutOfMemory = 2, hipErrorNotSupported = 801;
@@ -124,6 +126,8 @@ typedef void *hipDeviceptr_t;
 inline void emu_submit(hipStream_t s, std::function<void()> f) { if (s) s->push(std::move(f)); else f(); }
 
 inline hipError_t hipSetDevice(int) { return hipSuccess; }
+inline hipError_t hipGetDevice(int *d) { *d = 0; return hipSuccess; }
+template <class T> inline hipError_t hipGetSymbolAddress(void **p, T &symbol) { *p = &symbol; return hipSuccess; }   // the model has one "device"
 inline hipError_t hipGetDeviceCount(int *n) { *n = 1; return hipSuccess; }
 inline hipError_t hipMalloc(void **p, size_t n) { *p = aligned_alloc(256, (n + 255) / 256 * 256); return *p ? hipSuccess : hipErrorOutOfMemory; }
 inline hipError_t hipFree(void *p) { free(p); return hipSuccess; }

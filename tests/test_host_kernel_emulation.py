@@ -40,7 +40,7 @@ def _build_emu_engine(tmp_path_factory, sanitizer):
     cmd = [CLANG, "-x", "c++", "-std=c++17", "-O1", "-g", "-fsanitize=" + sanitizer, "-fno-omit-frame-pointer", "-pthread",
            "-I", os.path.join(ROOT, "tests", "emu"), "-o", exe, os.path.join(ROOT, "tests", "emu", "emu_engine.cpp"),
            *[os.path.join(csrc, f) for f in ("engine.cpp", "submit.cpp", "io_threads.cpp", "restore.cpp", "second_tier.cpp", "plan.cpp",
-                                             "pack_kernels.hip")]]
+                                             "pack_kernels.hip", "pack_image.hip")]]
     subprocess.run(cmd, check=True, cwd=os.path.join(ROOT, "tests", "emu"))
     return exe
 
