@@ -73,6 +73,16 @@ def parse_args():
     ap.add_argument("--paired-blocks", type=int, default=3,
                     help="workloads that checkpoint every step: alternate this many blocks of checkpointed and quiet steps "
                          "after the timed region for a stall figure free of thermal drift (0: off)")
+    ap.add_argument("--reduce", type=int, default=0,
+                    help="1: data reduction (format version 2): every p_bf16 tensor is declared derived from its master weights; "
+                         "a snapshot whose pairs hold leaves them out (12 instead of 14 bytes per parameter cross the link)")
+    ap.add_argument("--idle-library-steps", type=int, default=6,
+                    help="steps run with the library's calls in the loop but no snapshot pending or requested, long after the last "
+                         "copy (a third reference for the stall: what the calls themselves cost; 0: off)")
+    ap.add_argument("--pack-only", type=int, default=0,
+                    help="N > 0: no snapshot engine, no proxy; N calls of ckpt_pack_image over the whole workload (one launch of the pack "
+                         "kernel each) after one 4 GiB launch of the plain copy kernel. For rocprofv3 runs of the pack kernel alone: "
+                         "kernel durations and, with --pmc, HBM traffic, the copy kernel being the counters' calibration")
     ap.add_argument("--dump", default="", help="write per-step timings and per-snapshot measurements to this JSON file")
     return ap.parse_args()
 
@@ -176,7 +186,34 @@ def say(msg):
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
+def pack_only(args, B, harness, spec):
+    """The pack kernel alone on the workload's real tensor list (ckpt_pack_image), for profiler runs."""
+    stream = harness.make_compute_stream()
+    shard = harness.DeviceShard(spec)
+    shard.fill_device(stream)
+    a, b = harness.DevBuf(4 << 30), harness.DevBuf(4 << 30)
+    B.proxy_device_fill_async(a.ptr, 1, a.nbytes, stream.handle)
+    B.proxy_devcopy(b.ptr, a.ptr, a.nbytes, stream.handle)        # calibration launch: reads 4 GiB, writes 4 GiB
+    stream.synchronize()
+    a.free()
+    b.free()
+    descs = shard.descs()
+    data = sum(-(-d[4] // 4096) * 4096 for d in descs)
+    payload = sum(d[4] for d in descs)
+    dst = harness.DevBuf(data)
+    wall = []
+    for _ in range(args.pack_only):
+        t0 = time.perf_counter()
+        B.pack_image(descs, dst.ptr, data, stream.cuda_stream)
+        wall.append(round((time.perf_counter() - t0) * 1e3, 3))
+    print(json.dumps({"mode": "pack_only", "workload": spec.name, "n_tensors": len(descs), "payload_bytes": payload, "data_bytes": data,
+                      "algorithmic_bytes_per_launch": payload + data, "calibration_copy_bytes": 4 << 30,
+                      "call_wall_ms_including_table_build_alloc_and_sync": wall}), flush=True)
+
+
 def run(args, B, harness, spec, every, compute_ms, out_dir):
+    if args.pack_only > 0:
+        return pack_only(args, B, harness, spec)
     info = B.proxy_device_info()
     stream = harness.make_compute_stream()
     say("link peak and copy-kernel ceiling")
@@ -217,6 +254,9 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     say("ckpt_init + ckpt_register_tensors (ring pinned and touched, spare files pre-allocated)")
     t0 = time.perf_counter()
     ck = B.Checkpointer(cfg)
+    pairs = [(k, k + 1) for k, t in enumerate(spec.tensors) if t.role == "p_bf16"] if args.reduce else []
+    if pairs:
+        ck.declare_derived(pairs)
     ck.register_tensors(shard.descs())
     tier2_dir = ""
     if args.tier2_dir:
@@ -225,7 +265,9 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                               mode=B.CKPT_TIER2_EVERY if args.tier2_mode == "every" else B.CKPT_TIER2_NEWEST)
     init_s = time.perf_counter() - t0
     lay = ck.layout()
-    S = lay["data_bytes"]
+    # bytes one snapshot moves over the link and into its file: the version-2 data region when derived tensors are declared
+    # (and their pairs hold, which the update kernel of the proxy guarantees; every snapshot's own figure is in its stats)
+    S = lay["reduced_data_bytes"] if pairs else lay["data_bytes"]
     requested, live_files = [], []
     # the step counter starts so that the last warm-up step requests a snapshot: its copies then run in the
     # first timed steps whatever K and W are (with the defaults, W = 10 and a checkpoint every 10 steps, it starts at 0);
@@ -260,13 +302,14 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                 os.unlink(ck.file_name(it))
                 live_files.remove(it)
 
-    def baseline_phase(n):
+    def baseline_phase(n, library_calls=False):
         """Same steps with checkpointing off: (median step ms, median GEMM-phase ms). After an idle period
-        the card runs a few per cent faster for some seconds, so the first ~4 s of steps are discarded."""
+        the card runs a few per cent faster for some seconds, so the first ~4 s of steps are discarded.
+        library_calls: the loop makes the library's calls (window wait) but requests no snapshot."""
         marks = []
         skip = min(max(2, int(args.baseline_discard_s * 1000.0 / max(compute_ms, 1.0)) + 1), 40) if args.baseline_discard_s > 0 else 0
         for i in range(skip + n):
-            iteration(1000000 + i, False, marks)
+            iteration(1000000 + i, library_calls, marks, snap=False)
         stream.synchronize()
         return (statistics.median(m[0].elapsed_time(m[2]) for m in marks[skip:]),
                 statistics.median(m[0].elapsed_time(m[1]) for m in marks[skip:]))
@@ -311,9 +354,10 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         return nbytes / (ms * 1e-3) / 1e9 if ms and ms > 0 else None
 
     def stall_report(reg, base_iter_ms, base_gemm_ms, drained_before=False):
-        """Stall of a region. Reference step time: the quiet steps of the same region (4 or more steps after
-        the latest snapshot request) when there are at least three, measured under identical conditions;
-        otherwise the no-checkpoint baseline phases. GEMM slowdown: steps overlapping copies vs the same reference."""
+        """Stall of a region against BOTH references. The headline figures (stall_ms_per_step, stall_pct,
+        stall_ms_per_snapshot) are against the no-checkpoint baseline phases, which is the metric's definition
+        (training stall versus no checkpointing). The second reference, the quiet steps of the same region (4 or
+        more steps after the latest snapshot request, at least three of them), is given beside it."""
         # snapshots whose copies run inside the region: requested by the step before it (unless everything was
         # drained before the region began) up to the step before its last
         lo = reg["first"] if drained_before else reg["first"] - 1
@@ -326,20 +370,27 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
             elif since >= 4:
                 quiet.append(g)
                 quiet_iter.append(reg["iter_ms"][i])
-        use_quiet = len(quiet) >= 3
-        ref_iter = statistics.median(quiet_iter) if use_quiet else base_iter_ms
-        ref_gemm = statistics.median(quiet) if use_quiet else base_gemm_ms
-        total = sum(reg["iter_ms"]) - ref_iter * len(reg["iter_ms"])
-        return in_reg, {
-            "reference": "quiet steps of the same region" if use_quiet else "no-checkpoint baseline phases (before and after, averaged)",
-            "reference_ms_per_step": round(ref_iter, 3), "ms_per_step": round(statistics.mean(reg["iter_ms"]), 3),
-            "stall_ms_per_step": round(total / len(reg["iter_ms"]), 3),
-            "stall_pct": round(100.0 * total / (ref_iter * len(reg["iter_ms"])), 3),
+        n = len(reg["iter_ms"])
+        total = sum(reg["iter_ms"]) - base_iter_ms * n
+        out = {
+            "reference": "no-checkpoint baseline phases (before and after, averaged)",
+            "reference_ms_per_step": round(base_iter_ms, 3), "ms_per_step": round(statistics.mean(reg["iter_ms"]), 3),
+            "stall_ms_per_step": round(total / n, 3),
+            "stall_pct": round(100.0 * total / (base_iter_ms * n), 3),
             "stall_ms_per_snapshot": round(total / max(1, len(in_reg)), 2),
-            "baseline_phase_ms_per_step": round(base_iter_ms, 3),
-            "gemm_ms_reference": round(ref_gemm, 3),
+            "gemm_ms_reference": round(base_gemm_ms, 3),
             "gemm_ms_while_copying": round(statistics.median(busy), 3) if busy else None,
-            "gemm_slowdown_pct": round(100.0 * (statistics.median(busy) / ref_gemm - 1), 3) if busy else None}, ref_gemm
+            "gemm_slowdown_pct": round(100.0 * (statistics.median(busy) / base_gemm_ms - 1), 3) if busy else None}
+        if len(quiet) >= 3:
+            q_iter, q_gemm = statistics.median(quiet_iter), statistics.median(quiet)
+            q_total = sum(reg["iter_ms"]) - q_iter * n
+            out["vs_quiet_steps_of_the_same_region"] = {
+                "reference_ms_per_step": round(q_iter, 3), "stall_ms_per_step": round(q_total / n, 3),
+                "stall_pct": round(100.0 * q_total / (q_iter * n), 3), "stall_ms_per_snapshot": round(q_total / max(1, len(in_reg)), 2),
+                "gemm_ms_reference": round(q_gemm, 3),
+                "gemm_slowdown_pct": round(100.0 * (statistics.median(busy) / q_gemm - 1), 3) if busy else None,
+                "quiet_steps_slower_than_baseline_pct": round(100.0 * (q_iter / base_iter_ms - 1), 3)}
+        return in_reg, out, base_gemm_ms
 
     # ---- baseline before; warm-up (untimed); the timed region of exactly K steps
     say("baseline phase (no checkpoints)")
@@ -420,6 +471,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     base_after = baseline_phase(args.baseline_steps)
     base_iter_ms = 0.5 * (base_before[0] + base_after[0])
     base_gemm_ms = 0.5 * (base_before[1] + base_after[1])
+    idle_lib = baseline_phase(args.idle_library_steps, library_calls=True) if args.idle_library_steps > 0 else None
 
     in_region, stall, ref_gemm_ms = stall_report(main, base_iter_ms, base_gemm_ms)
     stats = [ck.stats(it) for it in in_region]
@@ -432,7 +484,9 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     pack_ms = sum(s["pack_ms_sum"] for s in stats)
     # algorithmic bytes of the pack kernel: every payload byte read once, every data-region byte written once
     # (tensors copied directly on the hybrid path never pass through the kernel)
-    pack_bytes_per_snapshot = lay["payload_bytes"] - lay["direct_bytes"] + lay["data_bytes"] - lay["direct_data_bytes"]
+    # (nor do the derived tensors a version-2 snapshot leaves out)
+    pack_bytes_per_snapshot = (lay["payload_bytes"] - lay["direct_bytes"] + lay["data_bytes"] - lay["direct_data_bytes"] if not pairs else
+                               lay["payload_bytes"] - lay["derived_bytes"] + lay["reduced_data_bytes"])
     pack_gbps = gbps(pack_bytes_per_snapshot * len(stats), pack_ms) if stats else None
     # physical floor under the paper's rule: the copies cannot end before D / B_link, the window is the GEMM phase
     stall["floor_ms_per_snapshot"] = round(max(0.0, S / (link["d2h"] * 1e9) * 1e3 - ref_gemm_ms), 2)
@@ -443,6 +497,8 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         paired["stall_minus_floor_ms_per_step"] = round(paired["stall_ms_per_step"] - stall["floor_ms_per_snapshot"], 2)
         stall["paired_alternating_blocks"] = paired
     stall["baseline_before_after_ms"] = [round(base_before[0], 2), round(base_after[0], 2)]
+    if idle_lib:
+        stall["library_idle_ms_per_step"] = round(idle_lib[0], 3)   # library calls in the loop, nothing pending, long after the last copy
     stall["gemm_tflops"] = round(gemm.flops_per_launch / (gemm_ms_per_launch * 1e-3) / 1e12, 1)
 
     result = {
@@ -461,7 +517,8 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                    "hip_runtime": info["hip_runtime_version"], "io_mode": args.io_mode, "o_direct": args.o_direct, "fsync_on_commit": args.fsync, "keep_last": args.keep_last,
                    "prealloc_files": args.prealloc, "sink": out_dir.rsplit("/", 1)[0],
                    "direct_min_mib": args.direct_min_mib, "direct_tensors": lay["n_direct_tensors"],
-                   "direct_bytes": lay["direct_bytes"], "copy_segments": lay["n_segments"]},
+                   "direct_bytes": lay["direct_bytes"], "copy_segments": lay["n_segments"],
+                   "reduce": args.reduce, "derived_tensors": lay["n_derived_tensors"], "link_bytes_per_snapshot": S},
         "roofline": {"bound": "hbm", "kernel": "pack_kernel", "achieved": round(pack_gbps, 1) if pack_gbps else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(pack_gbps / HBM_PEAK_GBPS, 4) if pack_gbps else None,
                      "traffic": None, "traffic_source": "rocprofv3 FETCH_SIZE+WRITE_SIZE of this kernel on this workload, scaled by a copy kernel of known size (profiles/), as a ratio x algorithmic bytes per launch",
@@ -475,6 +532,9 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                      "d2h_frac_of_link_peak": round(link_gbps / link["d2h"], 4) if link_gbps else None,
                      "snapshot_gbps_frac_of_link_peak": round(snap_gbps / link["d2h"], 4) if snap_gbps else None,
                      "host_snapshot_call_ms": round(max(s["host_snapshot_call_ms"] for s in all_stats), 3) if all_stats else None,
+                     "host_window_wait_ms": round(max(s["host_window_wait_ms"] for s in all_stats), 3) if all_stats else None,
+                     "format_versions": sorted({s["format_version"] for s in all_stats}),
+                     "verify_ms": round(statistics.median(s["verify_ms"] for s in all_stats), 3) if pairs and all_stats else None,
                      "flush_gbps": round(statistics.median(S / (s["host_flush_span_ms"] * 1e-3) / 1e9 for s in all_stats), 2) if all_stats else None,
                      "drain_s": round(drain_s, 2), "init_s": round(init_s, 2)},
         "stall": stall,

@@ -125,6 +125,9 @@ typedef struct {
     uint64_t direct_data_bytes;                    /* the same tensors' share of the data region (payload + padding) */
     uint64_t n_host_objects, host_bytes;           /* host-resident objects (CKPT_PLACE_HOST) and their payload */
     uint64_t host_data_bytes;                      /* their share of the data region */
+    uint64_t version;                              /* format version of the file this layout describes (1, or 2: derived tensors) */
+    uint64_t n_derived_tensors, derived_bytes;     /* version 2: tensors described but not stored, and their payload */
+    uint64_t reduced_header_bytes, reduced_data_bytes; /* of the version-2 file of the same registration (0: no pairs declared) */
 } ckpt_layout;
 
 /* One pack work item: `copy_bytes` bytes from device address `src` go to offset `dst_off` of the data
@@ -190,6 +193,10 @@ typedef struct {
     double host_io_wait_ms_sum;       /* host: summed over I/O threads, time waiting for chunks' copy events */
     double host_io_copy_ms_sum;       /* host: summed over I/O threads, time writing ring slots to the file */
     double host_tier2_ms;             /* host: copy of the committed file to the second tier, open to rename (-1: none yet) */
+    int32_t format_version;           /* 1 or 2 (docs/FORMAT.md); 0 while not yet decided */
+    int32_t reserved0;
+    double verify_ms;                 /* device time of the derived-tensor check that decides the version (-1: no pairs declared) */
+    double host_window_wait_ms;       /* host: time the caller spent inside ckpt_wait_immutable_window_end for this snapshot */
 } ckpt_stats;
 
 #define CKPT_ITER_ALL UINT64_MAX
@@ -200,6 +207,11 @@ typedef struct {
  * as given and never dereferenced. CKPT_EINVAL on a bad description or configuration. */
 int ckpt_plan_create(const ckpt_tensor_desc *tensors, size_t n, const ckpt_config *cfg, ckpt_plan **out);
 int ckpt_plan_layout(const ckpt_plan *plan, ckpt_layout *out);
+/* The same for format version 2 (docs/FORMAT.md, derived tensors): tensor derived[i] (bf16) is declared to be the
+ * round-to-nearest-even of tensor source[i] (f32, same shape, both device-resident) and gets a table entry but no
+ * place in the data region. CKPT_EINVAL for a malformed pair list. */
+int ckpt_plan_create_derived(const ckpt_tensor_desc *tensors, size_t n, const ckpt_config *cfg, const uint32_t *derived,
+                             const uint32_t *source, size_t n_pairs, ckpt_plan **out);
 /* Copies the header_bytes bytes of the header for iteration `iter` into buf (cap >= header_bytes). */
 int ckpt_plan_header(const ckpt_plan *plan, uint64_t iter, void *buf, uint64_t cap);
 /* File offset of every tensor, in registration order (cap >= n_tensors entries). */
@@ -228,6 +240,19 @@ int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out);
  * memory of this GPU (CKPT_EINVAL otherwise). CKPT_ESTATE if tensors are already registered.
  * Overlapping device ranges are allowed (serialized twice). */
 int ckpt_register_tensors(ckpt_ctx *ctx, const ckpt_tensor_desc *tensors, size_t n);
+
+/* Data reduction, the future work the paper's Conclusions name (and the limitation its Introduction states: link
+ * and storage cannot keep up with the checkpoint rate), in a first lossless form (docs/FORMAT.md, version 2).
+ * Declares that registered tensor derived[i] (bf16) is kept by the training loop as the round-to-nearest-even of
+ * tensor source[i] (f32, same shape): the working copy and the master weights of mixed-precision training, 2 of
+ * 14 bytes per parameter. To be called after ckpt_init and before ckpt_register_tensors (indices refer to the list
+ * registered afterwards, where they are checked: CKPT_EINVAL there). From then on every snapshot first checks on
+ * the device, on the captured state, that every declared pair holds element for element (integer arithmetic on
+ * the bit patterns, 6 bytes per parameter read once); if so the file is version 2 and the derived tensors are
+ * neither packed, nor copied, nor written; if any element differs the snapshot is an ordinary version-1 file.
+ * Either way a restore returns exactly the captured bytes: ckpt_restore reads both versions and recomputes the
+ * derived tensors on the device. Host-resident objects cannot take part. CKPT_ESTATE after registration. */
+int ckpt_declare_derived(ckpt_ctx *ctx, const uint32_t *derived, const uint32_t *source, size_t n_pairs);
 
 /* A checkpoint request as the "lazy non-blocking copies" design principle defines it: it returns at once,
  * the copies run while the next forward and backward passes leave the state untouched (the paper's section on

@@ -39,7 +39,8 @@ class ckpt_layout(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("n_tensors", "header_bytes", "data_bytes", "file_bytes", "payload_bytes", "n_tiles",
                                           "n_chunks", "n_superchunks", "dma_chunk_bytes", "pack_superchunk_bytes", "tile_bytes",
                                           "n_segments", "n_direct_tensors", "direct_bytes", "direct_data_bytes",
-                                          "n_host_objects", "host_bytes", "host_data_bytes")]
+                                          "n_host_objects", "host_bytes", "host_data_bytes", "version", "n_derived_tensors",
+                                          "derived_bytes", "reduced_header_bytes", "reduced_data_bytes")]
 
 
 class ckpt_tile(C.Structure):
@@ -62,7 +63,8 @@ class ckpt_stats(C.Structure):
                 ("request_to_pack_end_ms", C.c_double), ("host_submit_ms", C.c_double), ("host_request_to_commit_ms", C.c_double),
                 ("host_backpressure_ms", C.c_double), ("host_snapshot_call_ms", C.c_double),
                 ("host_flush_span_ms", C.c_double), ("host_io_wait_ms_sum", C.c_double), ("host_io_copy_ms_sum", C.c_double),
-                ("host_tier2_ms", C.c_double)]
+                ("host_tier2_ms", C.c_double), ("format_version", C.c_int32), ("reserved0", C.c_int32), ("verify_ms", C.c_double),
+                ("host_window_wait_ms", C.c_double)]
 
 CKPT_TIER2_NEWEST, CKPT_TIER2_EVERY = 0, 1
 CKPT_TIER2_NONE, CKPT_TIER2_QUEUED, CKPT_TIER2_COPYING, CKPT_TIER2_DONE, CKPT_TIER2_SKIPPED, CKPT_TIER2_FAILED = range(6)
@@ -84,6 +86,8 @@ lib = C.CDLL(LIB_PATH)
 _vp, _u64, _i32 = C.c_void_p, C.c_uint64, C.c_int32
 _SIGS = {
     "ckpt_plan_create": (C.c_int, [C.POINTER(ckpt_tensor_desc), C.c_size_t, C.POINTER(ckpt_config), C.POINTER(_vp)]),
+    "ckpt_plan_create_derived": (C.c_int, [C.POINTER(ckpt_tensor_desc), C.c_size_t, C.POINTER(ckpt_config), C.POINTER(C.c_uint32),
+                                            C.POINTER(C.c_uint32), C.c_size_t, C.POINTER(_vp)]),
     "ckpt_plan_layout": (C.c_int, [_vp, C.POINTER(ckpt_layout)]),
     "ckpt_plan_header": (C.c_int, [_vp, _u64, _vp, _u64]),
     "ckpt_plan_offsets": (C.c_int, [_vp, C.POINTER(_u64), C.c_size_t]),
@@ -93,6 +97,7 @@ _SIGS = {
     "ckpt_plan_chunk_segments": (C.c_int, [_vp, C.POINTER(_u64), C.c_size_t]),
     "ckpt_plan_destroy": (None, [_vp]),
     "ckpt_init": (C.c_int, [C.POINTER(ckpt_config), C.POINTER(_vp)]),
+    "ckpt_declare_derived": (C.c_int, [_vp, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.c_size_t]),
     "ckpt_register_tensors": (C.c_int, [_vp, C.POINTER(ckpt_tensor_desc), C.c_size_t]),
     "ckpt_snapshot_async": (C.c_int, [_vp, _u64, _vp]),
     "ckpt_wait_immutable_window_end": (C.c_int, [_vp, _vp, _i32]),
@@ -222,15 +227,27 @@ def pack_image_noalloc(tensors, dev_dst, dst_bytes, stream):
     _check(lib.ckpt_pack_image_noalloc(arr, len(tensors), dev_dst, dst_bytes, stream))
 
 
+def _pair_arrays(pairs):
+    pairs = list(pairs)
+    d = (C.c_uint32 * max(1, len(pairs)))(*[p[0] for p in pairs])
+    s = (C.c_uint32 * max(1, len(pairs)))(*[p[1] for p in pairs])
+    return d, s
+
+
 class Plan:
     """ckpt_plan_*: layout, header, offsets and tile table of a tensor list, no device needed."""
 
-    def __init__(self, tensors, cfg=None):
+    def __init__(self, tensors, cfg=None, derived=None):
+        """derived: list of (derived index, source index): the version-2 plan (ckpt_plan_create_derived)."""
         cfg = cfg or make_config()
         tensors = list(tensors)
         arr, keep = make_descs(tensors)
         self._h = _vp()
-        _check(lib.ckpt_plan_create(arr, len(tensors), C.byref(cfg), C.byref(self._h)))
+        if derived is None:
+            _check(lib.ckpt_plan_create(arr, len(tensors), C.byref(cfg), C.byref(self._h)))
+        else:
+            d, s = _pair_arrays(derived)
+            _check(lib.ckpt_plan_create_derived(arr, len(tensors), C.byref(cfg), d, s, len(derived), C.byref(self._h)))
 
     def layout(self):
         out = ckpt_layout()
@@ -289,6 +306,12 @@ class Checkpointer:
         self._h = _vp()
         self._cfg = cfg
         _check(lib.ckpt_init(C.byref(cfg), C.byref(self._h)))
+
+    def declare_derived(self, pairs):
+        """ckpt_declare_derived: pairs = list of (derived index, source index), before register_tensors."""
+        pairs = list(pairs)
+        d, s = _pair_arrays(pairs)
+        _check(lib.ckpt_declare_derived(self._h, d, s, len(pairs)))
 
     def register_tensors(self, tensors):
         tensors = list(tensors)

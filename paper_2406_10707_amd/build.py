@@ -8,8 +8,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libdsllm_ckpt.so")
 SOURCES = ["plan.cpp", "engine.cpp", "submit.cpp", "io_threads.cpp", "restore.cpp", "second_tier.cpp", "pack_kernels.hip",
-           "pack_image.hip", "proxy_kernels.hip"]
-HEADERS = ["plan.hpp", "engine_internal.hpp", "tile_batch.hpp", os.path.join("..", "..", "include", "ckpt.h"), os.path.join("..", "..", "include", "ckpt_proxy.h")]
+           "pack_image.hip", "derive_kernels.hip", "proxy_kernels.hip"]
+HEADERS = ["plan.hpp", "engine_internal.hpp", "tile_batch.hpp", "kernel_util.hpp", os.path.join("..", "..", "include", "ckpt.h"), os.path.join("..", "..", "include", "ckpt_proxy.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",

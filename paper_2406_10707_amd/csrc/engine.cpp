@@ -46,6 +46,7 @@ bool dsllm::preallocate_file(const std::string &path, uint64_t bytes, int n_thre
     if (!ok) { unlink(path.c_str()); return false; }
     // reopen the way the flush will use it; with a mapping, fault every page in now
     out->path = path;
+    out->bytes = bytes;
     out->fd = open(path.c_str(), (map_it ? O_RDWR : O_WRONLY) | (o_direct ? O_DIRECT : 0));
     if (out->fd < 0) { *err = path + ": open: " + strerror(errno); unlink(path.c_str()); return false; }
     if (map_it) {
@@ -93,6 +94,23 @@ int ckpt_plan_create(const ckpt_tensor_desc *tensors, size_t n, const ckpt_confi
     return CKPT_OK;
 }
 
+int ckpt_plan_create_derived(const ckpt_tensor_desc *tensors, size_t n, const ckpt_config *cfg, const uint32_t *derived, const uint32_t *source,
+                             size_t n_pairs, ckpt_plan **out) {
+    if (!cfg || !out || (n_pairs && (!derived || !source))) return fail(CKPT_EINVAL, "null argument");
+    ResolvedConfig rc;
+    std::string err;
+    int r = resolve_config(cfg, &rc, &err);
+    if (r) return fail(r, err);
+    DerivedPairs dp;
+    dp.derived.assign(derived, derived + n_pairs);
+    dp.source.assign(source, source + n_pairs);
+    std::unique_ptr<ckpt_plan> p(new ckpt_plan);
+    r = build_plan(tensors, n, rc, &p->plan, &err, &dp, true);
+    if (r) return fail(r, err);
+    *out = p.release();
+    return CKPT_OK;
+}
+
 static void fill_layout(const Plan &p, ckpt_layout *o) {
     o->n_tensors = p.tensors.size();
     o->header_bytes = p.header_bytes;
@@ -112,6 +130,11 @@ static void fill_layout(const Plan &p, ckpt_layout *o) {
     o->n_host_objects = p.n_host;
     o->host_bytes = p.host_bytes;
     o->host_data_bytes = p.host_data_bytes;
+    o->version = p.version;
+    o->n_derived_tensors = p.n_derived;
+    o->derived_bytes = p.derived_bytes;
+    o->reduced_header_bytes = p.version == 2 ? p.header_bytes : 0;
+    o->reduced_data_bytes = p.version == 2 ? p.data_bytes : 0;
 }
 
 int ckpt_plan_layout(const ckpt_plan *plan, ckpt_layout *out) {
@@ -254,9 +277,11 @@ int ckpt_register_tensors(ckpt_ctx *c, const ckpt_tensor_desc *tensors, size_t n
     for (size_t k = 0; tensors && k < n; k++)
         if (!tensors[k].dev_ptr) return fail(CKPT_EINVAL, "tensor " + std::to_string(k) + ": null device pointer");
     std::string err;
-    Plan p;
-    int r = build_plan(tensors, n, c->cfg, &p, &err);
+    Plan p, rp;
+    const bool reduce = c->pairs.size() > 0;
+    int r = build_plan(tensors, n, c->cfg, &p, &err, reduce ? &c->pairs : nullptr, false);
     if (r) return fail(r, err);
+    if (reduce && (r = build_plan(tensors, n, c->cfg, &rp, &err, &c->pairs, true)) != CKPT_OK) return fail(r, err);
     // every source range must be device memory of this GPU: checked here, once, before any launch
     for (const auto &t : p.tensors) {
         if (t.host) continue;   // host-resident object: the caller vouches for the range
@@ -283,6 +308,21 @@ int ckpt_register_tensors(ckpt_ctx *c, const ckpt_tensor_desc *tensors, size_t n
     e = hipMalloc(reinterpret_cast<void **>(&c->dev_tiles), p.tiles.size() * sizeof(ckpt_tile));
     if (e != hipSuccess) return fail(CKPT_ENOMEM, std::string("hipMalloc(tile table): ") + hipGetErrorString(e));
     HIP_TRY(c, hipMemcpy(c->dev_tiles, p.tiles.data(), p.tiles.size() * sizeof(ckpt_tile), hipMemcpyHostToDevice));
+    if (reduce) {
+        // the version-2 plan's tile table, the work items of the check, and the word its verdict lands in
+        e = hipMalloc(reinterpret_cast<void **>(&c->dev_rtiles), std::max<size_t>(rp.tiles.size(), 1) * sizeof(ckpt_tile));
+        if (e != hipSuccess) return fail(CKPT_ENOMEM, std::string("hipMalloc(tile table): ") + hipGetErrorString(e));
+        HIP_TRY(c, hipMemcpy(c->dev_rtiles, rp.tiles.data(), rp.tiles.size() * sizeof(ckpt_tile), hipMemcpyHostToDevice));
+        e = hipMalloc(reinterpret_cast<void **>(&c->dev_pairs), std::max<size_t>(p.pair_tiles.size(), 1) * sizeof(PairTile));
+        if (e != hipSuccess) return fail(CKPT_ENOMEM, std::string("hipMalloc(pair table): ") + hipGetErrorString(e));
+        HIP_TRY(c, hipMemcpy(c->dev_pairs, p.pair_tiles.data(), p.pair_tiles.size() * sizeof(PairTile), hipMemcpyHostToDevice));
+        HIP_TRY(c, hipMalloc(reinterpret_cast<void **>(&c->dev_flag), 256));
+        HIP_TRY(c, hipHostMalloc(reinterpret_cast<void **>(&c->host_flag), 4096, hipHostMallocDefault));
+        *c->host_flag = 1;
+        HIP_TRY(c, hipEventCreate(&c->ev_verify_start));
+        HIP_TRY(c, hipEventCreate(&c->ev_verify_done));
+        HIP_TRY(c, hipEventCreate(&c->ev_derived));
+    }
     for (uint64_t s = 0; s < p.n_superchunks; s++) {
         hipEvent_t a, b;
         HIP_TRY(c, hipEventCreate(&a));
@@ -297,8 +337,9 @@ int ckpt_register_tensors(ckpt_ctx *c, const ckpt_tensor_desc *tensors, size_t n
             HIP_TRY(c, hipEventCreateWithFlags(&ev, hipEventDisableTiming));
             c->ev_stage_done[s].push_back(ev);
         }
-    if (posix_memalign(reinterpret_cast<void **>(&c->hdr_buf), 4096, p.header_bytes) != 0) return fail(CKPT_ENOMEM, "header buffer");
+    if (posix_memalign(reinterpret_cast<void **>(&c->hdr_buf), 4096, std::max(p.header_bytes, reduce ? rp.header_bytes : 0)) != 0) return fail(CKPT_ENOMEM, "header buffer");
     c->plan = std::move(p);
+    if (reduce) { c->rplan = std::move(rp); c->have_rplan = true; }
     c->registered = true;
     // spare files side by side: page allocation is serialized per file, not across files
     // with a second tier the file under copy there is exempt from recycling: one more file is in rotation
@@ -310,7 +351,8 @@ int ckpt_register_tensors(ckpt_ctx *c, const ckpt_tensor_desc *tensors, size_t n
     for (int i = 0; i < n_spare; i++) {
         std::string spare = c->out_dir + "/.spare_" + std::to_string(getpid()) + "_" + std::to_string(c->spare_seq++) + ".dsl";
         workers.emplace_back([&, i, spare] {
-            ok[i] = preallocate_file(spare, c->plan.file_bytes(), std::min(c->cfg.n_io_threads, 8), c->cfg.io_mode == CKPT_IO_MMAP, c->cfg.o_direct,
+            // sized for the file a snapshot is expected to be: version 2 when pairs are declared
+            ok[i] = preallocate_file(spare, expected_file_bytes(c), std::min(c->cfg.n_io_threads, 8), c->cfg.io_mode == CKPT_IO_MMAP, c->cfg.o_direct,
                                      &made[i], &errs[i]);
         });
     }
@@ -343,7 +385,6 @@ int ckpt_snapshot_async(ckpt_ctx *c, uint64_t iter, void *stream) {
     sp->iter = iter;
     sp->final_path = file_name_for(c->out_dir, iter);
     sp->tmp_path = sp->final_path + ".tmp";
-    sp->chunks_left = c->plan.n_chunks;
     sp->t_request = t0;
     if (c->plan.n_host) {   // host memory is not ordered with the stream: read it now, the caller may change it after this call
         sp->host_capture.resize(c->plan.host_bytes);
@@ -382,6 +423,7 @@ int ckpt_snapshot_async(ckpt_ctx *c, uint64_t iter, void *stream) {
 
 int ckpt_wait_immutable_window_end(ckpt_ctx *c, void *stream, int32_t host_block) {
     if (!c) return fail(CKPT_EINVAL, "null context");
+    const auto t_enter = Clock::now();
     std::shared_ptr<Snap> sp;
     {
         std::unique_lock<std::mutex> lk(c->mu);
@@ -395,7 +437,7 @@ int ckpt_wait_immutable_window_end(ckpt_ctx *c, void *stream, int32_t host_block
     HIP_TRY(c, hipSetDevice(c->device));
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (sp->policy == CKPT_WINDOW_PACK) {
-        hipEvent_t ev = c->ev_packed[c->plan.n_superchunks - 1];
+        hipEvent_t ev = c->ev_packed[sp->plan->n_superchunks - 1];
         HIP_TRY(c, hipStreamWaitEvent(st, ev, 0));
         if (host_block) HIP_TRY(c, hipEventSynchronize(ev));
     } else {
@@ -405,6 +447,7 @@ int ckpt_wait_immutable_window_end(ckpt_ctx *c, void *stream, int32_t host_block
     }
     std::lock_guard<std::mutex> lk(c->mu);
     sp->window_closed = true;
+    sp->window_wait_ms = ms_between(t_enter, Clock::now());
     return CKPT_OK;
 }
 
@@ -452,6 +495,20 @@ int ckpt_get_layout(ckpt_ctx *c, ckpt_layout *out) {
     if (!c || !out) return fail(CKPT_EINVAL, "null argument");
     if (!c->registered) return fail(CKPT_ESTATE, "no tensors registered");
     fill_layout(c->plan, out);
+    if (c->have_rplan) {
+        out->n_derived_tensors = c->rplan.n_derived;
+        out->derived_bytes = c->rplan.derived_bytes;
+        out->reduced_header_bytes = c->rplan.header_bytes;
+        out->reduced_data_bytes = c->rplan.data_bytes;
+    }
+    return CKPT_OK;
+}
+
+int ckpt_declare_derived(ckpt_ctx *c, const uint32_t *derived, const uint32_t *source, size_t n_pairs) {
+    if (!c || (n_pairs && (!derived || !source))) return fail(CKPT_EINVAL, "null argument");
+    if (c->registered) return fail(CKPT_ESTATE, "derived tensors must be declared before ckpt_register_tensors");
+    c->pairs.derived.assign(derived, derived + n_pairs);
+    c->pairs.source.assign(source, source + n_pairs);
     return CKPT_OK;
 }
 
@@ -463,12 +520,16 @@ int ckpt_get_stats(ckpt_ctx *c, uint64_t iter, ckpt_stats *o) {
     const Snap &s = *it->second;
     memset(o, 0, sizeof *o);
     o->iter = s.iter;
-    o->payload_bytes = c->plan.payload_bytes;
-    o->data_bytes = c->plan.data_bytes;
-    o->file_bytes = c->plan.file_bytes();
+    const Plan &sp = s.plan ? *s.plan : c->plan;
+    o->payload_bytes = sp.payload_bytes - sp.derived_bytes;   // what this snapshot stores
+    o->data_bytes = sp.data_bytes;
+    o->file_bytes = sp.file_bytes();
+    o->format_version = s.plan ? int32_t(s.plan->version) : 0;
+    o->verify_ms = s.verify_ms;
+    o->host_window_wait_ms = s.window_wait_ms;
     o->d2h_done = s.d2h_done;
     o->committed = s.committed;
-    o->pack_launches = int32_t(c->plan.n_superchunks);
+    o->pack_launches = int32_t(sp.n_superchunks);
     o->tier2_state = s.tier2_state;
     o->host_tier2_ms = s.tier2_ms;
     o->pack_ms_sum = s.pack_ms_sum;
@@ -539,6 +600,13 @@ int ckpt_destroy(ckpt_ctx *c) {
     for (auto s : c->dma) (void)hipStreamDestroy(s);
     if (c->staging) (void)hipFree(c->staging);
     if (c->dev_tiles) (void)hipFree(c->dev_tiles);
+    if (c->dev_rtiles) (void)hipFree(c->dev_rtiles);
+    if (c->dev_pairs) (void)hipFree(c->dev_pairs);
+    if (c->dev_flag) (void)hipFree(c->dev_flag);
+    if (c->host_flag) (void)hipHostFree(c->host_flag);
+    if (c->ev_verify_start) (void)hipEventDestroy(c->ev_verify_start);
+    if (c->ev_verify_done) (void)hipEventDestroy(c->ev_verify_done);
+    if (c->ev_derived) (void)hipEventDestroy(c->ev_derived);
     if (c->ring) (void)hipHostFree(c->ring);
     for (auto &sp : c->spares) { sp.close_all(); unlink(sp.path.c_str()); }
     for (auto &kv : c->kept) kv.second.close_all();

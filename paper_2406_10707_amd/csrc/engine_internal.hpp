@@ -32,6 +32,8 @@
 namespace dsllm {
 hipError_t launch_pack(const ckpt_tile *dev_tiles, uint64_t n_tiles, void *slot_base, uint64_t slot_data_off, hipStream_t stream);
 hipError_t launch_scatter(const ckpt_tile *dev_tiles, uint64_t n_tiles, const void *slot_base, uint64_t slot_data_off, hipStream_t stream);
+hipError_t launch_verify_pairs(const PairTile *dev_tiles, uint64_t n_tiles, uint32_t *dev_flag, hipStream_t stream);
+hipError_t launch_derive_pairs(const PairTile *dev_tiles, uint64_t n_tiles, hipStream_t stream);
 }  // namespace dsllm
 
 using namespace dsllm;
@@ -62,6 +64,7 @@ struct FileSlot {
     int fd = -1;
     uint8_t *map = nullptr;           // whole-file shared mapping when the sink is written through mmap
     uint64_t map_bytes = 0;
+    uint64_t bytes = 0;               // size of the file (a spare is reused only for a snapshot of exactly this size)
     void close_all() {
         if (map) munmap(map, map_bytes);
         if (fd >= 0) ::close(fd);
@@ -71,6 +74,13 @@ struct FileSlot {
 
 struct Snap {
     uint64_t iter = 0;
+    // The plan this snapshot is written with: the registration's version-1 plan, or its version-2 plan when
+    // derived tensors were declared and the check on the captured state found every pair to hold. Chosen by the
+    // submit thread before the first pack launch; null until then.
+    const Plan *plan = nullptr;
+    const ckpt_tile *dev_tiles = nullptr;   // that plan's tile table on the device
+    double verify_ms = -1;                  // device time of the derivation check (-1: none)
+    double window_wait_ms = 0;              // host: time the caller spent in ckpt_wait_immutable_window_end for this snapshot
     int fd = -1;
     uint8_t *map = nullptr;
     std::string tmp_path, final_path;
@@ -122,6 +132,14 @@ struct ckpt_ctx {
     uint8_t *staging = nullptr;       // device
     uint64_t n_stage = 0;
     ckpt_tile *dev_tiles = nullptr;
+    // data reduction (format version 2): declared pairs, the plan without the derived tensors, the check's tables
+    DerivedPairs pairs;
+    bool have_rplan = false;
+    Plan rplan;
+    ckpt_tile *dev_rtiles = nullptr;
+    PairTile *dev_pairs = nullptr;
+    uint32_t *dev_flag = nullptr, *host_flag = nullptr;   // verdict of the check: device word, pinned host word it is copied to
+    hipEvent_t ev_verify_start = nullptr, ev_verify_done = nullptr, ev_derived = nullptr;
     hipStream_t pack_stream = nullptr;
     std::vector<hipStream_t> dma;
     std::vector<hipEvent_t> ev_slot;                      // per ring slot: copy into/out of the slot done
@@ -189,6 +207,8 @@ struct ckpt_ctx {
     } while (0)
 
 namespace dsllm {
+// size of the file a snapshot of this registration is expected to have (what spare files are made for)
+inline uint64_t expected_file_bytes(const ckpt_ctx *c) { return c->have_rplan ? c->rplan.file_bytes() : c->plan.file_bytes(); }
 inline std::string file_name_for(const std::string &dir, uint64_t iter) {
     char buf[64];
     snprintf(buf, sizeof buf, "/ckpt_iter%020llu.dsl", (unsigned long long)iter);

@@ -9,13 +9,14 @@ static void finish_d2h_stats(ckpt_ctx *c, Snap *s) {
     // called by the I/O thread that owns the snapshot's last chunk, after all tail events completed
     double pack_sum = 0, req_d2h = 0, span = 0, req_pack = 0;
     float ms = 0;
-    for (uint64_t i = 0; i < c->plan.n_superchunks; i++)
+    const uint64_t n_sc = s->plan->n_superchunks;
+    for (uint64_t i = 0; i < n_sc; i++)
         if (hipEventElapsedTime(&ms, c->ev_pack_start[i], c->ev_packed[i]) == hipSuccess) pack_sum += ms;
     for (size_t k = 0; k < c->dma.size(); k++) {
         if (hipEventElapsedTime(&ms, s->ev_boundary, c->ev_job_tail[k]) == hipSuccess && ms > req_d2h) req_d2h = ms;
         if (hipEventElapsedTime(&ms, c->ev_first_copy, c->ev_job_tail[k]) == hipSuccess && ms > span) span = ms;
     }
-    if (hipEventElapsedTime(&ms, s->ev_boundary, c->ev_packed[c->plan.n_superchunks - 1]) == hipSuccess) req_pack = ms;
+    if (hipEventElapsedTime(&ms, s->ev_boundary, c->ev_packed[n_sc - 1]) == hipSuccess) req_pack = ms;
     std::lock_guard<std::mutex> lk(c->mu);
     c->ev_boundary_free.push_back(s->ev_boundary);   // back to the pool
     s->ev_boundary = nullptr;
@@ -95,7 +96,7 @@ void dsllm::io_thread_main(ckpt_ctx *c) {
         auto tw1 = Clock::now();
         s->io_wait_us += uint64_t(ms_between(tw0, tw1) * 1000.0);
         if (he != hipSuccess) c->fail_snapshot(s, CKPT_EHIP, std::string("copy event: ") + hipGetErrorString(he));
-        if (job.file_off == c->plan.header_bytes) {
+        if (job.file_off == s->plan->header_bytes) {
             std::lock_guard<std::mutex> lk(c->mu);
             s->t_first_chunk = Clock::now();
             s->have_first_chunk = true;
@@ -125,11 +126,11 @@ void dsllm::io_thread_main(ckpt_ctx *c) {
             if (s->fd >= 0) {
                 const bool retain = c->cfg.keep_last > 0;
                 const bool sync = c->cfg.fsync_on_commit != 0;
-                if (s->map && sync && msync(s->map, c->plan.file_bytes(), MS_SYNC) != 0)
+                if (s->map && sync && msync(s->map, s->plan->file_bytes(), MS_SYNC) != 0)
                     c->fail_snapshot(s, CKPT_EIO, s->tmp_path + ": msync: " + strerror(errno));
                 if (sync && fsync(s->fd) != 0) c->fail_snapshot(s, CKPT_EIO, s->tmp_path + ": fsync: " + strerror(errno));
                 FileSlot fs;
-                fs.path = s->final_path; fs.fd = s->fd; fs.map = s->map; fs.map_bytes = c->plan.file_bytes();
+                fs.path = s->final_path; fs.fd = s->fd; fs.map = s->map; fs.map_bytes = s->plan->file_bytes(); fs.bytes = s->plan->file_bytes();
                 s->fd = -1; s->map = nullptr;
                 bool had_error;
                 { std::lock_guard<std::mutex> lk(c->mu); had_error = s->failed; }

@@ -14,11 +14,10 @@
 #include <stdint.h>
 
 #include "../../include/ckpt.h"
+#include "kernel_util.hpp"
 #include "tile_batch.hpp"
 
 namespace dsllm {
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // tuning constants (overridable at compile time for sweeps)
 #ifndef DSLLM_PACK_WAVES_PER_BLOCK
@@ -44,39 +43,20 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #ifndef DSLLM_PACK_MISALIGNED
 #define DSLLM_PACK_MISALIGNED 0
 #endif
+#ifndef DSLLM_PACK_UNROLL_MIS
+#define DSLLM_PACK_UNROLL_MIS DSLLM_PACK_UNROLL     // loads in flight per lane on the unaligned-load path
+#endif
+#ifndef DSLLM_PACK_PIPE
+#define DSLLM_PACK_PIPE 0                           // 1: the next group's loads are issued before this group's stores
+#endif
+#ifndef DSLLM_PACK_XCHG_MAX
+#define DSLLM_PACK_XCHG_MAX 8                       // largest group of the exchange path (8 or 16)
+#endif
 constexpr uint64_t kPackTileBytes = 32 * 1024;   // the planner's tile size (plan.hpp: kTileBytes)
 constexpr int kWavesPerBlock = DSLLM_PACK_WAVES_PER_BLOCK;
 constexpr int kBlock = 64 * kWavesPerBlock;
 constexpr int kUnroll = DSLLM_PACK_UNROLL;             // aligned path: 16-byte words per lane in flight
 constexpr int kUnrollShift = DSLLM_PACK_UNROLL_SHIFT;  // misaligned path: pairs of 16-byte words per lane in flight
-
-// Tensor addresses come out of the descriptor table as integers, so the compiler cannot know they
-// are global memory and would use flat loads (which also pass through the LDS address check and
-// count against two wait counters). Casting to the global address space gives global_load/store.
-#if defined(__HIP_DEVICE_COMPILE__)
-#define DSLLM_GLOBAL __attribute__((address_space(1)))
-// Keeps a loaded 16-byte word whole and in registers of its own. Without it the compiler narrows the
-// two loads of the misaligned path to the dwords the shift uses and packs them into overlapping
-// registers, which forces a wait after every pair of loads.
-#define DSLLM_KEEP_WHOLE(v) asm volatile("" : "+v"(v))
-#else
-#define DSLLM_GLOBAL
-#define DSLLM_KEEP_WHOLE(v) (void)0
-#endif
-__device__ __forceinline__ u32x4 ld16(const u32x4 *p) { return __builtin_nontemporal_load((const u32x4 DSLLM_GLOBAL *)p); }
-typedef u32x4 u32x4_bytealigned __attribute__((aligned(1)));
-// 16 bytes from any byte address; all 16 must lie inside the tensor
-__device__ __forceinline__ u32x4 ld16_unaligned(const uint8_t *p) { return __builtin_nontemporal_load((const u32x4_bytealigned DSLLM_GLOBAL *)p); }
-__device__ __forceinline__ void st16(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, (u32x4 DSLLM_GLOBAL *)p); }
-
-// A value that is the same in every lane of the wavefront, moved to scalar registers. The builtin
-// returns a signed int: each half goes through uint32_t before widening, or the low half would be
-// sign-extended into the high one.
-__device__ __forceinline__ uint32_t uniform_u32(uint32_t v) { return uint32_t(__builtin_amdgcn_readfirstlane(v)); }
-__device__ __forceinline__ uint64_t uniform_u64(uint64_t v) {
-    const uint32_t lo = uniform_u32(uint32_t(v)), hi = uniform_u32(uint32_t(v >> 32));
-    return (uint64_t(hi) << 32) | uint64_t(lo);
-}
 
 // bytes [sh, sh+16) of the 32-byte string lo||hi, for sh = 4*W + b, 1 <= sh <= 15
 template <int W>
@@ -103,6 +83,50 @@ __device__ __forceinline__ u32x4 keep_bytes(u32x4 v, uint32_t keep) {
 }
 
 // ---------------------------------------------------------------- pack: tensors -> staging
+
+// Output word j (16 bytes, aligned) = the 16 bytes at su + 16 j (any alignment), for j < n_full, lane-strided.
+// U loads per lane in flight; with PIPE a second set is loaded while the first is stored.
+template <int U, bool PIPE>
+__device__ __forceinline__ void copy_words(const uint8_t *su, u32x4 *dst, uint32_t n_full, uint32_t lane) {
+    uint32_t i = lane;
+    if (!PIPE) {
+        for (; i + 64 * (U - 1) < n_full; i += 64 * U) {
+            u32x4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; u++) v[u] = ld16_unaligned(su + 16ull * (i + 64 * u));
+#pragma unroll
+            for (int u = 0; u < U; u++) st16(dst + i + 64 * u, v[u]);
+        }
+    } else if (i + 64 * (U - 1) < n_full) {
+        u32x4 a[U], b[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) a[u] = ld16_unaligned(su + 16ull * (i + 64 * u));
+        for (;;) {
+            uint32_t j = i + 64 * U;
+            if (!(j + 64 * (U - 1) < n_full)) {
+#pragma unroll
+                for (int u = 0; u < U; u++) st16(dst + i + 64 * u, a[u]);
+                i = j;
+                break;
+            }
+#pragma unroll
+            for (int u = 0; u < U; u++) b[u] = ld16_unaligned(su + 16ull * (j + 64 * u));
+#pragma unroll
+            for (int u = 0; u < U; u++) st16(dst + i + 64 * u, a[u]);
+            i = j + 64 * U;
+            if (!(i + 64 * (U - 1) < n_full)) {
+#pragma unroll
+                for (int u = 0; u < U; u++) st16(dst + j + 64 * u, b[u]);
+                break;
+            }
+#pragma unroll
+            for (int u = 0; u < U; u++) a[u] = ld16_unaligned(su + 16ull * (i + 64 * u));
+#pragma unroll
+            for (int u = 0; u < U; u++) st16(dst + j + 64 * u, b[u]);
+        }
+    }
+    for (; i < n_full; i += 64) st16(dst + i, ld16_unaligned(su + 16ull * i));
+}
 
 // The aligned source word that follows this lane's own: lane l takes `cur` of lane l+1, lane 63 takes
 // `nxt` of lane 0 (the first word of the next 64). A register exchange through the LDS crossbar
@@ -148,9 +172,13 @@ __device__ __forceinline__ void pack_shifted_group(const u32x4 *src_al, u32x4 *d
 // Copies the full 16-byte words of a tile whose source is misaligned by 4*W+b bytes.
 template <int W>
 __device__ __forceinline__ void pack_shifted(const u32x4 *src_al, u32x4 *dst, uint32_t n_full, uint32_t b, uint32_t lane) {
-    static_assert(kUnroll == 8, "the group cascade below is written for 8, 4, 2, 1");
     uint32_t g = 0;
+#if DSLLM_PACK_XCHG_MAX == 16
+    for (; g + 64 * 16 <= n_full; g += 64 * 16) pack_shifted_group<W, 16>(src_al, dst, g, b, lane);
+    if (g + 64 * 8 <= n_full) { pack_shifted_group<W, 8>(src_al, dst, g, b, lane); g += 64 * 8; }
+#else
     for (; g + 64 * 8 <= n_full; g += 64 * 8) pack_shifted_group<W, 8>(src_al, dst, g, b, lane);
+#endif
     if (g + 64 * 4 <= n_full) { pack_shifted_group<W, 4>(src_al, dst, g, b, lane); g += 64 * 4; }
     if (g + 64 * 2 <= n_full) { pack_shifted_group<W, 2>(src_al, dst, g, b, lane); g += 64 * 2; }
     if (g + 64 <= n_full) { pack_shifted_group<W, 1>(src_al, dst, g, b, lane); g += 64; }
@@ -184,6 +212,9 @@ __global__ __launch_bounds__(kBlock) void pack_kernel(const ckpt_tile *__restric
 
     if (sh == 0) {
         const u32x4 *s = reinterpret_cast<const u32x4 *>(src);
+#if DSLLM_PACK_PIPE
+        copy_words<kUnroll, true>(reinterpret_cast<const uint8_t *>(src), dst, n_full, lane);
+#else
         uint32_t i = lane;
         for (; i + 64 * (kUnroll - 1) < n_full; i += 64 * kUnroll) {
             u32x4 v[kUnroll];
@@ -193,23 +224,14 @@ __global__ __launch_bounds__(kBlock) void pack_kernel(const ckpt_tile *__restric
             for (int u = 0; u < kUnroll; u++) st16(dst + i + 64 * u, v[u]);
         }
         for (; i < n_full; i += 64) st16(dst + i, ld16(s + i));
+#endif
         if (tail && lane == 0) st16(dst + n_full, keep_bytes(ld16(s + n_full), tail));
     } else {
         const u32x4 *s = reinterpret_cast<const u32x4 *>(src - sh);
         const uint32_t b = sh & 3;
 #if DSLLM_PACK_MISALIGNED == 1
-        {   // output word j = source bytes [16 j, 16 j + 16): inside the tensor for every j < n_full
-            const uint8_t *su = reinterpret_cast<const uint8_t *>(src);
-            uint32_t i = lane;
-            for (; i + 64 * (kUnroll - 1) < n_full; i += 64 * kUnroll) {
-                u32x4 v[kUnroll];
-#pragma unroll
-                for (int u = 0; u < kUnroll; u++) v[u] = ld16_unaligned(su + 16ull * (i + 64 * u));
-#pragma unroll
-                for (int u = 0; u < kUnroll; u++) st16(dst + i + 64 * u, v[u]);
-            }
-            for (; i < n_full; i += 64) st16(dst + i, ld16_unaligned(su + 16ull * i));
-        }
+        // output word j = source bytes [16 j, 16 j + 16): inside the tensor for every j < n_full
+        copy_words<DSLLM_PACK_UNROLL_MIS, DSLLM_PACK_PIPE != 0>(reinterpret_cast<const uint8_t *>(src), dst, n_full, lane);
 #else
         switch (sh >> 2) {
             case 0: pack_shifted<0>(s, dst, n_full, b, lane); break;

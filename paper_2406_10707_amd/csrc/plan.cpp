@@ -55,10 +55,12 @@ int resolve_config(const ckpt_config *in, ResolvedConfig *out, std::string *err)
 
 static void put_le(uint8_t *p, uint64_t v, int n) { for (int i = 0; i < n; i++) p[i] = uint8_t(v >> (8 * i)); }
 
-int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cfg, Plan *out, std::string *err) {
+int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cfg, Plan *out, std::string *err, const DerivedPairs *pairs,
+               bool omit_derived) {
     if (!descs || n == 0) { *err = "no tensors"; return CKPT_EINVAL; }
     Plan p;
     p.cfg = cfg;
+    p.version = pairs && omit_derived ? 2 : 1;
     p.tensors.reserve(n);
     uint64_t table = 0;
     for (size_t k = 0; k < n; k++) {
@@ -92,9 +94,41 @@ int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cf
         p.payload_bytes += d.nbytes;
         p.tensors.push_back(std::move(t));
     }
+    if (pairs) {
+        // a derived tensor is a bf16 tensor on the device, its source a stored f32 tensor of the same shape on the device
+        std::vector<uint8_t> is_derived(n, 0), is_source(n, 0);
+        for (size_t i = 0; i < pairs->size(); i++) {
+            const uint64_t d = pairs->derived[i], s = pairs->source[i];
+            if (d >= n || s >= n || d == s) { *err = "derived pair " + std::to_string(i) + ": index out of range"; return CKPT_EINVAL; }
+            const TensorInfo &td = p.tensors[d], &ts = p.tensors[s];
+            if (td.dtype != CKPT_BF16 || ts.dtype != CKPT_F32 || td.shape != ts.shape) { *err = "derived pair " + std::to_string(i) + ": needs a bf16 tensor and an f32 source of the same shape"; return CKPT_EINVAL; }
+            if (td.host || ts.host) { *err = "derived pair " + std::to_string(i) + ": host-resident objects cannot take part"; return CKPT_EINVAL; }
+            if (is_derived[d] || is_derived[s] || is_source[d]) { *err = "derived pair " + std::to_string(i) + ": a tensor is derived twice, or a source is itself derived"; return CKPT_EINVAL; }
+            is_derived[d] = 1; is_source[s] = 1;
+            const uint64_t numel = ts.nbytes / 4;
+            for (uint64_t e = 0; e < numel; e += kPairTileElems) {
+                PairTile pt;
+                pt.f32_addr = ts.dev_addr + 4 * e;
+                pt.bf16_addr = td.dev_addr + 2 * e;
+                pt.count = uint32_t(numel - e < kPairTileElems ? numel - e : kPairTileElems);
+                pt.pad = 0; pt.reserved = 0;
+                p.pair_tiles.push_back(pt);
+            }
+            if (omit_derived) {
+                TensorInfo &t = p.tensors[d];
+                t.derived = true; t.source = uint32_t(s);
+                if (t.direct) { t.direct = false; p.n_direct--; p.direct_bytes -= t.nbytes; p.direct_data_bytes -= align_up(t.nbytes, kAlign); }
+                p.n_derived++; p.derived_bytes += t.nbytes;
+            }
+        }
+    }
+    if (p.version == 2) table += 5ull * n;     // enc u8 + ref u32 at the end of every entry
     p.header_bytes = align_up(kFixedHeader + table, kAlign);
     uint64_t off = p.header_bytes;
-    for (auto &t : p.tensors) { t.file_off = off; off += align_up(t.nbytes, kAlign); }
+    for (auto &t : p.tensors) {
+        if (t.derived) { t.file_off = 0; continue; }
+        t.file_off = off; off += align_up(t.nbytes, kAlign);
+    }
     p.data_bytes = off - p.header_bytes;
 
     // header image (iter left zero; patched per snapshot at byte 16)
@@ -102,7 +136,7 @@ int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cf
     uint8_t *h = p.header.data();
     static const uint8_t magic[8] = {'D', 'S', 'L', 'L', 'M', 'C', 'K', 1};
     memcpy(h, magic, 8);
-    put_le(h + 8, 1, 4);
+    put_le(h + 8, p.version, 4);
     put_le(h + 12, kAlign, 4);
     put_le(h + 24, n, 8);
     put_le(h + 32, p.header_bytes, 8);
@@ -117,6 +151,7 @@ int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cf
         for (int64_t s : t.shape) { put_le(w, uint64_t(s), 8); w += 8; }
         put_le(w, t.file_off, 8); w += 8;
         put_le(w, t.nbytes, 8); w += 8;
+        if (p.version == 2) { *w++ = t.derived ? 1 : 0; put_le(w, t.derived ? t.source : 0, 4); w += 4; }
     }
 
     // chunks and super-chunks partition the data region at fixed strides
@@ -129,6 +164,7 @@ int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cf
     p.sc_first_tile.assign(p.n_superchunks + 1, 0);
     uint64_t next_sc = 0;
     for (const auto &t : p.tensors) {
+        if (t.derived) continue;                               // described, not stored: no place in the data region
         uint64_t d0 = t.file_off - p.header_bytes;             // data-region offset of the tensor
         uint64_t dend = d0 + align_up(t.nbytes, kAlign);
         uint64_t pos = t.direct || t.host ? dend : d0;         // direct tensors and host objects have no tiles
@@ -179,6 +215,7 @@ int build_plan(const ckpt_tensor_desc *descs, size_t n, const ResolvedConfig &cf
     };
     for (size_t k = 0; k < p.tensors.size(); k++) {
         const TensorInfo &t = p.tensors[k];
+        if (t.derived) continue;
         const uint64_t d0 = t.file_off - p.header_bytes, dend = d0 + align_up(t.nbytes, kAlign);
         if (t.direct || t.host) {
             emit(d0, d0 + t.nbytes, t.host ? CKPT_SEG_HOST : CKPT_SEG_DIRECT, t.dev_addr, uint32_t(k));
@@ -201,7 +238,7 @@ bool verify_plan(const Plan &p, std::string *err) {
     size_t i = 0;
     for (size_t k = 0; k < p.tensors.size(); k++) {
         const TensorInfo &ti = p.tensors[k];
-        if (ti.direct || ti.host) continue;
+        if (ti.direct || ti.host || ti.derived) continue;
         const uint64_t d0 = ti.file_off - p.header_bytes, dend = d0 + align_up(ti.nbytes, kAlign);
         uint64_t expect = d0;
         while (expect < dend) {
@@ -235,7 +272,7 @@ bool verify_plan(const Plan &p, std::string *err) {
         uint64_t a = sg.data_off;
         const uint64_t b = sg.data_off + sg.nbytes;
         while (a < b) {
-            while (k < p.tensors.size() && a >= p.tensors[k].file_off - p.header_bytes + align_up(p.tensors[k].nbytes, kAlign)) k++;
+            while (k < p.tensors.size() && (p.tensors[k].derived || a >= p.tensors[k].file_off - p.header_bytes + align_up(p.tensors[k].nbytes, kAlign))) k++;
             if (k >= p.tensors.size()) { *err = "plan: segment beyond last tensor"; return false; }
             const TensorInfo &ti = p.tensors[k];
             const uint64_t d0 = ti.file_off - p.header_bytes, dend = d0 + align_up(ti.nbytes, kAlign);

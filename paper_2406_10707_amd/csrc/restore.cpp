@@ -4,7 +4,6 @@
 using namespace dsllm;
 
 static int restore_body(ckpt_ctx *c, int fd, const char *path, hipStream_t stream, uint64_t base, uint64_t *issued_out, uint64_t *iter_out) {
-    const Plan &p = c->plan;
     const uint64_t CH = c->cfg.dma_chunk_bytes, SC = c->cfg.pack_superchunk_bytes;
     const size_t nk = c->dma.size();
     struct stat st;
@@ -16,8 +15,14 @@ static int restore_body(ckpt_ctx *c, int fd, const char *path, hipStream_t strea
     uint8_t *hb = c->hdr_buf;
     if (!pread_all(fd, hb, kAlign, 0, &err)) return fail(CKPT_EIO, err);
     auto le = [&](const uint8_t *q, int n) { uint64_t v = 0; for (int i = 0; i < n; i++) v |= uint64_t(q[i]) << (8 * i); return v; };
-    if (memcmp(hb, p.header.data(), 8) != 0 || le(hb + 8, 4) != 1 || le(hb + 12, 4) != kAlign || le(hb + 56, 8) != 0)
+    const uint64_t version = le(hb + 8, 4);
+    if (memcmp(hb, c->plan.header.data(), 8) != 0 || (version != 1 && version != 2) || le(hb + 12, 4) != kAlign || le(hb + 56, 8) != 0)
         return fail(CKPT_EFORMAT, "bad magic, version or alignment");
+    // a version-2 file (derived tensors left out) is read with the registration's version-2 plan, which exists
+    // only if the same derivations were declared; its derived tensors are recomputed at the end
+    if (version == 2 && !c->have_rplan) return fail(CKPT_EMISMATCH, "the file leaves derived tensors out, this registration declares none");
+    const Plan &p = version == 2 ? c->rplan : c->plan;
+    const ckpt_tile *dev_tiles = version == 2 ? c->dev_rtiles : c->dev_tiles;
     const uint64_t f_hb = le(hb + 32, 8), f_db = le(hb + 40, 8), f_fb = le(hb + 48, 8), f_iter = le(hb + 16, 8);
     if (f_hb % kAlign || f_hb < kAlign || f_fb != f_hb + f_db || f_fb != uint64_t(st.st_size))
         return fail(CKPT_EFORMAT, "size fields inconsistent with the file (truncated?)");
@@ -87,7 +92,7 @@ static int restore_body(ckpt_ctx *c, int fd, const char *path, hipStream_t strea
             HIP_TRY(c, hipStreamWaitEvent(c->pack_stream, c->ev_stage_done[stage][k], 0));
         }
         const uint64_t t0 = p.sc_first_tile[sc], t1 = p.sc_first_tile[sc + 1];
-        HIP_TRY(c, launch_scatter(c->dev_tiles + t0, t1 - t0, stage_base, sc * SC, c->pack_stream));
+        HIP_TRY(c, launch_scatter(dev_tiles + t0, t1 - t0, stage_base, sc * SC, c->pack_stream));
         HIP_TRY(c, hipEventRecord(c->ev_packed[sc], c->pack_stream));
     }
     HIP_TRY(c, hipStreamWaitEvent(stream, c->ev_packed[p.n_superchunks - 1], 0));
@@ -96,6 +101,15 @@ static int restore_body(ckpt_ctx *c, int fd, const char *path, hipStream_t strea
             HIP_TRY(c, hipEventRecord(c->ev_job_tail[k], c->dma[k]));
             HIP_TRY(c, hipStreamWaitEvent(stream, c->ev_job_tail[k], 0));
         }
+    if (version == 2) {
+        // every stored tensor is in place once the pack stream has run its last scatter kernel (and the copy streams
+        // their direct copies): the derived tensors are then recomputed from their sources
+        if (p.n_direct)
+            for (size_t k = 0; k < nk; k++) HIP_TRY(c, hipStreamWaitEvent(c->pack_stream, c->ev_job_tail[k], 0));
+        HIP_TRY(c, launch_derive_pairs(c->dev_pairs, c->plan.pair_tiles.size(), c->pack_stream));
+        HIP_TRY(c, hipEventRecord(c->ev_derived, c->pack_stream));
+        HIP_TRY(c, hipStreamWaitEvent(stream, c->ev_derived, 0));
+    }
     if (iter_out) *iter_out = f_iter;
     return CKPT_OK;
 }
@@ -114,7 +128,7 @@ static bool whole_checkpoint(const std::string &path, uint64_t iter) {
     if (!ok) return false;
     auto le = [&](int off, int n) { uint64_t v = 0; for (int i = 0; i < n; i++) v |= uint64_t(h[off + i]) << (8 * i); return v; };
     static const uint8_t magic[8] = {'D', 'S', 'L', 'L', 'M', 'C', 'K', 1};
-    if (memcmp(h, magic, 8) != 0 || le(8, 4) != 1 || le(12, 4) != kAlign || le(56, 8) != 0) return false;
+    if (memcmp(h, magic, 8) != 0 || (le(8, 4) != 1 && le(8, 4) != 2) || le(12, 4) != kAlign || le(56, 8) != 0) return false;
     const uint64_t hb = le(32, 8), db = le(40, 8), fb = le(48, 8);
     return le(16, 8) == iter && hb >= kAlign && hb % kAlign == 0 && db % kAlign == 0 && fb == hb + db && fb == uint64_t(st.st_size);
 }
@@ -135,7 +149,8 @@ int ckpt_describe_file(const char *path, char *buf, size_t cap, size_t *needed_o
     auto le = [](const uint8_t *q, int n) { uint64_t v = 0; for (int i = 0; i < n; i++) v |= uint64_t(q[i]) << (8 * i); return v; };
     static const uint8_t magic[8] = {'D', 'S', 'L', 'L', 'M', 'C', 'K', 1};
     const uint64_t iter = le(fixed + 16, 8), n = le(fixed + 24, 8), hb = le(fixed + 32, 8), db = le(fixed + 40, 8), fb = le(fixed + 48, 8);
-    if (memcmp(fixed, magic, 8) != 0 || le(fixed + 8, 4) != 1 || le(fixed + 12, 4) != kAlign || le(fixed + 56, 8) != 0 || hb < kAlign ||
+    const uint64_t version = le(fixed + 8, 4);
+    if (memcmp(fixed, magic, 8) != 0 || (version != 1 && version != 2) || le(fixed + 12, 4) != kAlign || le(fixed + 56, 8) != 0 || hb < kAlign ||
         hb % kAlign || db % kAlign || fb != hb + db || fb != uint64_t(st.st_size) || hb > (1ull << 32)) {
         close(fd);
         return fail(CKPT_EFORMAT, std::string(path) + ": not a whole checkpoint file");
@@ -157,14 +172,17 @@ int ckpt_describe_file(const char *path, char *buf, size_t cap, size_t *needed_o
         pos += len;
         const unsigned dtype = h[pos], ndim = h[pos + 1];
         pos += 2;
-        if (dtype < 1 || dtype > 6 || ndim > 8 || pos + 8ull * ndim + 16 > hb) return fail(CKPT_EFORMAT, "bad tensor table entry");
+        if (dtype < 1 || dtype > 6 || ndim > 8 || pos + 8ull * ndim + 16 + (version == 2 ? 5 : 0) > hb) return fail(CKPT_EFORMAT, "bad tensor table entry");
         text += std::string("\t") + dtype_name[dtype] + "\t";
         if (ndim == 0) text += "-";
         for (unsigned i = 0; i < ndim; i++) { text += (i ? "x" : "") + std::to_string(le(&h[pos], 8)); pos += 8; }
         const uint64_t off = le(&h[pos], 8), nb = le(&h[pos + 8], 8);
         pos += 16;
-        if (off < hb || off % kAlign || off + nb > fb) return fail(CKPT_EFORMAT, "tensor lies outside the data region");
-        text += "\t" + std::to_string(off) + "\t" + std::to_string(nb) + "\n";
+        uint64_t enc = 0, ref = 0;
+        if (version == 2) { enc = h[pos]; ref = le(&h[pos + 1], 4); pos += 5; }
+        if (enc > 1 || (enc == 1 && (off != 0 || ref >= n))) return fail(CKPT_EFORMAT, "bad derived-tensor entry");
+        if (enc == 0 && (off < hb || off % kAlign || off + nb > fb)) return fail(CKPT_EFORMAT, "tensor lies outside the data region");
+        text += "\t" + std::to_string(off) + "\t" + std::to_string(nb) + (enc ? "\tbf16 rounding of tensor " + std::to_string(ref) : "") + "\n";
     }
     if (needed_out) *needed_out = text.size() + 1;
     if (!buf || cap < text.size() + 1) return fail(CKPT_EINVAL, "buffer smaller than the description");

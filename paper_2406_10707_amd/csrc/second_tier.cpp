@@ -18,7 +18,7 @@ void dsllm::tier2_offer_locked(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
 // turn, from the kept mapping when there is one (tmpfs pages: a memory read), else with pread;
 // fsync, rename, then older second-tier files beyond tier2_keep are removed.
 static void tier2_copy(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
-    const uint64_t total = c->plan.file_bytes(), blk = 8ull << 20;
+    const uint64_t total = sp->plan->file_bytes(), blk = 8ull << 20;
     const uint64_t n_blk = (total + blk - 1) / blk;
     auto t0 = Clock::now();
     const uint8_t *src_map = nullptr;
@@ -174,7 +174,7 @@ int ckpt_enable_second_tier(ckpt_ctx *c, const char *dir, int32_t n_threads, int
     // write path. Writing a whole file of zeros takes seconds to minutes: not under the context's mutex.
     FileSlot fs;
     std::string err;
-    const bool spare_ok = !want_spare || preallocate_file(spare, c->plan.file_bytes(), std::min(c->cfg.n_io_threads, 8),
+    const bool spare_ok = !want_spare || preallocate_file(spare, expected_file_bytes(c), std::min(c->cfg.n_io_threads, 8),
                                                           c->cfg.io_mode == CKPT_IO_MMAP, c->cfg.o_direct, &fs, &err);
     std::lock_guard<std::mutex> lk(c->mu);
     c->tier2_enabling = false;

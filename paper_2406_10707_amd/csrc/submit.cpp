@@ -6,7 +6,6 @@ using namespace dsllm;
 
 static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
     Snap *s = sp.get();
-    const Plan &p = c->plan;
     const uint64_t CH = c->cfg.dma_chunk_bytes, SC = c->cfg.pack_superchunk_bytes;
     const size_t nk = c->dma.size();
     auto hip_fail = [&](const char *what, hipError_t e) { c->fail_snapshot(s, CKPT_EHIP, std::string(what) + ": " + hipGetErrorString(e)); };
@@ -31,15 +30,49 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
         }
     }
 
+    // everything below comes after the boundary on the device timeline
+    if ((e = hipStreamWaitEvent(c->pack_stream, s->ev_boundary, 0)) != hipSuccess) hip_fail("wait boundary", e);
+
+    // Data reduction: with derived tensors declared, the captured state is checked on the device first (every bf16
+    // copy against the rounding of its f32 source). The verdict decides which of the registration's two plans this
+    // snapshot is written with; this thread waits for it (some milliseconds after the boundary), the caller does not.
+    const Plan *chosen = &c->plan;
+    const ckpt_tile *chosen_tiles = c->dev_tiles;
+    if (c->have_rplan) {
+        bool launched = true;
+        if ((e = hipEventRecord(c->ev_verify_start, c->pack_stream)) != hipSuccess) { hip_fail("record", e); launched = false; }
+        if (launched && (e = launch_verify_pairs(c->dev_pairs, c->plan.pair_tiles.size(), c->dev_flag, c->pack_stream)) != hipSuccess) { hip_fail("verify launch", e); launched = false; }
+        if (launched && (e = hipMemcpyAsync(c->host_flag, c->dev_flag, sizeof(uint32_t), hipMemcpyDeviceToHost, c->pack_stream)) != hipSuccess) { hip_fail("verdict copy", e); launched = false; }
+        if (launched && (e = hipEventRecord(c->ev_verify_done, c->pack_stream)) != hipSuccess) { hip_fail("record", e); launched = false; }
+        if (launched && (e = hipEventSynchronize(c->ev_verify_done)) != hipSuccess) { hip_fail("verdict sync", e); launched = false; }
+        if (launched && *c->host_flag == 0) { chosen = &c->rplan; chosen_tiles = c->dev_rtiles; }   // anything else: the full file
+        float vms = 0;
+        if (launched && hipEventElapsedTime(&vms, c->ev_verify_start, c->ev_verify_done) == hipSuccess) s->verify_ms = vms;
+    }
+    const Plan &p = *chosen;
+    s->chunks_left = p.n_chunks;
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        s->plan = chosen;
+        s->dev_tiles = chosen_tiles;
+    }
+
     // file and header
     const bool use_mmap = c->cfg.io_mode == CKPT_IO_MMAP;
     memcpy(c->hdr_buf, p.header.data(), p.header_bytes);
     for (int i = 0; i < 8; i++) c->hdr_buf[16 + i] = uint8_t(s->iter >> (8 * i));
     FileSlot reuse;
+    std::vector<FileSlot> wrong_size;
     {
         std::lock_guard<std::mutex> lk(c->mu);
-        if (!c->spares.empty()) { reuse = c->spares.back(); c->spares.pop_back(); }
+        while (!c->spares.empty() && reuse.fd < 0) {
+            FileSlot f = c->spares.back();
+            c->spares.pop_back();
+            if (f.bytes == p.file_bytes()) reuse = f; else wrong_size.push_back(f);
+        }
     }
+    // a spare of another size (the previous snapshot had the other format version) cannot be overwritten in place
+    for (auto &f : wrong_size) { f.close_all(); unlink(f.path.c_str()); }
     std::string ferr;
     if (reuse.fd >= 0) {
         // a retired file of this registration: same size, pages allocated, still open (and mapped);
@@ -74,7 +107,6 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
         s->map = nullptr; s->fd = -1;
     }
 
-    if ((e = hipStreamWaitEvent(c->pack_stream, s->ev_boundary, 0)) != hipSuccess) hip_fail("wait boundary", e);
     if (p.n_direct)   // these copies read the tensors themselves
         for (size_t k = 0; k < nk; k++)
             if ((e = hipStreamWaitEvent(c->dma[k], s->ev_boundary, 0)) != hipSuccess) hip_fail("wait boundary", e);
@@ -94,7 +126,7 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
                 if ((e = hipStreamWaitEvent(c->pack_stream, c->ev_stage_done[(sc - ahead) % c->n_stage][k], 0)) != hipSuccess) hip_fail("wait stage", e);
         if ((e = hipEventRecord(c->ev_pack_start[sc], c->pack_stream)) != hipSuccess) hip_fail("record", e);
         const uint64_t t0 = p.sc_first_tile[sc], t1 = p.sc_first_tile[sc + 1];
-        if ((e = launch_pack(c->dev_tiles + t0, t1 - t0, c->staging + stage * SC, sc * SC, c->pack_stream)) != hipSuccess) hip_fail("pack launch", e);
+        if ((e = launch_pack(s->dev_tiles + t0, t1 - t0, c->staging + stage * SC, sc * SC, c->pack_stream)) != hipSuccess) hip_fail("pack launch", e);
         if ((e = hipEventRecord(c->ev_packed[sc], c->pack_stream)) != hipSuccess) hip_fail("record", e);
         if (sc + 1 == p.n_superchunks) {   // every read of the tensors is now in the pack stream
             std::lock_guard<std::mutex> lk(c->mu);

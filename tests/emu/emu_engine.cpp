@@ -315,6 +315,173 @@ static int failed_chunk_scenario(const std::string &dir, int keep_last) {
     return 0;
 }
 
+// ---- data reduction: bf16 copies declared as roundings of f32 masters. The update keeps them so (version-2
+// files, the copies left out) except at one iteration, where one element is off (that snapshot must be the full
+// version-1 file). Every file against an image built here; restore of both versions into poisoned memory.
+static uint16_t rne_bits(uint32_t u) { return (u & 0x7FFFFFFFu) > 0x7F800000u ? uint16_t((u >> 16) | 0x40u) : uint16_t((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16); }
+
+static int derived_scenario(const std::string &dir, int policy, int keep_last, int io_mode, uint64_t direct_min) {
+    std::string what = "derived tensors, policy " + std::to_string(policy) + " keep_last " + std::to_string(keep_last) + " direct_min " + std::to_string(direct_min);
+    const std::string title = what;
+    const int n_params = 9;
+    struct Param { uint8_t *p_base, *m_base, *x_base; uint64_t p_lead, m_lead, numel; std::string pn, mn, xn; int64_t shape; int64_t xshape; };
+    std::vector<Param> ps(n_params);
+    for (int k = 0; k < n_params; k++) {
+        Param &q = ps[k];
+        q.numel = k == 0 ? 3 : (k == 1 ? 8192 : (k == 2 ? 8193 : 1 + rnd() % 40000));
+        q.p_lead = k % 2 ? 2 * (rnd() % 8) : 0;          // element-aligned, some not 8-byte aligned: the element-wise path
+        q.m_lead = k % 3 == 1 ? 4 * (rnd() % 4) : 0;
+        q.p_base = static_cast<uint8_t *>(aligned_alloc(16, (q.p_lead + 2 * q.numel + 15) / 16 * 16));
+        q.m_base = static_cast<uint8_t *>(aligned_alloc(16, (q.m_lead + 4 * q.numel + 15) / 16 * 16));
+        q.x_base = static_cast<uint8_t *>(aligned_alloc(16, (4 * q.numel + 15) / 16 * 16));      // a third tensor per parameter, never derived
+        q.pn = "w" + std::to_string(k) + ".p_bf16"; q.mn = "w" + std::to_string(k) + ".master"; q.xn = "w" + std::to_string(k) + ".m";
+        q.shape = int64_t(q.numel); q.xshape = int64_t(q.numel);
+    }
+    std::vector<ckpt_tensor_desc> descs;
+    std::vector<uint32_t> derived, source;
+    for (auto &q : ps) {
+        ckpt_tensor_desc d{};
+        derived.push_back(uint32_t(descs.size())); source.push_back(uint32_t(descs.size() + 1));
+        d.name = q.pn.c_str(); d.dtype = CKPT_BF16; d.ndim = 1; d.shape = &q.shape; d.dev_ptr = q.p_base + q.p_lead; d.nbytes = 2 * q.numel; descs.push_back(d);
+        d.name = q.mn.c_str(); d.dtype = CKPT_F32; d.dev_ptr = q.m_base + q.m_lead; d.nbytes = 4 * q.numel; descs.push_back(d);
+        d.name = q.xn.c_str(); d.dtype = CKPT_F32; d.shape = &q.xshape; d.dev_ptr = q.x_base; d.nbytes = 4 * q.numel; descs.push_back(d);
+    }
+    ckpt_config cfg{};
+    cfg.out_dir = dir.c_str();
+    cfg.host_ring_bytes = 256 << 10;
+    cfg.dma_chunk_bytes = 64 << 10;
+    cfg.pack_superchunk_bytes = 256 << 10;
+    cfg.n_dma_streams = 2;
+    cfg.n_io_threads = 3;
+    cfg.window_policy = policy;
+    cfg.io_mode = io_mode;
+    cfg.keep_last = keep_last;
+    cfg.prealloc_files = keep_last ? 1 : 0;
+    cfg.direct_min_bytes = direct_min;
+    ckpt_ctx *ctx = nullptr;
+    REQUIRE(ckpt_init(&cfg, &ctx) == CKPT_OK);
+    { uint32_t bad_d = 1, bad_s = 0; REQUIRE(ckpt_declare_derived(ctx, &bad_d, &bad_s, 1) == CKPT_OK); }      // f32 "derived" from bf16: caught at registration
+    REQUIRE(ckpt_register_tensors(ctx, descs.data(), descs.size()) == CKPT_EINVAL);
+    REQUIRE(ckpt_declare_derived(ctx, derived.data(), source.data(), derived.size()) == CKPT_OK);
+    REQUIRE(ckpt_register_tensors(ctx, descs.data(), descs.size()) == CKPT_OK);
+    REQUIRE(ckpt_declare_derived(ctx, derived.data(), source.data(), derived.size()) == CKPT_ESTATE);
+    ckpt_plan *plan1 = nullptr, *plan2 = nullptr;
+    REQUIRE(ckpt_plan_create(descs.data(), descs.size(), &cfg, &plan1) == CKPT_OK);
+    REQUIRE(ckpt_plan_create_derived(descs.data(), descs.size(), &cfg, derived.data(), source.data(), derived.size(), &plan2) == CKPT_OK);
+    ckpt_layout lay1, lay2, layc;
+    REQUIRE(ckpt_plan_layout(plan1, &lay1) == CKPT_OK && ckpt_plan_layout(plan2, &lay2) == CKPT_OK && ckpt_get_layout(ctx, &layc) == CKPT_OK);
+    REQUIRE(lay1.version == 1 && lay2.version == 2 && lay2.n_derived_tensors == uint64_t(n_params) && lay2.data_bytes < lay1.data_bytes);
+    REQUIRE(layc.data_bytes == lay1.data_bytes && layc.reduced_data_bytes == lay2.data_bytes && layc.reduced_header_bytes == lay2.header_bytes);
+    std::vector<uint64_t> offs1(descs.size()), offs2(descs.size());
+    REQUIRE(ckpt_plan_offsets(plan1, offs1.data(), offs1.size()) == CKPT_OK && ckpt_plan_offsets(plan2, offs2.data(), offs2.size()) == CKPT_OK);
+
+    hipStream_t compute;
+    hipStreamCreateWithFlags(&compute, hipStreamNonBlocking);
+    const int iters = 6, broken_iter = 3;
+    std::vector<std::vector<uint8_t>> expect(iters + 1);
+    std::vector<int> expect_version(iters + 1, 2);
+    expect_version[broken_iter] = 1;
+    for (int it = 1; it <= iters; it++) {
+        REQUIRE(ckpt_wait_immutable_window_end(ctx, compute, 0) == CKPT_OK);
+        // the update: new master bits (all kinds of patterns, NaNs and ties among them), the bf16 copy re-rounded from them
+        emu_submit(compute, [&ps, it, broken_iter] {
+            for (size_t k = 0; k < ps.size(); k++) {
+                Param &q = ps[k];
+                for (uint64_t e = 0; e < q.numel; e++) {
+                    uint32_t u = uint32_t((e * 2654435761ull + k * 40503ull + uint64_t(it) * 0x9E3779B9ull) ^ (e << 17));
+                    if (e % 97 == 5) u = 0x7F800001u + uint32_t(e);            // NaNs
+                    if (e % 89 == 7) u = (u & 0xFFFF0000u) | 0x8000u;          // ties
+                    memcpy(q.m_base + q.m_lead + 4 * e, &u, 4);
+                    uint16_t b = rne_bits(u);
+                    memcpy(q.p_base + q.p_lead + 2 * e, &b, 2);
+                    uint32_t x = u * 31u + uint32_t(it);
+                    memcpy(q.x_base + 4 * e, &x, 4);
+                }
+            }
+            if (it == broken_iter) { Param &q = ps[4]; q.p_base[q.p_lead + 2 * (q.numel - 1)] ^= 1; }   // one bit of one element: the pair no longer holds
+        });
+        std::vector<uint8_t> *img = &expect[it];
+        const bool v2 = expect_version[it] == 2;
+        img->assign(v2 ? lay2.file_bytes : lay1.file_bytes, 0);
+        emu_submit(compute, [&, img, it, v2] {
+            ckpt_plan_header(v2 ? plan2 : plan1, uint64_t(it), img->data(), v2 ? lay2.header_bytes : lay1.header_bytes);
+            const std::vector<uint64_t> &offs = v2 ? offs2 : offs1;
+            for (size_t j = 0; j < descs.size(); j++) {
+                if (v2 && j % 3 == 0) continue;      // the bf16 copies are described, not stored
+                memcpy(img->data() + offs[j], descs[j].dev_ptr, descs[j].nbytes);
+            }
+        });
+        REQUIRE(ckpt_snapshot_async(ctx, uint64_t(it), compute) == CKPT_OK);
+    }
+    REQUIRE(ckpt_flush(ctx, CKPT_ITER_ALL) == CKPT_OK);
+    hipStreamSynchronize(compute);
+    char name[4096];
+    for (int it = 1; it <= iters; it++) {
+        ckpt_stats st;
+        REQUIRE(ckpt_get_stats(ctx, uint64_t(it), &st) == CKPT_OK && st.committed == 1);
+        what = "iteration " + std::to_string(it);
+        REQUIRE(st.format_version == expect_version[it]);
+        REQUIRE(st.data_bytes == (expect_version[it] == 2 ? lay2.data_bytes : lay1.data_bytes));
+        REQUIRE(ckpt_file_name(ctx, uint64_t(it), name, sizeof name) == CKPT_OK);
+        std::vector<uint8_t> got = read_file(name);
+        const bool should_exist = keep_last == 0 || it > iters - keep_last;
+        if (!should_exist) { REQUIRE(got.empty()); continue; }
+        REQUIRE(got == expect[it]);
+    }
+    // restore the newest (version 2) file into poisoned memory: stored tensors come back, derived ones are recomputed
+    auto poison = [&] { for (auto &q : ps) { memset(q.p_base, 0xA5, (q.p_lead + 2 * q.numel + 15) / 16 * 16); memset(q.m_base, 0xA5, (q.m_lead + 4 * q.numel + 15) / 16 * 16); memset(q.x_base, 0xA5, (4 * q.numel + 15) / 16 * 16); } };
+    auto check_restored = [&](int it) -> bool {
+        const bool v2 = expect_version[it] == 2;
+        const std::vector<uint64_t> &offs = v2 ? offs2 : offs1;
+        for (size_t k = 0; k < ps.size(); k++) {
+            Param &q = ps[k];
+            if (memcmp(q.m_base + q.m_lead, expect[it].data() + offs[3 * k + 1], 4 * q.numel) != 0) return false;
+            if (memcmp(q.x_base, expect[it].data() + offs[3 * k + 2], 4 * q.numel) != 0) return false;
+            for (uint64_t e = 0; e < q.numel; e++) {
+                uint32_t u; uint16_t b;
+                memcpy(&u, q.m_base + q.m_lead + 4 * e, 4); memcpy(&b, q.p_base + q.p_lead + 2 * e, 2);
+                uint16_t want = rne_bits(u);
+                if (!v2) memcpy(&want, expect[it].data() + offs[3 * k] + 2 * e, 2);
+                if (b != want) return false;
+            }
+            for (uint64_t i = 0; i < q.p_lead; i++) if (q.p_base[i] != 0xA5) return false;                                   // bytes around the tensors untouched
+            for (uint64_t i = q.p_lead + 2 * q.numel; i < (q.p_lead + 2 * q.numel + 15) / 16 * 16; i++) if (q.p_base[i] != 0xA5) return false;
+            for (uint64_t i = 0; i < q.m_lead; i++) if (q.m_base[i] != 0xA5) return false;
+        }
+        return true;
+    };
+    uint64_t got_iter = 0;
+    what = "restore of a version-2 file";
+    poison();
+    REQUIRE(ckpt_file_name(ctx, uint64_t(iters), name, sizeof name) == CKPT_OK);
+    REQUIRE(ckpt_restore(ctx, name, compute, &got_iter) == CKPT_OK && got_iter == uint64_t(iters));
+    hipStreamSynchronize(compute);
+    REQUIRE(check_restored(iters));
+    if (keep_last == 0) {
+        what = "restore of the version-1 file";
+        poison();
+        REQUIRE(ckpt_file_name(ctx, uint64_t(broken_iter), name, sizeof name) == CKPT_OK);
+        REQUIRE(ckpt_restore(ctx, name, compute, &got_iter) == CKPT_OK && got_iter == uint64_t(broken_iter));
+        hipStreamSynchronize(compute);
+        REQUIRE(check_restored(broken_iter));
+    }
+    REQUIRE(ckpt_destroy(ctx) == CKPT_OK);
+    // a registration that declares nothing refuses the version-2 file
+    if (keep_last == 0) {
+        what = "version-2 file, nothing declared";
+        REQUIRE(ckpt_init(&cfg, &ctx) == CKPT_OK);
+        REQUIRE(ckpt_register_tensors(ctx, descs.data(), descs.size()) == CKPT_OK);
+        REQUIRE(ckpt_file_name(ctx, uint64_t(iters), name, sizeof name) == CKPT_OK);
+        REQUIRE(ckpt_restore(ctx, name, compute, nullptr) == CKPT_EMISMATCH);
+        REQUIRE(ckpt_destroy(ctx) == CKPT_OK);
+    }
+    ckpt_plan_destroy(plan1); ckpt_plan_destroy(plan2);
+    hipStreamDestroy(compute);
+    for (auto &q : ps) { free(q.p_base); free(q.m_base); free(q.x_base); }
+    printf("ok %s: version-2 files %llu data bytes instead of %llu\n", title.c_str(), (unsigned long long)lay2.data_bytes, (unsigned long long)lay1.data_bytes);
+    return 0;
+}
+
 // ---- crash consistency: the process ends itself (SIGKILL) at its kill_at-th file write, somewhere in the
 // middle of a flush. Tensor bytes are a closed form of (tensor, byte, iteration), so the parent can tell what
 // every file that carries a final name must hold. variant 0: plain files; 1: retention with recycled files;
@@ -388,6 +555,17 @@ int main(int argc, char **argv) {
         return 0;
     }
     if (std::string(argv[1]) == "--crash" && argc >= 5) return crash_child(argv[2], atoi(argv[3]), atol(argv[4]));
+    if (std::string(argv[1]) == "--derived" && argc >= 3) {
+        rng_state = argc > 3 ? strtoull(argv[3], 0, 10) : 5;
+        const std::string root = argv[2];
+        int n = 0;
+        auto sub = [&] { std::string d = root + "/d" + std::to_string(n++); mkdir(d.c_str(), 0755); return d; };
+        if (derived_scenario(sub(), CKPT_WINDOW_D2H, 0, CKPT_IO_PWRITE, 0)) return 1;
+        if (derived_scenario(sub(), CKPT_WINDOW_D2H, 1, CKPT_IO_MMAP, 0)) return 1;      // recycled spares change size when the version changes
+        if (derived_scenario(sub(), CKPT_WINDOW_PACK, 2, CKPT_IO_MMAP, 0)) return 1;
+        if (derived_scenario(sub(), CKPT_WINDOW_D2H, 0, CKPT_IO_PWRITE, 30000)) return 1;  // hybrid: large tensors by direct copy
+        return 0;
+    }
     rng_state = argc > 2 ? strtoull(argv[2], 0, 10) : 1;
     std::string root = argv[1];
     int n = 0;

@@ -40,7 +40,7 @@ def _build_emu_engine(tmp_path_factory, sanitizer):
     cmd = [CLANG, "-x", "c++", "-std=c++17", "-O1", "-g", "-fsanitize=" + sanitizer, "-fno-omit-frame-pointer", "-pthread",
            "-I", os.path.join(ROOT, "tests", "emu"), "-o", exe, os.path.join(ROOT, "tests", "emu", "emu_engine.cpp"),
            *[os.path.join(csrc, f) for f in ("engine.cpp", "submit.cpp", "io_threads.cpp", "restore.cpp", "second_tier.cpp", "plan.cpp",
-                                             "pack_kernels.hip", "pack_image.hip")]]
+                                             "pack_kernels.hip", "pack_image.hip", "derive_kernels.hip")]]
     subprocess.run(cmd, check=True, cwd=os.path.join(ROOT, "tests", "emu"))
     return exe
 
@@ -146,3 +146,17 @@ def test_kill_during_flush_leaves_no_torn_named_file(emu_engine, variant, tmp_pa
             with pytest.raises(B.CkptError):
                 B.find_latest(str(d))
     assert died == len(kills) and leftovers > 0 and named > 0
+
+
+@pytest.mark.parametrize("which", ["thread", "address"])
+def test_derived_tensors_through_the_engine(which, emu_engine, emu_engine_asan, tmp_path):
+    """Data reduction through the whole engine on the CPU (ThreadSanitizer, then AddressSanitizer): the
+    derivation check and both kernels run from the library's source; snapshots whose pairs hold are version-2
+    files, the one with a single wrong bit is a version-1 file, both restore, recycled spares of the wrong size
+    are replaced, and a registration without the declaration refuses the version-2 file."""
+    exe = emu_engine if which == "thread" else emu_engine_asan
+    r = subprocess.run([exe, "--derived", str(tmp_path)], capture_output=True, text=True, timeout=600)
+    out = r.stdout + r.stderr
+    assert r.returncode == 0 and "FAILED" not in out, out[-6000:]
+    assert not any(w in out for w in ("ThreadSanitizer", "AddressSanitizer", "LeakSanitizer", "runtime error")), out[-6000:]
+    assert out.count("ok derived tensors") == 4

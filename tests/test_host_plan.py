@@ -335,3 +335,46 @@ def test_describe_file_agrees_with_the_independent_reader(tmp_path):
     with pytest.raises(B.CkptError) as e:
         B.describe_file(os.path.join(tmp_path, "missing.dsl"))
     assert e.value.code == B.CKPT_EIO
+
+
+@pytest.mark.parametrize("tiny", [True, False])
+@pytest.mark.parametrize("config", [1, 2, 3, 4])
+def test_version_2_plan_matches_the_oracle(config, tiny):
+    """The planner's version-2 header, offsets and sizes (derived tensors described, not stored) against the
+    oracle's: byte-identical header on the tiny shards (taken from the oracle's whole version-2 file), sizes at
+    full size; the tile table covers exactly the stored tensors."""
+    spec = shards.make_shard(config, tiny=tiny)
+    descs, span = _fake_descs(spec)
+    pairs = [(k, k + 1) for k, t in enumerate(spec.tensors) if t.role == "p_bf16"]
+    plan = B.Plan(descs, derived=pairs)
+    lay = plan.layout()
+    ots = [(t.name, t.dtype, t.shape, None) for t in spec.tensors]
+    hb, db = oracle.v2_sizes(ots, pairs)
+    assert (lay["version"], lay["header_bytes"], lay["data_bytes"]) == (2, hb, db)
+    assert lay["n_derived_tensors"] == len(pairs) and lay["derived_bytes"] == sum(spec.tensors[d].nbytes for d, _ in pairs)
+    assert lay["payload_bytes"] == spec.payload_bytes
+    if tiny:
+        host = [shards.host_values(spec, k) for k in range(len(spec.tensors))]
+        blob, version = oracle.serialize_bytes_v2([(t.name, t.dtype, t.shape, h) for t, h in zip(spec.tensors, host)], 41, pairs)
+        assert version == 2 and plan.header(41) == blob[:hb]
+        # the tile table over a fake address space reproduces the oracle's version-2 data region
+        mem = np.full(span + 64, 0xEE, dtype=np.uint8)
+        for (name, dtype, shape, p, nb), v in zip(descs, host):
+            mem[p - FAKE_BASE:p - FAKE_BASE + nb] = v
+        out = np.full(db, 0xCC, dtype=np.uint8)
+        pos = 0
+        for t in plan.tiles():
+            assert t.dst_off == pos
+            s = t.src - FAKE_BASE
+            out[pos:pos + t.copy_bytes] = mem[s:s + t.copy_bytes]
+            out[pos + t.copy_bytes:pos + t.total_bytes] = 0
+            pos += t.total_bytes
+        assert pos == db and out.tobytes() == blob[hb:]
+        offs = plan.offsets()
+        assert all(offs[d] == 0 for d, _ in pairs) and offs[1] == hb
+    plan.close()
+    # malformed declarations are refused by the planner
+    for wrong in ([(1, 0)], [(0, 1), (0, 1)], [(0, len(descs) + 5)]):
+        with pytest.raises(B.CkptError) as e:
+            B.Plan(descs, derived=wrong)
+        assert e.value.code == B.CKPT_EINVAL
