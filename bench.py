@@ -79,6 +79,14 @@ def parse_args():
     ap.add_argument("--idle-library-steps", type=int, default=6,
                     help="steps run with the library's calls in the loop but no snapshot pending or requested, long after the last "
                          "copy (a third reference for the stall: what the calls themselves cost; 0: off)")
+    ap.add_argument("--hbm-victim-gib", type=float, default=0.0,
+                    help="G > 0: a heavier victim. After every 16 GEMM launches of the forward/backward stand-in one streaming "
+                         "copy kernel moves G GiB through HBM (the memory-bound phases of a real step: normalisation, element-wise "
+                         "work, attention softmax), so the snapshot's pack kernel and copies meet HBM traffic as well as MFMA work")
+    ap.add_argument("--torch-runtime", type=int, default=1,
+                    help="1: before anything else touches the GPU, a child process measures workload 1 with PyTorch owning device "
+                         "memory, stream and HIP runtime (paper_2406_10707_amd/torch_runtime_probe.py); its figures go into the "
+                         "torch_runtime block of the JSON line. 0: skip")
     ap.add_argument("--pack-only", type=int, default=0,
                     help="N > 0: no snapshot engine, no proxy; N calls of ckpt_pack_image over the whole workload (one launch of the pack "
                          "kernel each) after one 4 GiB launch of the plain copy kernel. For rocprofv3 runs of the pack kernel alone: "
@@ -92,6 +100,10 @@ def measure_link_peak(B, harness, s, nbytes=1 << 30, reps=10):
     d = harness.DevBuf(nbytes)
     h = B.proxy_host_alloc_pinned(nbytes)
     best = {"d2h": 0.0, "h2d": 0.0}
+    t_end = time.perf_counter() + 0.5          # half a second of copies first: a card fresh out of idle has been seen at half the rate
+    while time.perf_counter() < t_end:
+        B.proxy_copy_pinned_async(h, d.ptr, nbytes, True, s.handle)
+        s.synchronize()
     for name, to_host in (("d2h", True), ("h2d", False)):
         for _ in range(reps):
             e0, e1 = harness.Event(), harness.Event()
@@ -170,6 +182,7 @@ def main():
     from paper_2406_10707_amd import binding as B
     from paper_2406_10707_amd import harness, shards
 
+    args.torch_runtime_result = torch_runtime_probe() if args.torch_runtime and not args.pack_only else None
     spec = shards.make_shard(args.config)
     every = args.ckpt_every or spec.ckpt_every
     compute_ms = args.compute_ms or spec.compute_ms
@@ -179,6 +192,22 @@ def main():
         run(args, B, harness, spec, every, compute_ms, out_dir)
     finally:
         shutil.rmtree(out_dir, ignore_errors=True)
+
+
+def torch_runtime_probe():
+    """The same path in a process of its own where PyTorch owns memory, stream and HIP runtime (this process uses
+    neither PyTorch nor its runtime, and has not touched the GPU yet)."""
+    import subprocess
+    say("child process: workload 1 under PyTorch's HIP runtime")
+    try:
+        r = subprocess.run([sys.executable, "-m", "paper_2406_10707_amd.torch_runtime_probe"], cwd=ROOT, capture_output=True, text=True,
+                           timeout=400)
+        lines = [ln for ln in r.stdout.splitlines() if ln.startswith("{")]
+        if r.returncode != 0 or not lines:
+            return {"error": (r.stderr or r.stdout)[-400:]}
+        return json.loads(lines[-1])
+    except Exception as e:      # a probe must not take the benchmark down with it
+        return {"error": repr(e)[:400]}
 
 
 def say(msg):
@@ -226,6 +255,31 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     stream.synchronize()
     gemm = harness.GemmProxy(8192)
     launches, gemm_ms_per_launch = gemm.calibrate(compute_ms, stream)
+    hbm_a = hbm_b = None
+    if args.hbm_victim_gib > 0:
+        nb = int(args.hbm_victim_gib * (1 << 30)) // 4096 * 4096
+        hbm_a, hbm_b = harness.DevBuf(nb), harness.DevBuf(nb)
+        B.proxy_device_fill_async(hbm_a.ptr, 1, nb, stream.handle)
+        e0, e1 = harness.Event(), harness.Event()
+        B.proxy_devcopy(hbm_b.ptr, hbm_a.ptr, nb, stream.handle)
+        e0.record(stream)
+        B.proxy_devcopy(hbm_b.ptr, hbm_a.ptr, nb, stream.handle)
+        e1.record(stream)
+        e1.synchronize()
+        copy_ms = e0.elapsed_time(e1)
+        # keep the phase's length: the copies take their share of it
+        launches = max(16, int(round(compute_ms / (gemm_ms_per_launch + copy_ms / 16.0))))
+
+    def forward_backward():
+        if hbm_a is None:
+            gemm.run(launches, stream)
+            return
+        done = 0
+        while done < launches:
+            n = min(16, launches - done)
+            gemm.run(n, stream)
+            B.proxy_devcopy(hbm_b.ptr, hbm_a.ptr, hbm_a.nbytes, stream.handle)
+            done += n
 
     policy = B.CKPT_WINDOW_PACK if args.policy == "pack" else B.CKPT_WINDOW_D2H
     chunk, sc = args.chunk_mib << 20, args.superchunk_mib << 20
@@ -278,7 +332,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         """One step on `stream`; marks gets (start, after-gemm, end) events."""
         e = [harness.Event() for _ in range(3)]
         e[0].record(stream)
-        gemm.run(launches, stream)
+        forward_backward()
         e[1].record(stream)
         if with_ckpt:
             ck.wait_immutable_window_end(stream.cuda_stream)
@@ -518,7 +572,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                    "prealloc_files": args.prealloc, "sink": out_dir.rsplit("/", 1)[0],
                    "direct_min_mib": args.direct_min_mib, "direct_tensors": lay["n_direct_tensors"],
                    "direct_bytes": lay["direct_bytes"], "copy_segments": lay["n_segments"],
-                   "reduce": args.reduce, "derived_tensors": lay["n_derived_tensors"], "link_bytes_per_snapshot": S},
+                   "hbm_victim_gib": args.hbm_victim_gib, "reduce": args.reduce, "derived_tensors": lay["n_derived_tensors"], "link_bytes_per_snapshot": S},
         "roofline": {"bound": "hbm", "kernel": "pack_kernel", "achieved": round(pack_gbps, 1) if pack_gbps else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(pack_gbps / HBM_PEAK_GBPS, 4) if pack_gbps else None,
                      "traffic": None, "traffic_source": "rocprofv3 FETCH_SIZE+WRITE_SIZE of this kernel on this workload, scaled by a copy kernel of known size (profiles/), as a ratio x algorithmic bytes per launch",
@@ -532,11 +586,15 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                      "d2h_frac_of_link_peak": round(link_gbps / link["d2h"], 4) if link_gbps else None,
                      "snapshot_gbps_frac_of_link_peak": round(snap_gbps / link["d2h"], 4) if snap_gbps else None,
                      "host_snapshot_call_ms": round(max(s["host_snapshot_call_ms"] for s in all_stats), 3) if all_stats else None,
+                     # time inside ckpt_wait_immutable_window_end: in this open loop the host runs steps ahead of the device, and
+                     # the call also absorbs that lead; the part the ring causes is the back-pressure time of the submit thread
                      "host_window_wait_ms": round(max(s["host_window_wait_ms"] for s in all_stats), 3) if all_stats else None,
+                     "host_backpressure_ms": round(max(s["host_backpressure_ms"] for s in all_stats), 3) if all_stats else None,
+                     "pack_fat_launch_share": round(sum(s["pack_fat_launches"] for s in stats) / max(1, pack_launches), 3) if stats else None,
                      "format_versions": sorted({s["format_version"] for s in all_stats}),
                      "verify_ms": round(statistics.median(s["verify_ms"] for s in all_stats), 3) if pairs and all_stats else None,
                      "flush_gbps": round(statistics.median(S / (s["host_flush_span_ms"] * 1e-3) / 1e9 for s in all_stats), 2) if all_stats else None,
-                     "drain_s": round(drain_s, 2), "init_s": round(init_s, 2)},
+                     "drain_s": round(drain_s, 2), "init_s": round(init_s, 2), "init_probe_d2h_gbps": round(ck.init_probe(), 2)},
         "stall": stall,
     }
     if solo_rows:
@@ -588,6 +646,8 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
             "wait_after_run_s": round(t2_wait, 2)}
     if restore_result:
         result["restore"] = restore_result
+    if args.torch_runtime_result is not None:
+        result["torch_runtime"] = args.torch_runtime_result
     ck.destroy()
     if not args.no_cpu_baseline:
         # the library's files go first: the sample's host arrays and its file need the memory (tmpfs is host memory)

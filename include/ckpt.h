@@ -108,7 +108,14 @@ typedef struct {
                                        device memory and the ring slot, without pack kernel or staging; only smaller
                                        tensors are packed. Needs window_policy CKPT_WINDOW_D2H (the copies read the
                                        tensors themselves). At least 4096 when set. */
-    int32_t reserved[2];            /* must be zero */
+    int32_t pack_shape;             /* which of the pack kernel's two shapes a launch uses. 0 (default): decided by measurement,
+                                       per launch: both shapes are tried at the start of every snapshot and every 32nd launch
+                                       in between; the shape in use changes when the other one's recent launches moved a
+                                       byte in at least 5 % less time.
+                                       1: always the slim shape (8 loads per lane in flight, few registers: fastest beside
+                                       the matrix kernels of a training step). 2: always the fat shape (a wave's whole tile
+                                       in flight: fastest on an otherwise idle card). Same bytes either way. */
+    int32_t reserved[1];            /* must be zero */
 } ckpt_config;
 
 /* Sizes that follow from a tensor list and a configuration. */
@@ -194,9 +201,10 @@ typedef struct {
     double host_io_copy_ms_sum;       /* host: summed over I/O threads, time writing ring slots to the file */
     double host_tier2_ms;             /* host: copy of the committed file to the second tier, open to rename (-1: none yet) */
     int32_t format_version;           /* 1 or 2 (docs/FORMAT.md); 0 while not yet decided */
-    int32_t reserved0;
+    int32_t pack_fat_launches;        /* of pack_launches, how many used the fat kernel shape (ckpt_config.pack_shape) */
     double verify_ms;                 /* device time of the derived-tensor check that decides the version (-1: no pairs declared) */
     double host_window_wait_ms;       /* host: time the caller spent inside ckpt_wait_immutable_window_end for this snapshot */
+    double init_d2h_gbps;             /* the context's set-up probe (ckpt_get_init_probe), repeated here */
 } ckpt_stats;
 
 #define CKPT_ITER_ALL UINT64_MAX
@@ -368,6 +376,13 @@ int ckpt_pack_image(const ckpt_tensor_desc *tensors, size_t n, void *dev_dst, ui
 int ckpt_pack_image_noalloc(const ckpt_tensor_desc *tensors, size_t n, void *dev_dst, uint64_t dst_bytes, void *hip_stream);
 
 int ckpt_get_layout(ckpt_ctx *ctx, ckpt_layout *out);
+/* ckpt_init copies one ring slot's worth (at most 64 MiB) from device memory into the pinned ring on a copy
+ * stream and times it: *d2h_gbps is that rate in GB/s (-1 if it could not be measured). The paper's design rests on
+ * a copy engine that moves checkpoints without taking compute resources from training; whether the copies of
+ * this process go that way is a property of the HIP runtime it has loaded. On MI355X the system runtime reaches
+ * about 56 GB/s here; a figure far below the link's rate means the runtime executes copies with kernels on the
+ * compute units, and snapshots will both run slower and slow training down. */
+int ckpt_get_init_probe(ckpt_ctx *ctx, double *d2h_gbps);
 /* Measurements of one requested snapshot; CKPT_EINVAL if unknown (records of the 1024 most recent
  * requests are kept). Device-timeline fields are filled
  * once d2h_done is set. */

@@ -261,6 +261,25 @@ int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out) {
         for (auto &t : th) t.join();
     }
     trace("init: pages touched");
+    {   // One ring slot's worth of device-to-host copy, timed on a copy stream: tells the caller at what rate the HIP
+        // runtime of this process moves pinned copies (the copy engines reach the link's rate; a runtime that
+        // executes copies with kernels on the compute units does not, and takes the units from training).
+        const size_t nb = size_t(std::min<uint64_t>(rc.dma_chunk_bytes, 64ull << 20));
+        void *d = nullptr;
+        hipEvent_t t0 = nullptr, t1 = nullptr;
+        if (hipMalloc(&d, nb) == hipSuccess && hipEventCreate(&t0) == hipSuccess && hipEventCreate(&t1) == hipSuccess) {
+            float ms = 0;
+            bool ok = hipMemcpyAsync(c->ring, d, nb, hipMemcpyDeviceToHost, c->dma[0]) == hipSuccess;   // first use of the path
+            ok = ok && hipEventRecord(t0, c->dma[0]) == hipSuccess;
+            ok = ok && hipMemcpyAsync(c->ring, d, nb, hipMemcpyDeviceToHost, c->dma[0]) == hipSuccess;
+            ok = ok && hipEventRecord(t1, c->dma[0]) == hipSuccess && hipEventSynchronize(t1) == hipSuccess;
+            if (ok && hipEventElapsedTime(&ms, t0, t1) == hipSuccess && ms > 0) c->init_d2h_gbps = double(nb) / (double(ms) * 1e6);
+        }
+        (void)hipGetLastError();
+        if (t0) (void)hipEventDestroy(t0);
+        if (t1) (void)hipEventDestroy(t1);
+        if (d) (void)hipFree(d);
+    }
     trace("init: starting threads");
     c->submit_thread = std::thread(submit_thread_main, c.get());
     for (int i = 0; i < rc.n_io_threads; i++) c->io_threads.emplace_back(io_thread_main, c.get());
@@ -512,6 +531,12 @@ int ckpt_declare_derived(ckpt_ctx *c, const uint32_t *derived, const uint32_t *s
     return CKPT_OK;
 }
 
+int ckpt_get_init_probe(ckpt_ctx *c, double *d2h_gbps) {
+    if (!c || !d2h_gbps) return fail(CKPT_EINVAL, "null argument");
+    *d2h_gbps = c->init_d2h_gbps;
+    return CKPT_OK;
+}
+
 int ckpt_get_stats(ckpt_ctx *c, uint64_t iter, ckpt_stats *o) {
     if (!c || !o) return fail(CKPT_EINVAL, "null argument");
     std::lock_guard<std::mutex> lk(c->mu);
@@ -525,8 +550,10 @@ int ckpt_get_stats(ckpt_ctx *c, uint64_t iter, ckpt_stats *o) {
     o->data_bytes = sp.data_bytes;
     o->file_bytes = sp.file_bytes();
     o->format_version = s.plan ? int32_t(s.plan->version) : 0;
+    o->pack_fat_launches = s.fat_launches;
     o->verify_ms = s.verify_ms;
     o->host_window_wait_ms = s.window_wait_ms;
+    o->init_d2h_gbps = c->init_d2h_gbps;
     o->d2h_done = s.d2h_done;
     o->committed = s.committed;
     o->pack_launches = int32_t(sp.n_superchunks);

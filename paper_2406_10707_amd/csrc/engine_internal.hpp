@@ -30,7 +30,8 @@
 #include "plan.hpp"
 
 namespace dsllm {
-hipError_t launch_pack(const ckpt_tile *dev_tiles, uint64_t n_tiles, void *slot_base, uint64_t slot_data_off, hipStream_t stream);
+// shape: 0 slim (few registers, finds room beside a training step's kernels), 1 fat (whole tile in flight, fastest alone)
+hipError_t launch_pack(const ckpt_tile *dev_tiles, uint64_t n_tiles, void *slot_base, uint64_t slot_data_off, int shape, hipStream_t stream);
 hipError_t launch_scatter(const ckpt_tile *dev_tiles, uint64_t n_tiles, const void *slot_base, uint64_t slot_data_off, hipStream_t stream);
 hipError_t launch_verify_pairs(const PairTile *dev_tiles, uint64_t n_tiles, uint32_t *dev_flag, hipStream_t stream);
 hipError_t launch_derive_pairs(const PairTile *dev_tiles, uint64_t n_tiles, hipStream_t stream);
@@ -80,6 +81,7 @@ struct Snap {
     const Plan *plan = nullptr;
     const ckpt_tile *dev_tiles = nullptr;   // that plan's tile table on the device
     double verify_ms = -1;                  // device time of the derivation check (-1: none)
+    int fat_launches = 0;                   // pack launches of this snapshot that used the fat kernel shape
     double window_wait_ms = 0;              // host: time the caller spent in ckpt_wait_immutable_window_end for this snapshot
     int fd = -1;
     uint8_t *map = nullptr;
@@ -149,6 +151,14 @@ struct ckpt_ctx {
     hipEvent_t ev_first_copy = nullptr, ev_user = nullptr;
     uint8_t *hdr_buf = nullptr;                           // 4 KiB-aligned scratch for header writes
     uint64_t ring_next = 0;                               // global chunk counter -> ring slot
+    // Choice of the pack kernel's shape (cfg.pack_shape 0: by measurement). Touched by the submit thread only.
+    // ns per byte of recent launches of each shape (exponential average, 0: none yet), the shape each super-chunk's
+    // launch of the current snapshot used, and how many of them have been read back from their events.
+    double shape_ns_per_byte[2] = {0, 0};
+    std::vector<uint8_t> shape_of_sc;
+    uint64_t shapes_harvested = 0, launches_since_probe = 0;
+    int shape_in_use = 0;
+    double init_d2h_gbps = -1;                            // one ring slot copied device-to-host at set-up, timed (-1: could not be measured)
 
     // threads and queues
     std::mutex mu;

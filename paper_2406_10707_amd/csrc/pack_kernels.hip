@@ -36,27 +36,20 @@ namespace dsllm {
 #ifndef DSLLM_PACK_UNROLL_SHIFT
 #define DSLLM_PACK_UNROLL_SHIFT 4
 #endif
-// How the pack kernel reads a source that is not 16-byte aligned. 0: aligned 16-byte loads, the neighbour
-// lane's word by register exchange, byte funnel. 1: one 16-byte load per lane at the tensor's own (unaligned)
-// address; the memory pipeline splits what straddles a line. The target allows unaligned vector loads (the
-// compiler itself emits a single global_load_dwordx4 for an under-aligned 16-byte access).
-#ifndef DSLLM_PACK_MISALIGNED
-#define DSLLM_PACK_MISALIGNED 0
-#endif
-#ifndef DSLLM_PACK_UNROLL_MIS
-#define DSLLM_PACK_UNROLL_MIS DSLLM_PACK_UNROLL     // loads in flight per lane on the unaligned-load path
-#endif
-#ifndef DSLLM_PACK_PIPE
-#define DSLLM_PACK_PIPE 0                           // 1: the next group's loads are issued before this group's stores
-#endif
-#ifndef DSLLM_PACK_XCHG_MAX
-#define DSLLM_PACK_XCHG_MAX 8                       // largest group of the exchange path (8 or 16)
-#endif
 constexpr uint64_t kPackTileBytes = 32 * 1024;   // the planner's tile size (plan.hpp: kTileBytes)
 constexpr int kWavesPerBlock = DSLLM_PACK_WAVES_PER_BLOCK;
 constexpr int kBlock = 64 * kWavesPerBlock;
-constexpr int kUnroll = DSLLM_PACK_UNROLL;             // aligned path: 16-byte words per lane in flight
-constexpr int kUnrollShift = DSLLM_PACK_UNROLL_SHIFT;  // misaligned path: pairs of 16-byte words per lane in flight
+constexpr int kUnroll = DSLLM_PACK_UNROLL;             // slim shape, aligned path: 16-byte words per lane in flight
+constexpr int kUnrollShift = DSLLM_PACK_UNROLL_SHIFT;  // scatter, misaligned path: pairs of 16-byte words per lane in flight
+
+// The pack kernel comes in two shapes, same bytes out, chosen per launch by the host (launch_pack):
+//  SLIM  8 loads of 16 bytes per lane in flight, 50 vector registers: a wave finds room on a SIMD beside the
+//        register-hungry matrix kernels of a training step, so this is the shape that is fastest while they run.
+//  FAT   the whole tile (32 loads per lane, 32 KiB per wave) in flight before the first store, about 150 registers,
+//        three waves per SIMD: fewer, longer bursts per wave. Fastest when the card has nothing else to do
+//        (measured on the fragmented workload, one launch over 40 GB: 5.86 against 5.18 TB/s), slowest beside a
+//        kernel that leaves it no registers.
+constexpr int kShapeSlim = 0, kShapeFat = 1;
 
 // bytes [sh, sh+16) of the 32-byte string lo||hi, for sh = 4*W + b, 1 <= sh <= 15
 template <int W>
@@ -84,48 +77,29 @@ __device__ __forceinline__ u32x4 keep_bytes(u32x4 v, uint32_t keep) {
 
 // ---------------------------------------------------------------- pack: tensors -> staging
 
-// Output word j (16 bytes, aligned) = the 16 bytes at su + 16 j (any alignment), for j < n_full, lane-strided.
-// U loads per lane in flight; with PIPE a second set is loaded while the first is stored.
-template <int U, bool PIPE>
-__device__ __forceinline__ void copy_words(const uint8_t *su, u32x4 *dst, uint32_t n_full, uint32_t lane) {
-    uint32_t i = lane;
-    if (!PIPE) {
-        for (; i + 64 * (U - 1) < n_full; i += 64 * U) {
-            u32x4 v[U];
+// FAT shape. Output word j (16 bytes, aligned) = the 16 bytes at su + 16 j, for j < n: groups of 32, 16, ... 1 times 64
+// words, every load of a group issued before its first store. su may have any alignment: the target supports
+// unaligned vector loads (a 16-byte load at a 2-byte-aligned address is a single global_load_dwordx4), and all 16
+// bytes of every word lie inside the tensor, so nothing outside it is read.
+template <int U>
+__device__ __forceinline__ void copy_group(const uint8_t *su, u32x4 *dst, uint32_t g, uint32_t lane) {
+    u32x4 v[U];
 #pragma unroll
-            for (int u = 0; u < U; u++) v[u] = ld16_unaligned(su + 16ull * (i + 64 * u));
+    for (int u = 0; u < U; u++) v[u] = ld16_unaligned(su + 16ull * (g + 64 * u + lane));
 #pragma unroll
-            for (int u = 0; u < U; u++) st16(dst + i + 64 * u, v[u]);
-        }
-    } else if (i + 64 * (U - 1) < n_full) {
-        u32x4 a[U], b[U];
-#pragma unroll
-        for (int u = 0; u < U; u++) a[u] = ld16_unaligned(su + 16ull * (i + 64 * u));
-        for (;;) {
-            uint32_t j = i + 64 * U;
-            if (!(j + 64 * (U - 1) < n_full)) {
-#pragma unroll
-                for (int u = 0; u < U; u++) st16(dst + i + 64 * u, a[u]);
-                i = j;
-                break;
-            }
-#pragma unroll
-            for (int u = 0; u < U; u++) b[u] = ld16_unaligned(su + 16ull * (j + 64 * u));
-#pragma unroll
-            for (int u = 0; u < U; u++) st16(dst + i + 64 * u, a[u]);
-            i = j + 64 * U;
-            if (!(i + 64 * (U - 1) < n_full)) {
-#pragma unroll
-                for (int u = 0; u < U; u++) st16(dst + j + 64 * u, b[u]);
-                break;
-            }
-#pragma unroll
-            for (int u = 0; u < U; u++) a[u] = ld16_unaligned(su + 16ull * (i + 64 * u));
-#pragma unroll
-            for (int u = 0; u < U; u++) st16(dst + j + 64 * u, b[u]);
-        }
-    }
-    for (; i < n_full; i += 64) st16(dst + i, ld16_unaligned(su + 16ull * i));
+    for (int u = 0; u < U; u++) st16(dst + g + 64 * u + lane, v[u]);
+}
+
+__device__ __forceinline__ void copy_whole(const uint8_t *su, u32x4 *dst, uint32_t n, uint32_t lane) {
+    uint32_t g = 0;
+    for (; g + 64 * 32 <= n; g += 64 * 32) copy_group<32>(su, dst, g, lane);
+    if (g + 64 * 16 <= n) { copy_group<16>(su, dst, g, lane); g += 64 * 16; }
+    if (g + 64 * 8 <= n) { copy_group<8>(su, dst, g, lane); g += 64 * 8; }
+    if (g + 64 * 4 <= n) { copy_group<4>(su, dst, g, lane); g += 64 * 4; }
+    if (g + 64 * 2 <= n) { copy_group<2>(su, dst, g, lane); g += 64 * 2; }
+    if (g + 64 <= n) { copy_group<1>(su, dst, g, lane); g += 64; }
+    const uint32_t i = g + lane;
+    if (i < n) st16(dst + i, ld16_unaligned(su + 16ull * i));
 }
 
 // The aligned source word that follows this lane's own: lane l takes `cur` of lane l+1, lane 63 takes
@@ -172,13 +146,9 @@ __device__ __forceinline__ void pack_shifted_group(const u32x4 *src_al, u32x4 *d
 // Copies the full 16-byte words of a tile whose source is misaligned by 4*W+b bytes.
 template <int W>
 __device__ __forceinline__ void pack_shifted(const u32x4 *src_al, u32x4 *dst, uint32_t n_full, uint32_t b, uint32_t lane) {
+    static_assert(kUnroll == 8, "the group cascade below is written for 8, 4, 2, 1");
     uint32_t g = 0;
-#if DSLLM_PACK_XCHG_MAX == 16
-    for (; g + 64 * 16 <= n_full; g += 64 * 16) pack_shifted_group<W, 16>(src_al, dst, g, b, lane);
-    if (g + 64 * 8 <= n_full) { pack_shifted_group<W, 8>(src_al, dst, g, b, lane); g += 64 * 8; }
-#else
     for (; g + 64 * 8 <= n_full; g += 64 * 8) pack_shifted_group<W, 8>(src_al, dst, g, b, lane);
-#endif
     if (g + 64 * 4 <= n_full) { pack_shifted_group<W, 4>(src_al, dst, g, b, lane); g += 64 * 4; }
     if (g + 64 * 2 <= n_full) { pack_shifted_group<W, 2>(src_al, dst, g, b, lane); g += 64 * 2; }
     if (g + 64 <= n_full) { pack_shifted_group<W, 1>(src_al, dst, g, b, lane); g += 64; }
@@ -187,6 +157,66 @@ __device__ __forceinline__ void pack_shifted(const u32x4 *src_al, u32x4 *dst, ui
     if (i < n_full) st16(dst + i, funnel<W>(ld16(src_al + i), ld16(src_al + i + 1), b));
 }
 
+// Output words [lo, hi) of one tile (16-byte words of its destination): source bytes where the tile has them,
+// the masked tail word, zero padding behind it. All lanes of the wave in step; the tile's fields are wave-uniform.
+template <int SHAPE>
+__device__ __forceinline__ void pack_range(uint64_t src, u32x4 *dst, uint32_t copy_bytes, uint32_t total_bytes, uint32_t lo, uint32_t hi,
+                                           uint32_t lane) {
+    const uint32_t n_total = total_bytes >> 4;   // 16-byte words to write
+    const uint32_t n_full = copy_bytes >> 4;     // of which fully covered by source bytes
+    const uint32_t tail = copy_bytes & 15;       // source bytes in word n_full
+    const uint32_t sh = uint32_t(src) & 15;
+    if (hi > n_total) hi = n_total;
+    if (lo >= hi) return;
+    const uint32_t c_hi = hi < n_full ? hi : n_full;            // copy words [lo, c_hi)
+    const uint32_t n = c_hi > lo ? c_hi - lo : 0;
+    const bool own_tail = tail && lo <= n_full && n_full < hi;  // the range that holds word n_full writes the tail
+    const u32x4 *s = reinterpret_cast<const u32x4 *>(src - sh); // the aligned words that cover the tile's source bytes
+    const uint32_t b = sh & 3;
+
+    if (SHAPE == kShapeFat) {
+        copy_whole(reinterpret_cast<const uint8_t *>(src) + 16ull * lo, dst + lo, n, lane);
+    } else if (sh == 0) {
+        uint32_t i = lo + lane;
+        for (; i + 64 * (kUnroll - 1) < c_hi; i += 64 * kUnroll) {
+            u32x4 v[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; u++) v[u] = ld16(s + i + 64 * u);
+#pragma unroll
+            for (int u = 0; u < kUnroll; u++) st16(dst + i + 64 * u, v[u]);
+        }
+        for (; i < c_hi; i += 64) st16(dst + i, ld16(s + i));
+    } else {
+        // the exchange reads aligned source word lo + n as the upper half of the last output word: it exists,
+        // because lo + n <= n_full and word n_full holds tensor bytes (or lies in the line of the last one)
+        switch (sh >> 2) {
+            case 0: pack_shifted<0>(s + lo, dst + lo, n, b, lane); break;
+            case 1: pack_shifted<1>(s + lo, dst + lo, n, b, lane); break;
+            case 2: pack_shifted<2>(s + lo, dst + lo, n, b, lane); break;
+            default: pack_shifted<3>(s + lo, dst + lo, n, b, lane); break;
+        }
+    }
+    if (own_tail && lane == 0) {
+        // The tail word never comes from an unaligned load (that would read up to 15 bytes past the tensor, possibly
+        // into an unmapped page): aligned word n_full holds source bytes, word n_full + 1 only if sh + tail > 16.
+        u32x4 v = ld16(s + n_full);
+        if (sh != 0) {
+            const u32x4 w1 = (sh + tail > 16) ? ld16(s + n_full + 1) : u32x4{0, 0, 0, 0};
+            switch (sh >> 2) {
+                case 0: v = funnel<0>(v, w1, b); break;
+                case 1: v = funnel<1>(v, w1, b); break;
+                case 2: v = funnel<2>(v, w1, b); break;
+                default: v = funnel<3>(v, w1, b); break;
+            }
+        }
+        st16(dst + n_full, keep_bytes(v, tail));
+    }
+    // zero padding after the tensor's last byte
+    const uint32_t z0 = n_full + (tail ? 1u : 0u);
+    for (uint32_t i = (z0 > lo ? z0 : lo) + lane; i < hi; i += 64) st16(dst + i, u32x4{0, 0, 0, 0});
+}
+
+template <int SHAPE>
 __global__ __launch_bounds__(kBlock) void pack_kernel(const ckpt_tile *__restrict__ tiles, uint64_t n_tiles,
                                                      uint8_t *__restrict__ slot_base, uint64_t slot_data_off) {
     const uint32_t lane = threadIdx.x & 63;
@@ -201,62 +231,8 @@ __global__ __launch_bounds__(kBlock) void pack_kernel(const ckpt_tile *__restric
     const ckpt_tile *tp = tiles + t;
     const uint64_t src = uniform_u64(tp->src);
     const uint64_t dst_off = uniform_u64(tp->dst_off);
-    const uint32_t copy_bytes = uniform_u32(tp->copy_bytes);
-    const uint32_t total_bytes = uniform_u32(tp->total_bytes);
-
     u32x4 *dst = reinterpret_cast<u32x4 *>(slot_base + (dst_off - slot_data_off));
-    const uint32_t n_total = total_bytes >> 4;   // 16-byte words to write
-    const uint32_t n_full = copy_bytes >> 4;     // of which fully covered by source bytes
-    const uint32_t tail = copy_bytes & 15;       // source bytes in word n_full
-    const uint32_t sh = uint32_t(src) & 15;
-
-    if (sh == 0) {
-        const u32x4 *s = reinterpret_cast<const u32x4 *>(src);
-#if DSLLM_PACK_PIPE
-        copy_words<kUnroll, true>(reinterpret_cast<const uint8_t *>(src), dst, n_full, lane);
-#else
-        uint32_t i = lane;
-        for (; i + 64 * (kUnroll - 1) < n_full; i += 64 * kUnroll) {
-            u32x4 v[kUnroll];
-#pragma unroll
-            for (int u = 0; u < kUnroll; u++) v[u] = ld16(s + i + 64 * u);
-#pragma unroll
-            for (int u = 0; u < kUnroll; u++) st16(dst + i + 64 * u, v[u]);
-        }
-        for (; i < n_full; i += 64) st16(dst + i, ld16(s + i));
-#endif
-        if (tail && lane == 0) st16(dst + n_full, keep_bytes(ld16(s + n_full), tail));
-    } else {
-        const u32x4 *s = reinterpret_cast<const u32x4 *>(src - sh);
-        const uint32_t b = sh & 3;
-#if DSLLM_PACK_MISALIGNED == 1
-        // output word j = source bytes [16 j, 16 j + 16): inside the tensor for every j < n_full
-        copy_words<DSLLM_PACK_UNROLL_MIS, DSLLM_PACK_PIPE != 0>(reinterpret_cast<const uint8_t *>(src), dst, n_full, lane);
-#else
-        switch (sh >> 2) {
-            case 0: pack_shifted<0>(s, dst, n_full, b, lane); break;
-            case 1: pack_shifted<1>(s, dst, n_full, b, lane); break;
-            case 2: pack_shifted<2>(s, dst, n_full, b, lane); break;
-            default: pack_shifted<3>(s, dst, n_full, b, lane); break;
-        }
-#endif
-        if (tail && lane == 0) {
-            // word n_full of the aligned source holds source bytes; word n_full+1 only if sh + tail > 16
-            u32x4 lo = ld16(s + n_full);
-            u32x4 hi = (sh + tail > 16) ? ld16(s + n_full + 1) : u32x4{0, 0, 0, 0};
-            u32x4 v;
-            switch (sh >> 2) {
-                case 0: v = funnel<0>(lo, hi, b); break;
-                case 1: v = funnel<1>(lo, hi, b); break;
-                case 2: v = funnel<2>(lo, hi, b); break;
-                default: v = funnel<3>(lo, hi, b); break;
-            }
-            st16(dst + n_full, keep_bytes(v, tail));
-        }
-    }
-    // zero padding after the tensor's last byte
-    const uint32_t z0 = n_full + (tail ? 1u : 0u);
-    for (uint32_t i = z0 + lane; i < n_total; i += 64) st16(dst + i, u32x4{0, 0, 0, 0});
+    pack_range<SHAPE>(src, dst, uniform_u32(tp->copy_bytes), uniform_u32(tp->total_bytes), 0, uint32_t(kPackTileBytes / 16), lane);
 }
 
 // ---------------------------------------------------------------- scatter: staging -> tensors
@@ -379,10 +355,14 @@ hipError_t launch_build_tiles(const TileBatch &bt, ckpt_tile *dev_table, hipStre
 
 static inline unsigned grid_for(uint64_t n_tiles) { return unsigned((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock); }
 
-hipError_t launch_pack(const ckpt_tile *dev_tiles, uint64_t n_tiles, void *slot_base, uint64_t slot_data_off, hipStream_t stream) {
+hipError_t launch_pack(const ckpt_tile *dev_tiles, uint64_t n_tiles, void *slot_base, uint64_t slot_data_off, int shape, hipStream_t stream) {
     if (n_tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL(pack_kernel, dim3(grid_for(n_tiles)), dim3(kBlock), 0, stream, dev_tiles, n_tiles,
-                       static_cast<uint8_t *>(slot_base), slot_data_off);
+    if (shape == kShapeFat)
+        hipLaunchKernelGGL(pack_kernel<kShapeFat>, dim3(grid_for(n_tiles)), dim3(kBlock), 0, stream, dev_tiles, n_tiles,
+                           static_cast<uint8_t *>(slot_base), slot_data_off);
+    else
+        hipLaunchKernelGGL(pack_kernel<kShapeSlim>, dim3(grid_for(n_tiles)), dim3(kBlock), 0, stream, dev_tiles, n_tiles,
+                           static_cast<uint8_t *>(slot_base), slot_data_off);
     return hipGetLastError();
 }
 

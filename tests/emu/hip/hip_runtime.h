@@ -37,6 +37,9 @@ extern thread_local dim3 threadIdx, blockIdx, blockDim, gridDim;
 #define __host__
 #define __forceinline__ inline __attribute__((always_inline))
 #define __launch_bounds__(...)
+// one "thread" runs at a time per launch, and launches of different streams may run at the same time: LDS of the
+// model belongs to the host thread that runs the launch (only kernels whose lanes read back what they wrote themselves)
+#define __shared__ static thread_local
 #define __align__(n) __attribute__((aligned(n)))
 #define HIP_SYMBOL(x) x
 
@@ -166,6 +169,11 @@ inline hipError_t hipEventSynchronize(hipEvent_t e) {
     const uint64_t gen = e->recorded;       // never recorded: returns at once, like the real call
     e->cv.wait(lk, [&] { return e->completed >= gen; });
     return hipSuccess;
+}
+static const hipError_t hipErrorNotReady = 600;
+inline hipError_t hipEventQuery(hipEvent_t e) {
+    std::lock_guard<std::mutex> lk(e->m);
+    return e->completed >= e->recorded ? hipSuccess : hipErrorNotReady;
 }
 inline hipError_t hipStreamWaitEvent(hipStream_t s, hipEvent_t e, unsigned) {
     uint64_t gen;
