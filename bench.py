@@ -520,6 +520,12 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         ck.flush()
         ck.set_window_policy(B.CKPT_WINDOW_D2H)
 
+    # ---- the link peak once more: the first measurement of a process has been seen at half the rate when the previous
+    # process on the box had just released a hundred GB of pinned and file memory; the better of the two counts
+    link2 = measure_link_peak(B, harness, stream)
+    link_first = dict(link)
+    link = {k: max(link[k], link2[k]) for k in link}
+
     # ---- baseline after; GEMM speed drifts a few per cent with temperature, so before and after are averaged
     say("baseline phase (no checkpoints)")
     base_after = baseline_phase(args.baseline_steps)
@@ -582,6 +588,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                      "devcopy_ceiling_gbps": round(devcopy_gbps, 1)},
         "snapshot": {"snapshots_in_timed_region": len(in_region), "link_peak_d2h_gbps": round(link["d2h"], 2),
                      "link_peak_h2d_gbps": round(link["h2d"], 2),
+                     "link_peak_d2h_measurements_gbps": [round(link_first["d2h"], 2), round(link2["d2h"], 2)],
                      "d2h_gbps": round(link_gbps, 2) if link_gbps else None,
                      "d2h_frac_of_link_peak": round(link_gbps / link["d2h"], 4) if link_gbps else None,
                      "snapshot_gbps_frac_of_link_peak": round(snap_gbps / link["d2h"], 4) if snap_gbps else None,

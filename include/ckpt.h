@@ -108,13 +108,12 @@ typedef struct {
                                        device memory and the ring slot, without pack kernel or staging; only smaller
                                        tensors are packed. Needs window_policy CKPT_WINDOW_D2H (the copies read the
                                        tensors themselves). At least 4096 when set. */
-    int32_t pack_shape;             /* which of the pack kernel's two shapes a launch uses. 0 (default): decided by measurement,
-                                       per launch: both shapes are tried at the start of every snapshot and every 32nd launch
-                                       in between; the shape in use changes when the other one's recent launches moved a
-                                       byte in at least 5 % less time.
-                                       1: always the slim shape (8 loads per lane in flight, few registers: fastest beside
-                                       the matrix kernels of a training step). 2: always the fat shape (a wave's whole tile
-                                       in flight: fastest on an otherwise idle card). Same bytes either way. */
+    int32_t pack_shape;             /* which of the pack kernel's two shapes a launch uses. 0 (default): the fat shape when the
+                                       stream the snapshot was requested on has no work left at the moment of the launch,
+                                       the slim shape otherwise. 1: always the slim shape (8 loads per lane in flight, few
+                                       registers: fastest beside the matrix kernels of a training step). 2: always the fat
+                                       shape (a wave's whole tile in flight: fastest on an otherwise idle card). Same bytes
+                                       either way. With 0 the stream handle must stay valid until the snapshot's window is closed. */
     int32_t reserved[1];            /* must be zero */
 } ckpt_config;
 

@@ -405,6 +405,7 @@ int ckpt_snapshot_async(ckpt_ctx *c, uint64_t iter, void *stream) {
     sp->final_path = file_name_for(c->out_dir, iter);
     sp->tmp_path = sp->final_path + ".tmp";
     sp->t_request = t0;
+    sp->stream = static_cast<hipStream_t>(stream);
     if (c->plan.n_host) {   // host memory is not ordered with the stream: read it now, the caller may change it after this call
         sp->host_capture.resize(c->plan.host_bytes);
         for (const auto &t : c->plan.tensors)

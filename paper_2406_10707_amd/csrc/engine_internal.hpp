@@ -88,6 +88,7 @@ struct Snap {
     std::string tmp_path, final_path;
     std::atomic<uint64_t> chunks_left{0};
     hipEvent_t ev_boundary = nullptr;
+    hipStream_t stream = nullptr;           // the caller's stream the snapshot was requested on (asked whether it has run dry)
     bool submitted = false, packs_submitted = false, d2h_done = false, committed = false, window_closed = false;
     Clock::time_point t_request, t_submitted, t_committed, t_first_chunk;
     bool have_first_chunk = false;
@@ -151,13 +152,6 @@ struct ckpt_ctx {
     hipEvent_t ev_first_copy = nullptr, ev_user = nullptr;
     uint8_t *hdr_buf = nullptr;                           // 4 KiB-aligned scratch for header writes
     uint64_t ring_next = 0;                               // global chunk counter -> ring slot
-    // Choice of the pack kernel's shape (cfg.pack_shape 0: by measurement). Touched by the submit thread only.
-    // ns per byte of recent launches of each shape (exponential average, 0: none yet), the shape each super-chunk's
-    // launch of the current snapshot used, and how many of them have been read back from their events.
-    double shape_ns_per_byte[2] = {0, 0};
-    std::vector<uint8_t> shape_of_sc;
-    uint64_t shapes_harvested = 0, launches_since_probe = 0;
-    int shape_in_use = 0;
     double init_d2h_gbps = -1;                            // one ring slot copied device-to-host at set-up, timed (-1: could not be measured)
 
     // threads and queues

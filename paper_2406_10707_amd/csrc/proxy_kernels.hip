@@ -125,14 +125,23 @@ __global__ __launch_bounds__(256) void devcopy_kernel(u32x4 *__restrict__ dst, c
 
 // ------------------------------------------------------------------ bf16 GEMM on the matrix cores
 
-// Block tile 128x128, K step 32, 256 threads = 4 wavefronts in a 2x2 arrangement, each computing a
-// 64x64 sub-tile as 2x2 MFMA 32x32x16 tiles. Both operands are K-contiguous, so an A or B
+// Block tile (64 T) x (64 T), K step 32, 256 threads = 4 wavefronts in a 2x2 arrangement, each computing a
+// (32 T) x (32 T) sub-tile as T x T MFMA 32x32x16 tiles. Both operands are K-contiguous, so an A or B
 // fragment (8 consecutive K values of one row/column per lane) is one 16-byte LDS read. LDS rows are
 // padded from 64 to 80 bytes, which spreads the 16-byte reads of 16 consecutive rows over all banks.
-constexpr int BM = 128, BN = 128, BK = 32, LDS_ROW = 40;   // LDS_ROW in bf16 elements
-
+//
+// T = 2 (128 x 128 block, 64 accumulator registers per lane, three blocks per CU) is LDS-bound: per MFMA one
+// fragment read, and with the stores of the next tile the LDS pipe is busier than the matrix pipe. T = 4
+// (256 x 256 block, one block per CU, 256 accumulator registers per lane) halves the reads per MFMA: eight
+// fragment reads feed sixteen MFMAs, LDS traffic is about three quarters of the matrix pipe's time, and the
+// next K step's fragments are read while this step's MFMAs run.
+template <int T, int BK>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint16_t *__restrict__ A, const uint16_t *__restrict__ B,
                                                        uint16_t *__restrict__ C, int M, int N, int K) {
+    constexpr int BM = 64 * T, BN = 64 * T, WT = 32 * T;   // block tile and one wave's share of it
+    constexpr int LDS_ROW = BK + 8;                        // in bf16 elements: rows padded by 16 bytes (80 or 144 bytes per row)
+    constexpr int PIECES = BK / 8;                         // 16-byte pieces per row of a K step
+    constexpr int ROWS_PER_PASS = 256 / PIECES, PASSES = BM / ROWS_PER_PASS;
     __shared__ __attribute__((aligned(16))) uint16_t lds_a[2][BM * LDS_ROW];
     __shared__ __attribute__((aligned(16))) uint16_t lds_b[2][BN * LDS_ROW];
 
@@ -152,29 +161,29 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint16_t *__restri
     const uint16_t *a_blk = A + size_t(tm) * BM * K;
     const uint16_t *b_blk = B + size_t(tn) * BN * K;
 
-    // global -> LDS staging: thread t moves 16 bytes of row (t/4 + 64*pass), K offset 8*(t%4)
-    const int ld_row = tid >> 2, ld_col = (tid & 3) * 8;
-    u32x4 ra[2], rb[2];
+    // global -> LDS staging: thread t moves 16 bytes of row (t / PIECES + ROWS_PER_PASS * pass), K offset 8 * (t % PIECES)
+    const int ld_row = tid / PIECES, ld_col = (tid % PIECES) * 8;
+    u32x4 ra[PASSES], rb[PASSES];
     auto load_tile = [&](int kt) {
 #pragma unroll
-        for (int ps = 0; ps < 2; ps++) {
-            ra[ps] = *reinterpret_cast<const u32x4 *>(a_blk + size_t(ld_row + 64 * ps) * K + kt * BK + ld_col);
-            rb[ps] = *reinterpret_cast<const u32x4 *>(b_blk + size_t(ld_row + 64 * ps) * K + kt * BK + ld_col);
+        for (int ps = 0; ps < PASSES; ps++) {
+            ra[ps] = *reinterpret_cast<const u32x4 *>(a_blk + size_t(ld_row + ROWS_PER_PASS * ps) * K + kt * BK + ld_col);
+            rb[ps] = *reinterpret_cast<const u32x4 *>(b_blk + size_t(ld_row + ROWS_PER_PASS * ps) * K + kt * BK + ld_col);
         }
     };
     auto store_tile = [&](int buf) {
 #pragma unroll
-        for (int ps = 0; ps < 2; ps++) {
-            *reinterpret_cast<u32x4 *>(&lds_a[buf][(ld_row + 64 * ps) * LDS_ROW + ld_col]) = ra[ps];
-            *reinterpret_cast<u32x4 *>(&lds_b[buf][(ld_row + 64 * ps) * LDS_ROW + ld_col]) = rb[ps];
+        for (int ps = 0; ps < PASSES; ps++) {
+            *reinterpret_cast<u32x4 *>(&lds_a[buf][(ld_row + ROWS_PER_PASS * ps) * LDS_ROW + ld_col]) = ra[ps];
+            *reinterpret_cast<u32x4 *>(&lds_b[buf][(ld_row + ROWS_PER_PASS * ps) * LDS_ROW + ld_col]) = rb[ps];
         }
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[T][T];
 #pragma unroll
-    for (int i = 0; i < 2; i++)
+    for (int i = 0; i < T; i++)
 #pragma unroll
-        for (int j = 0; j < 2; j++)
+        for (int j = 0; j < T; j++)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[i][j][r] = 0.0f;
 
@@ -183,21 +192,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint16_t *__restri
     store_tile(0);
     __syncthreads();
     const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+    bf16x8 fa[2][T], fb[2][T];          // two sets: the fragments of the next K slice are read while this slice's MFMAs run
+    auto read_frags = [&](int set, int buf, int kk) {
+#pragma unroll
+        for (int i = 0; i < T; i++) {
+            fa[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&lds_a[buf][(wm * WT + i * 32 + frag_row) * LDS_ROW + kk * 16 + frag_k]));
+            fb[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&lds_b[buf][(wn * WT + i * 32 + frag_row) * LDS_ROW + kk * 16 + frag_k]));
+        }
+    };
     for (int kt = 0; kt < KT; kt++) {
         const int buf = kt & 1;
         if (kt + 1 < KT) load_tile(kt + 1);
+        read_frags(0, buf, 0);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; kk++) {
-            bf16x8 fa[2], fb[2];
+            if (kk + 1 < BK / 16) read_frags((kk + 1) & 1, buf, kk + 1);
 #pragma unroll
-            for (int i = 0; i < 2; i++) {
-                fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&lds_a[buf][(wm * 64 + i * 32 + frag_row) * LDS_ROW + kk * 16 + frag_k]));
-                fb[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&lds_b[buf][(wn * 64 + i * 32 + frag_row) * LDS_ROW + kk * 16 + frag_k]));
-            }
+            for (int i = 0; i < T; i++)
 #pragma unroll
-            for (int i = 0; i < 2; i++)
-#pragma unroll
-                for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < T; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
         }
         if (kt + 1 < KT) store_tile(buf ^ 1);
         __syncthreads();
@@ -206,13 +219,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint16_t *__restri
     // accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile
     uint16_t *c_blk = C + size_t(tm) * BM * N + size_t(tn) * BN;
 #pragma unroll
-    for (int i = 0; i < 2; i++)
+    for (int i = 0; i < T; i++)
 #pragma unroll
-        for (int j = 0; j < 2; j++)
+        for (int j = 0; j < T; j++)
 #pragma unroll
             for (int r = 0; r < 16; r++) {
-                const int row = wm * 64 + i * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-                const int col = wn * 64 + j * 32 + (lane & 31);
+                const int row = wm * WT + i * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+                const int col = wn * WT + j * 32 + (lane & 31);
                 c_blk[size_t(row) * N + col] = bf16_rne(acc[i][j][r]);
             }
 }
@@ -230,10 +243,15 @@ int hip_rc() { return hipGetLastError() == hipSuccess ? 0 : -4; }
 extern "C" {
 
 int proxy_gemm_bf16(const void *a, const void *b, void *c, int32_t m, int32_t n, int32_t k, void *stream) {
-    if (!a || !b || !c || m <= 0 || n <= 0 || k <= 0 || m % BM || n % BN || k % 64) return -1;
+    if (!a || !b || !c || m <= 0 || n <= 0 || k <= 0 || m % 128 || n % 128 || k % 64) return -1;
     if ((uint64_t(a) | uint64_t(b) | uint64_t(c)) & 15) return -1;
-    hipLaunchKernelGGL(gemm_bf16_kernel, dim3((m / BM) * (n / BN)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint16_t *>(a), static_cast<const uint16_t *>(b), static_cast<uint16_t *>(c), m, n, k);
+    // the 256 x 256 block tile where the shape allows it and there are enough tiles to fill the card
+    if (m % 256 == 0 && n % 256 == 0 && (m / 256) * (n / 256) >= 256)
+        hipLaunchKernelGGL((gemm_bf16_kernel<4, 64>), dim3((m / 256) * (n / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                           static_cast<const uint16_t *>(a), static_cast<const uint16_t *>(b), static_cast<uint16_t *>(c), m, n, k);
+    else
+        hipLaunchKernelGGL((gemm_bf16_kernel<2, 32>), dim3((m / 128) * (n / 128)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                           static_cast<const uint16_t *>(a), static_cast<const uint16_t *>(b), static_cast<uint16_t *>(c), m, n, k);
     return hip_rc();
 }
 

@@ -119,35 +119,17 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
     // The copies further down may block this thread on ring back-pressure; pack launches are
     // therefore enqueued before the copies they do not depend on.
     const uint64_t ahead = s->policy == CKPT_WINDOW_PACK ? c->n_stage : std::min<uint64_t>(c->n_stage, 2);
-    // Which shape of the pack kernel a launch uses (cfg.pack_shape 0): whichever moved a byte in less time in its recent
-    // launches. The times come from the events around every launch, read back here without waiting (launches finish in
-    // order; under the paper's rule the launch two super-chunks back is long over). Both shapes are tried at the start
-    // of every snapshot, and the one not in use again every eighth launch, so that the choice follows the card: beside
-    // the kernels of a forward pass the slim shape wins, once they are over (an update held up by the window) the fat one.
-    c->shape_of_sc.assign(p.n_superchunks, 0);
-    c->shapes_harvested = 0;
-    auto harvest = [&](uint64_t upto) {
-        for (; c->shapes_harvested < upto; c->shapes_harvested++) {
-            const uint64_t j = c->shapes_harvested;
-            if (hipEventQuery(c->ev_packed[j]) != hipSuccess) { (void)hipGetLastError(); break; }
-            float ms = 0;
-            if (hipEventElapsedTime(&ms, c->ev_pack_start[j], c->ev_packed[j]) != hipSuccess || ms <= 0) { (void)hipGetLastError(); continue; }
-            const double v = double(ms) * 1e6 / double(p.superchunk_bytes(j));
-            double &avg = c->shape_ns_per_byte[c->shape_of_sc[j]];
-            avg = avg == 0 ? v : 0.7 * avg + 0.3 * v;
-        }
-    };
-    auto choose_shape = [&](uint64_t sc) -> int {
+    // Which shape of the pack kernel a launch uses (cfg.pack_shape 0): the fat one when the stream the snapshot was
+    // requested on has run dry (nothing of the caller's is executing or waiting there: a snapshot taken at the end of
+    // a run, between phases, or with no training going on), the slim one while that stream still has work, because
+    // beside a training step's kernels only the slim shape finds registers. Asked before every launch: it costs a
+    // host call, and the answer changes in the middle of a snapshot when the caller's work ends.
+    auto choose_shape = [&](uint64_t) -> int {
         if (c->cfg.pack_shape == 1) return 0;
         if (c->cfg.pack_shape == 2) return 1;
-        harvest(sc);
-        if (sc < 2) return int(sc);                       // every snapshot starts with one launch of each shape
-        // the shape in use stays in use unless the other one's recent launches were at least 5 % faster per byte
-        const double *a = c->shape_ns_per_byte;
-        int &cur = c->shape_in_use;
-        if (a[1 - cur] != 0 && (a[cur] == 0 || a[1 - cur] < 0.95 * a[cur])) cur = 1 - cur;
-        if (++c->launches_since_probe >= 32) { c->launches_since_probe = 0; return 1 - cur; }
-        return cur;
+        if (hipStreamQuery(s->stream) == hipSuccess) return 1;
+        (void)hipGetLastError();    // "not ready" is an answer, not an error
+        return 0;
     };
     auto enqueue_pack = [&](uint64_t sc) {
         const uint64_t stage = sc % c->n_stage;
@@ -157,7 +139,6 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
         if ((e = hipEventRecord(c->ev_pack_start[sc], c->pack_stream)) != hipSuccess) hip_fail("record", e);
         const uint64_t t0 = p.sc_first_tile[sc], t1 = p.sc_first_tile[sc + 1];
         const int shape = choose_shape(sc);
-        c->shape_of_sc[sc] = uint8_t(shape);
         s->fat_launches += shape;
         if ((e = launch_pack(s->dev_tiles + t0, t1 - t0, c->staging + stage * SC, sc * SC, shape, c->pack_stream)) != hipSuccess) hip_fail("pack launch", e);
         if ((e = hipEventRecord(c->ev_packed[sc], c->pack_stream)) != hipSuccess) hip_fail("record", e);

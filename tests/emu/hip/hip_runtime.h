@@ -147,6 +147,11 @@ inline hipError_t hipMemGetAddressRange(hipDeviceptr_t *, size_t *, hipDeviceptr
 inline hipError_t hipStreamCreateWithFlags(hipStream_t *s, unsigned) { *s = new EmuStream; return hipSuccess; }
 inline hipError_t hipStreamDestroy(hipStream_t s) { delete s; return hipSuccess; }
 inline hipError_t hipStreamSynchronize(hipStream_t s) { if (s) s->drain(); return hipSuccess; }
+inline hipError_t hipStreamQuery(hipStream_t s) {
+    if (!s) return hipSuccess;
+    std::lock_guard<std::mutex> lk(s->m);
+    return s->done >= s->enqueued ? hipSuccess : 600;   // hipErrorNotReady
+}
 
 inline hipError_t hipEventCreateWithFlags(hipEvent_t *e, unsigned) { *e = new EmuEvent; return hipSuccess; }
 inline hipError_t hipEventCreate(hipEvent_t *e) { return hipEventCreateWithFlags(e, 0); }

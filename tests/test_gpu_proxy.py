@@ -79,7 +79,8 @@ def test_devcopy_exact_with_ragged_size():
     assert np.array_equal(out[:n], src) and np.all(out[n:] == 0xEE)
 
 
-@pytest.mark.parametrize("m,n,k", [(128, 128, 64), (256, 384, 192), (1024, 640, 512)])
+@pytest.mark.parametrize("m,n,k", [(128, 128, 64), (256, 384, 192), (1024, 640, 512),
+                                   (4096, 4096, 64), (4096, 4352, 192), (8192, 4096, 320)])     # the last three take the 256 x 256 block tile
 def test_gemm_bf16_against_float64(m, n, k):
     print(f"gemm {m}x{n}x{k}", flush=True)
     rng = np.random.default_rng(m + n + k)
