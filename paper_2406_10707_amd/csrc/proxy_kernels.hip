@@ -125,16 +125,19 @@ __global__ __launch_bounds__(256) void devcopy_kernel(u32x4 *__restrict__ dst, c
 
 // ------------------------------------------------------------------ bf16 GEMM on the matrix cores
 
-// Block tile (64 T) x (64 T), K step 32, 256 threads = 4 wavefronts in a 2x2 arrangement, each computing a
+// Block tile (64 T) x (64 T), K step BK, 256 threads = 4 wavefronts in a 2x2 arrangement, each computing a
 // (32 T) x (32 T) sub-tile as T x T MFMA 32x32x16 tiles. Both operands are K-contiguous, so an A or B
 // fragment (8 consecutive K values of one row/column per lane) is one 16-byte LDS read. LDS rows are
-// padded from 64 to 80 bytes, which spreads the 16-byte reads of 16 consecutive rows over all banks.
+// padded by 16 bytes (80 bytes for BK = 32, 144 for BK = 64), which spreads the 16-byte reads of 16
+// consecutive rows over all banks.
 //
-// T = 2 (128 x 128 block, 64 accumulator registers per lane, three blocks per CU) is LDS-bound: per MFMA one
-// fragment read, and with the stores of the next tile the LDS pipe is busier than the matrix pipe. T = 4
-// (256 x 256 block, one block per CU, 256 accumulator registers per lane) halves the reads per MFMA: eight
-// fragment reads feed sixteen MFMAs, LDS traffic is about three quarters of the matrix pipe's time, and the
-// next K step's fragments are read while this step's MFMAs run.
+// T = 2, BK = 32 (128 x 128 block, 64 accumulator registers per lane, three blocks per CU) is LDS-bound: per
+// MFMA one fragment read, and with the stores of the next tile the LDS pipe is busier than the matrix pipe.
+// T = 4, BK = 64 (256 x 256 block, 144 KiB of LDS, one block per CU, one wave per SIMD, 256 accumulator
+// registers per lane) halves the reads per MFMA: eight fragment reads feed sixteen MFMAs and LDS traffic is
+// about three quarters of the matrix pipe's time. With one wave per SIMD no other wave hides a wait, so the
+// loop is software-pipelined by hand: the fragments of K slice kk+1 are read while the MFMAs of slice kk run,
+// the next tile's LDS stores go under the last slice's MFMAs, and scheduling fences keep that order.
 template <int T, int BK>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint16_t *__restrict__ A, const uint16_t *__restrict__ B,
                                                        uint16_t *__restrict__ C, int M, int N, int K) {
@@ -200,20 +203,28 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint16_t *__restri
             fb[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&lds_b[buf][(wn * WT + i * 32 + frag_row) * LDS_ROW + kk * 16 + frag_k]));
         }
     };
+    // The scheduler, left alone, sinks every fragment read to just before the MFMA that uses it and waits for it
+    // there: with one wave per SIMD nothing hides that LDS latency. The fences below keep the order written
+    // here: the reads of slice kk+1 are issued, then the MFMAs of slice kk run while those reads are in flight.
+    read_frags(0, 0, 0);
     for (int kt = 0; kt < KT; kt++) {
         const int buf = kt & 1;
         if (kt + 1 < KT) load_tile(kt + 1);
-        read_frags(0, buf, 0);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; kk++) {
             if (kk + 1 < BK / 16) read_frags((kk + 1) & 1, buf, kk + 1);
+            // the next tile goes to the other LDS buffer (whose readers left at the previous barrier) under the
+            // last slice's MFMAs
+            if (kk + 1 == BK / 16 && kt + 1 < KT) store_tile(buf ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < T; i++)
 #pragma unroll
                 for (int j = 0; j < T; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (kt + 1 < KT) store_tile(buf ^ 1);
         __syncthreads();
+        if (kt + 1 < KT) read_frags(0, buf ^ 1, 0);
     }
 
     // accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile
