@@ -232,13 +232,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint16_t *__restri
 #pragma unroll
     for (int i = 0; i < T; i++)
 #pragma unroll
-        for (int j = 0; j < T; j++)
+        for (int j = 0; j < T; j++) {
+#if defined(__HIP_DEVICE_COMPILE__)
+            asm volatile("" : "+a"(acc[i][j]));      // this tile stays in its accumulator registers up to here
+#endif
 #pragma unroll
             for (int r = 0; r < 16; r++) {
                 const int row = wm * WT + i * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
                 const int col = wn * WT + j * 32 + (lane & 31);
                 c_blk[size_t(row) * N + col] = bf16_rne(acc[i][j][r]);
             }
+            // one 32x32 tile at a time: without the pin above and this fence all accumulators are copied out at
+            // once, the kernel then holds 256 + 256 registers per lane and no other wave fits on its SIMD
+            __builtin_amdgcn_sched_barrier(0);
+        }
 }
 
 unsigned blocks_for(uint64_t n, unsigned per_block) {
