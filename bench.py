@@ -157,17 +157,14 @@ def cpu_baseline(harness, shard, sample_bytes, out_dir):
                       % (len(ks), total / 1e9, dt, os.cpu_count())}
 
 
-def traffic_ratio(workload=""):
-    """HBM traffic of the pack kernel over its algorithmic bytes, as measured with rocprofv3 counters: on the
-    benchmark's own workload (profiles/pack_kernel_hbm_traffic_llama7b.txt) when that is the one running,
-    else on the small one (profiles/pack_kernel_hbm_traffic_gpt2small.txt); None when the summary is not there."""
-    name = "pack_kernel_hbm_traffic_llama7b.txt" if workload.startswith("llama-7B") else "pack_kernel_hbm_traffic_gpt2small.txt"
-    try:
-        for line in open(os.path.join(ROOT, "profiles", name)):
+def traffic_ratio(config):
+    """HBM traffic of the pack kernel over its algorithmic bytes on this workload, as measured with rocprofv3
+    counters (profiles/snapshot_path_workload<config>_*.txt, part 3); None when the summary is not there."""
+    import glob
+    for path in glob.glob(os.path.join(ROOT, "profiles", "snapshot_path_workload%d_*.txt" % config)):
+        for line in open(path):
             if line.strip().startswith("traffic_over_algorithmic:"):
                 return float(line.split(":")[1].split()[0])
-    except OSError:
-        pass
     return None
 
 
@@ -634,7 +631,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         iso = gbps(pack_bytes_per_snapshot, tail[0]["pack_ms_sum"])
         result["roofline"]["no_gemm_running"] = {"achieved": round(iso, 1), "frac": round(iso / HBM_PEAK_GBPS, 4),
                                                  "avg_launch_ms": round(tail[0]["pack_ms_sum"] / tail[0]["pack_launches"], 4)}
-    ratio = traffic_ratio(spec.name)
+    ratio = traffic_ratio(args.config)
     if ratio and pack_launches:
         result["roofline"]["traffic"] = round(ratio * result["roofline"]["bytes_per_launch"])
     if tier2_dir:
