@@ -594,7 +594,6 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                      # the call also absorbs that lead; the part the ring causes is the back-pressure time of the submit thread
                      "host_window_wait_ms": round(max(s["host_window_wait_ms"] for s in all_stats), 3) if all_stats else None,
                      "host_backpressure_ms": round(max(s["host_backpressure_ms"] for s in all_stats), 3) if all_stats else None,
-                     "pack_fat_launch_share": round(sum(s["pack_fat_launches"] for s in stats) / max(1, pack_launches), 3) if stats else None,
                      "format_versions": sorted({s["format_version"] for s in all_stats}),
                      "verify_ms": round(statistics.median(s["verify_ms"] for s in all_stats), 3) if pairs and all_stats else None,
                      "flush_gbps": round(statistics.median(S / (s["host_flush_span_ms"] * 1e-3) / 1e9 for s in all_stats), 2) if all_stats else None,

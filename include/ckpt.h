@@ -108,13 +108,7 @@ typedef struct {
                                        device memory and the ring slot, without pack kernel or staging; only smaller
                                        tensors are packed. Needs window_policy CKPT_WINDOW_D2H (the copies read the
                                        tensors themselves). At least 4096 when set. */
-    int32_t pack_shape;             /* which of the pack kernel's two shapes a launch uses. 0 (default): the fat shape when the
-                                       stream the snapshot was requested on has no work left at the moment of the launch,
-                                       the slim shape otherwise. 1: always the slim shape (8 loads per lane in flight, few
-                                       registers: fastest beside the matrix kernels of a training step). 2: always the fat
-                                       shape (a wave's whole tile in flight: fastest on an otherwise idle card). Same bytes
-                                       either way. With 0 the stream handle must stay valid until the snapshot's window is closed. */
-    int32_t reserved[1];            /* must be zero */
+    int32_t reserved[2];            /* must be zero */
 } ckpt_config;
 
 /* Sizes that follow from a tensor list and a configuration. */
@@ -200,7 +194,7 @@ typedef struct {
     double host_io_copy_ms_sum;       /* host: summed over I/O threads, time writing ring slots to the file */
     double host_tier2_ms;             /* host: copy of the committed file to the second tier, open to rename (-1: none yet) */
     int32_t format_version;           /* 1 or 2 (docs/FORMAT.md); 0 while not yet decided */
-    int32_t pack_fat_launches;        /* of pack_launches, how many used the fat kernel shape (ckpt_config.pack_shape) */
+    int32_t reserved0;                /* zero */
     double verify_ms;                 /* device time of the derived-tensor check that decides the version (-1: no pairs declared) */
     double host_window_wait_ms;       /* host: time the caller spent inside ckpt_wait_immutable_window_end for this snapshot */
     double init_d2h_gbps;             /* the context's set-up probe (ckpt_get_init_probe), repeated here */

@@ -17,7 +17,6 @@ CKPT_OK, CKPT_EINVAL, CKPT_ENOMEM, CKPT_EIO, CKPT_EHIP, CKPT_ESTATE, CKPT_EFORMA
 CKPT_BF16, CKPT_F32, CKPT_F16, CKPT_U8, CKPT_I32, CKPT_I64 = 1, 2, 3, 4, 5, 6
 CKPT_WINDOW_D2H, CKPT_WINDOW_PACK = 0, 1
 CKPT_IO_AUTO, CKPT_IO_PWRITE, CKPT_IO_MMAP = 0, 1, 2
-CKPT_PACK_AUTO, CKPT_PACK_SLIM, CKPT_PACK_FAT = 0, 1, 2
 CKPT_ITER_ALL = 0xFFFFFFFFFFFFFFFF
 _STATUS_NAMES = {0: "CKPT_OK", -1: "CKPT_EINVAL", -2: "CKPT_ENOMEM", -3: "CKPT_EIO", -4: "CKPT_EHIP", -5: "CKPT_ESTATE",
                  -6: "CKPT_EFORMAT", -7: "CKPT_EMISMATCH"}
@@ -33,7 +32,7 @@ class ckpt_config(C.Structure):
                 ("dma_chunk_bytes", C.c_uint64), ("pack_superchunk_bytes", C.c_uint64), ("dev_staging_bytes", C.c_uint64),
                 ("n_dma_streams", C.c_int32), ("n_io_threads", C.c_int32), ("window_policy", C.c_int32),
                 ("o_direct", C.c_int32), ("fsync_on_commit", C.c_int32), ("io_mode", C.c_int32), ("keep_last", C.c_int32),
-                ("prealloc_files", C.c_int32), ("direct_min_bytes", C.c_uint64), ("pack_shape", C.c_int32), ("reserved", C.c_int32 * 1)]
+                ("prealloc_files", C.c_int32), ("direct_min_bytes", C.c_uint64), ("reserved", C.c_int32 * 2)]
 
 
 class ckpt_layout(C.Structure):
@@ -64,7 +63,7 @@ class ckpt_stats(C.Structure):
                 ("request_to_pack_end_ms", C.c_double), ("host_submit_ms", C.c_double), ("host_request_to_commit_ms", C.c_double),
                 ("host_backpressure_ms", C.c_double), ("host_snapshot_call_ms", C.c_double),
                 ("host_flush_span_ms", C.c_double), ("host_io_wait_ms_sum", C.c_double), ("host_io_copy_ms_sum", C.c_double),
-                ("host_tier2_ms", C.c_double), ("format_version", C.c_int32), ("pack_fat_launches", C.c_int32), ("verify_ms", C.c_double),
+                ("host_tier2_ms", C.c_double), ("format_version", C.c_int32), ("reserved0", C.c_int32), ("verify_ms", C.c_double),
                 ("host_window_wait_ms", C.c_double), ("init_d2h_gbps", C.c_double)]
 
 CKPT_TIER2_NEWEST, CKPT_TIER2_EVERY = 0, 1
@@ -163,7 +162,7 @@ def _struct_dict(s):
 
 def make_config(out_dir="", device=0, host_ring_bytes=0, dma_chunk_bytes=0, pack_superchunk_bytes=0, dev_staging_bytes=0,
                 n_dma_streams=0, n_io_threads=0, window_policy=CKPT_WINDOW_D2H, o_direct=0, fsync_on_commit=0,
-                io_mode=CKPT_IO_AUTO, keep_last=0, prealloc_files=0, direct_min_bytes=0, pack_shape=0):
+                io_mode=CKPT_IO_AUTO, keep_last=0, prealloc_files=0, direct_min_bytes=0):
     cfg = ckpt_config()
     cfg.device = device
     cfg.out_dir = os.fsencode(out_dir) if out_dir else None
@@ -180,7 +179,6 @@ def make_config(out_dir="", device=0, host_ring_bytes=0, dma_chunk_bytes=0, pack
     cfg.keep_last = keep_last
     cfg.prealloc_files = prealloc_files
     cfg.direct_min_bytes = direct_min_bytes
-    cfg.pack_shape = pack_shape
     return cfg
 
 

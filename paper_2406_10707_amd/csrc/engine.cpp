@@ -405,7 +405,6 @@ int ckpt_snapshot_async(ckpt_ctx *c, uint64_t iter, void *stream) {
     sp->final_path = file_name_for(c->out_dir, iter);
     sp->tmp_path = sp->final_path + ".tmp";
     sp->t_request = t0;
-    sp->stream = static_cast<hipStream_t>(stream);
     if (c->plan.n_host) {   // host memory is not ordered with the stream: read it now, the caller may change it after this call
         sp->host_capture.resize(c->plan.host_bytes);
         for (const auto &t : c->plan.tensors)
@@ -551,7 +550,6 @@ int ckpt_get_stats(ckpt_ctx *c, uint64_t iter, ckpt_stats *o) {
     o->data_bytes = sp.data_bytes;
     o->file_bytes = sp.file_bytes();
     o->format_version = s.plan ? int32_t(s.plan->version) : 0;
-    o->pack_fat_launches = s.fat_launches;
     o->verify_ms = s.verify_ms;
     o->host_window_wait_ms = s.window_wait_ms;
     o->init_d2h_gbps = c->init_d2h_gbps;

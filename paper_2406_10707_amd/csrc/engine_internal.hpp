@@ -30,8 +30,7 @@
 #include "plan.hpp"
 
 namespace dsllm {
-// shape: 0 slim (few registers, finds room beside a training step's kernels), 1 fat (whole tile in flight, fastest alone)
-hipError_t launch_pack(const ckpt_tile *dev_tiles, uint64_t n_tiles, void *slot_base, uint64_t slot_data_off, int shape, hipStream_t stream);
+hipError_t launch_pack(const ckpt_tile *dev_tiles, uint64_t n_tiles, void *slot_base, uint64_t slot_data_off, hipStream_t stream);
 hipError_t launch_scatter(const ckpt_tile *dev_tiles, uint64_t n_tiles, const void *slot_base, uint64_t slot_data_off, hipStream_t stream);
 hipError_t launch_verify_pairs(const PairTile *dev_tiles, uint64_t n_tiles, uint32_t *dev_flag, hipStream_t stream);
 hipError_t launch_derive_pairs(const PairTile *dev_tiles, uint64_t n_tiles, hipStream_t stream);
@@ -81,14 +80,12 @@ struct Snap {
     const Plan *plan = nullptr;
     const ckpt_tile *dev_tiles = nullptr;   // that plan's tile table on the device
     double verify_ms = -1;                  // device time of the derivation check (-1: none)
-    int fat_launches = 0;                   // pack launches of this snapshot that used the fat kernel shape
     double window_wait_ms = 0;              // host: time the caller spent in ckpt_wait_immutable_window_end for this snapshot
     int fd = -1;
     uint8_t *map = nullptr;
     std::string tmp_path, final_path;
     std::atomic<uint64_t> chunks_left{0};
     hipEvent_t ev_boundary = nullptr;
-    hipStream_t stream = nullptr;           // the caller's stream the snapshot was requested on (asked whether it has run dry)
     bool submitted = false, packs_submitted = false, d2h_done = false, committed = false, window_closed = false;
     Clock::time_point t_request, t_submitted, t_committed, t_first_chunk;
     bool have_first_chunk = false;

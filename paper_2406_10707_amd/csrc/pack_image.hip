@@ -61,7 +61,7 @@ int check_pack_arguments(const ckpt_tensor_desc *tensors, size_t n, const void *
 
 // Enqueues, on `stream`, the kernels that write the tile table into `dev_table` (room for n_tiles entries)
 // and then the pack kernel over it. Allocates nothing, on either side.
-int enqueue_pack_image(const ckpt_tensor_desc *tensors, size_t n, void *dev_dst, ckpt_tile *dev_table, uint64_t n_tiles, int shape,
+int enqueue_pack_image(const ckpt_tensor_desc *tensors, size_t n, void *dev_dst, ckpt_tile *dev_table, uint64_t n_tiles,
                        hipStream_t stream) {
     TileBatch bt;
     bt.count = 0;
@@ -81,7 +81,7 @@ int enqueue_pack_image(const ckpt_tensor_desc *tensors, size_t n, void *dev_dst,
         }
     }
     if (tile != n_tiles) return fail(CKPT_EINVAL, "internal: tile count changed between check and launch");
-    HIP_TRY(nullptr, launch_pack(dev_table, n_tiles, dev_dst, 0, shape, stream));
+    HIP_TRY(nullptr, launch_pack(dev_table, n_tiles, dev_dst, 0, stream));
     return CKPT_OK;
 }
 
@@ -129,8 +129,7 @@ int ckpt_pack_image_noalloc(const ckpt_tensor_desc *tensors, size_t n, void *dev
     if (r) return r;
     // every entry the pack kernel reads is written by the table kernels just before it, on the same stream:
     // nothing of the previous call's table has to be cleared
-    // the slim shape: this entry point is for callers whose own kernels are running beside it
-    return enqueue_pack_image(tensors, n, dev_dst, static_cast<ckpt_tile *>(table), n_tiles, 0, static_cast<hipStream_t>(hip_stream));
+    return enqueue_pack_image(tensors, n, dev_dst, static_cast<ckpt_tile *>(table), n_tiles, static_cast<hipStream_t>(hip_stream));
 }
 
 int ckpt_pack_image(const ckpt_tensor_desc *tensors, size_t n, void *dev_dst, uint64_t dst_bytes, void *hip_stream) {
@@ -141,7 +140,7 @@ int ckpt_pack_image(const ckpt_tensor_desc *tensors, size_t n, void *dev_dst, ui
     ckpt_tile *table = nullptr;
     hipError_t e = hipMalloc(reinterpret_cast<void **>(&table), n_tiles * sizeof(ckpt_tile));
     if (e != hipSuccess) return fail(CKPT_ENOMEM, std::string("hipMalloc(tile table): ") + hipGetErrorString(e));
-    r = enqueue_pack_image(tensors, n, dev_dst, table, n_tiles, /*fat: the call waits for the image anyway*/ 1, stream);
+    r = enqueue_pack_image(tensors, n, dev_dst, table, n_tiles, stream);
     hipError_t es = hipStreamSynchronize(stream);   // the table must outlive the kernels that read it
     (void)hipFree(table);
     if (r) return r;

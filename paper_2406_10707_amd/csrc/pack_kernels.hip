@@ -2,14 +2,12 @@
 // contiguous, 4 KiB-aligned staging image of the checkpoint's data region. HBM-bound.
 //
 // One wavefront (64 lanes) walks one tile of the descriptor table: up to 32 KiB of destination,
-// 16 bytes per lane per step, 1 KiB per wavefront step, 8 steps in flight (which keeps the kernel at
-// 64 VGPRs, 8 wavefronts per SIMD); sweeps of tile size, unroll depth and block size on MI355X put
-// this shape at the top for the table-driven kernel (a plain copy without a table is about 5% faster). The staging side is
-// always 16-byte aligned. The tensor side is aligned to its element size only; when it is not
-// 16-byte aligned each lane reads the two aligned 16-byte words that cover its bytes and
-// byte-shifts them together (v_alignbyte), so every global access is an aligned 128-bit one. An
-// aligned 16-byte word that holds at least one byte of a tensor lies in the tensor's page, so those
-// reads stay inside mapped memory; words that hold no byte of the tensor are never read.
+// 16 bytes per lane per step, 1 KiB per wavefront step. The staging side is always 16-byte aligned. The
+// tensor side is aligned to its element size only. The pack kernel reads it with 16-byte vector loads at the
+// tensor's own addresses (the target supports unaligned vector loads), each of which lies wholly inside the
+// tensor; the one word that holds the tensor's last bytes, and everything the scatter kernel writes next to
+// a tensor's edges, is built from aligned 16-byte words and byte shifts (v_alignbyte) or written byte by
+// byte, so nothing outside a tensor is ever read past its 16-byte line or written at all.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -33,23 +31,19 @@ namespace dsllm {
 #ifndef DSLLM_PACK_PRIO
 #define DSLLM_PACK_PRIO 3
 #endif
+// Ten loads in flight need 54 vector registers, which are handed out as 56 (eight need 46, eleven 58 = 64).
+#ifndef DSLLM_PACK_ROLL
+#define DSLLM_PACK_ROLL 10
+#endif
 #ifndef DSLLM_PACK_UNROLL_SHIFT
 #define DSLLM_PACK_UNROLL_SHIFT 4
 #endif
 constexpr uint64_t kPackTileBytes = 32 * 1024;   // the planner's tile size (plan.hpp: kTileBytes)
 constexpr int kWavesPerBlock = DSLLM_PACK_WAVES_PER_BLOCK;
 constexpr int kBlock = 64 * kWavesPerBlock;
-constexpr int kUnroll = DSLLM_PACK_UNROLL;             // slim shape, aligned path: 16-byte words per lane in flight
+constexpr int kUnroll = DSLLM_PACK_UNROLL;             // scatter, aligned path: 16-byte words per lane in flight
+constexpr int kRoll = DSLLM_PACK_ROLL;                 // pack: 16-byte words per lane in flight
 constexpr int kUnrollShift = DSLLM_PACK_UNROLL_SHIFT;  // scatter, misaligned path: pairs of 16-byte words per lane in flight
-
-// The pack kernel comes in two shapes, same bytes out, chosen per launch by the host (launch_pack):
-//  SLIM  8 loads of 16 bytes per lane in flight, 50 vector registers: a wave finds room on a SIMD beside the
-//        register-hungry matrix kernels of a training step, so this is the shape that is fastest while they run.
-//  FAT   the whole tile (32 loads per lane, 32 KiB per wave) in flight before the first store, about 150 registers,
-//        three waves per SIMD: fewer, longer bursts per wave. Fastest when the card has nothing else to do
-//        (measured on the fragmented workload, one launch over 40 GB: 5.86 against 5.18 TB/s), slowest beside a
-//        kernel that leaves it no registers.
-constexpr int kShapeSlim = 0, kShapeFat = 1;
 
 // bytes [sh, sh+16) of the 32-byte string lo||hi, for sh = 4*W + b, 1 <= sh <= 15
 template <int W>
@@ -77,24 +71,55 @@ __device__ __forceinline__ u32x4 keep_bytes(u32x4 v, uint32_t keep) {
 
 // ---------------------------------------------------------------- pack: tensors -> staging
 
-// FAT shape. Output word j (16 bytes, aligned) = the 16 bytes at su + 16 j, for j < n: groups of 32, 16, ... 1 times 64
-// words, every load of a group issued before its first store. su may have any alignment: the target supports
-// unaligned vector loads (a 16-byte load at a 2-byte-aligned address is a single global_load_dwordx4), and all 16
-// bytes of every word lie inside the tensor, so nothing outside it is read.
+// Output word j (16 bytes, aligned) = the 16 bytes at su + 16 j: one group of 64 U words starting at word g, every
+// load of the group issued before its first store. su may have any alignment: the target supports unaligned vector
+// loads (a 16-byte load at a 2-byte-aligned address is a single global_load_dwordx4), and all 16 bytes of every
+// word lie inside the tensor, so nothing outside it is read.
 template <int U>
 __device__ __forceinline__ void copy_group(const uint8_t *su, u32x4 *dst, uint32_t g, uint32_t lane) {
+    // one 64-bit base per side and constant offsets: a 32-bit word index per load would cost an address register pair each
+    const uint8_t *sl = su + 16ull * (g + lane);
+    u32x4 *dl = dst + (g + lane);
     u32x4 v[U];
 #pragma unroll
-    for (int u = 0; u < U; u++) v[u] = ld16_unaligned(su + 16ull * (g + 64 * u + lane));
+    for (int u = 0; u < U; u++) v[u] = ld16_unaligned(sl + 1024 * u);
 #pragma unroll
-    for (int u = 0; u < U; u++) st16(dst + g + 64 * u + lane, v[u]);
+    for (int u = 0; u < U; u++) st16(dl + 64 * u, v[u]);
 }
 
-__device__ __forceinline__ void copy_whole(const uint8_t *su, u32x4 *dst, uint32_t n, uint32_t lane) {
+// Output words [0, n) of a tile from the n words at su (same contract as copy_group). A full tile (2048 words, 32
+// per lane) runs as a rolling pipeline: kRoll loads are issued, then every store is followed at once by the load
+// that reuses its registers, so kRoll loads stay in flight from the first word of the tile to the last instead
+// of draining after every group. The fences keep the compiler from hoisting all loads to the front, which costs
+// a hundred registers more. Shorter tiles (the last tile of a tensor, small tensors) go group by group.
+//
+// Measured on MI355X against a shape that keeps the whole tile (32 loads per lane, 138 registers) in flight:
+// alone on the card the two are within 1 % of each other and of a plain table-free copy kernel (0.75 of the HBM
+// peak on aligned tensors, 0.71 on the fragmented workload); beside a matrix kernel that leaves 64 registers per
+// lane free only this one finds room on the SIMDs (0.71 to 0.74 against 0.45 to 0.55).
+__device__ __forceinline__ void copy_rolling(const uint8_t *su, u32x4 *dst, uint32_t n, uint32_t lane) {
     uint32_t g = 0;
-    for (; g + 64 * 32 <= n; g += 64 * 32) copy_group<32>(su, dst, g, lane);
-    if (g + 64 * 16 <= n) { copy_group<16>(su, dst, g, lane); g += 64 * 16; }
-    if (g + 64 * 8 <= n) { copy_group<8>(su, dst, g, lane); g += 64 * 8; }
+#pragma unroll 1
+    for (; g + 2048 <= n; g += 2048) {
+        const uint8_t *sl = su + 16ull * (g + lane);
+        u32x4 *dl = dst + g + lane;
+        u32x4 v[kRoll];
+#pragma unroll
+        for (int u = 0; u < kRoll; u++) v[u] = ld16_unaligned(sl + 1024 * u);
+#if defined(__HIP_DEVICE_COMPILE__)
+        __builtin_amdgcn_sched_barrier(0);
+#endif
+#pragma unroll
+        for (int k = 0; k < 32; k++) {
+            st16(dl + 64 * k, v[k % kRoll]);
+            if (k + kRoll < 32) v[k % kRoll] = ld16_unaligned(sl + 1024 * (k + kRoll));
+#if defined(__HIP_DEVICE_COMPILE__)
+            __builtin_amdgcn_sched_barrier(0);
+#endif
+        }
+    }
+#pragma unroll 1
+    for (; g + 64 * 8 <= n; g += 64 * 8) copy_group<8>(su, dst, g, lane);
     if (g + 64 * 4 <= n) { copy_group<4>(su, dst, g, lane); g += 64 * 4; }
     if (g + 64 * 2 <= n) { copy_group<2>(su, dst, g, lane); g += 64 * 2; }
     if (g + 64 <= n) { copy_group<1>(su, dst, g, lane); g += 64; }
@@ -102,64 +127,8 @@ __device__ __forceinline__ void copy_whole(const uint8_t *su, u32x4 *dst, uint32
     if (i < n) st16(dst + i, ld16_unaligned(su + 16ull * i));
 }
 
-// The aligned source word that follows this lane's own: lane l takes `cur` of lane l+1, lane 63 takes
-// `nxt` of lane 0 (the first word of the next 64). A register exchange through the LDS crossbar
-// (ds_bpermute, no memory involved) instead of a second, overlapping load: each source word is then
-// fetched once and twice as many distinct words are in flight per wave. `same` points at that word
-// in memory; only the host build (kernel source run lane by lane on the CPU) reads it from there.
-__device__ __forceinline__ u32x4 next_lane_word(u32x4 cur, u32x4 nxt, uint32_t lane, const u32x4 *same) {
-#if defined(__HIP_DEVICE_COMPILE__)
-    const int from = int(((lane + 1) & 63) << 2);
-    const bool first = lane == 0;
-    u32x4 o;
-    o.x = uint32_t(__builtin_amdgcn_ds_bpermute(from, int(first ? nxt.x : cur.x)));
-    o.y = uint32_t(__builtin_amdgcn_ds_bpermute(from, int(first ? nxt.y : cur.y)));
-    o.z = uint32_t(__builtin_amdgcn_ds_bpermute(from, int(first ? nxt.z : cur.z)));
-    o.w = uint32_t(__builtin_amdgcn_ds_bpermute(from, int(first ? nxt.w : cur.w)));
-    return o;
-#else
-    (void)cur; (void)nxt; (void)lane;
-    return *same;
-#endif
-}
-
-// Copies the full 16-byte words of a tile whose source is misaligned by 4*W+b bytes.
-// One group of 64*U consecutive output words starting at word g, all lanes in step: one load per
-// source word, the neighbour's word by exchange. Output word j needs source words j and j+1; j+1 <=
-// n_full always exists (it holds the tensor's tail bytes or, behind the last full word, bytes of the
-// same 16-byte line as the tensor's last byte).
-template <int W, int U>
-__device__ __forceinline__ void pack_shifted_group(const u32x4 *src_al, u32x4 *dst, uint32_t g, uint32_t b, uint32_t lane) {
-    u32x4 w[U], ex = {0, 0, 0, 0};
-#pragma unroll
-    for (int u = 0; u < U; u++) w[u] = ld16(src_al + g + 64 * u + lane);
-    if (lane == 0) ex = ld16(src_al + g + 64 * U);
-#pragma unroll
-    for (int u = 0; u < U; u++) DSLLM_KEEP_WHOLE(w[u]);
-#pragma unroll
-    for (int u = 0; u < U; u++) {
-        const u32x4 hi = next_lane_word(w[u], u + 1 < U ? w[u + 1] : ex, lane, src_al + g + 64 * u + lane + 1);
-        st16(dst + g + 64 * u + lane, funnel<W>(w[u], hi, b));
-    }
-}
-
-// Copies the full 16-byte words of a tile whose source is misaligned by 4*W+b bytes.
-template <int W>
-__device__ __forceinline__ void pack_shifted(const u32x4 *src_al, u32x4 *dst, uint32_t n_full, uint32_t b, uint32_t lane) {
-    static_assert(kUnroll == 8, "the group cascade below is written for 8, 4, 2, 1");
-    uint32_t g = 0;
-    for (; g + 64 * 8 <= n_full; g += 64 * 8) pack_shifted_group<W, 8>(src_al, dst, g, b, lane);
-    if (g + 64 * 4 <= n_full) { pack_shifted_group<W, 4>(src_al, dst, g, b, lane); g += 64 * 4; }
-    if (g + 64 * 2 <= n_full) { pack_shifted_group<W, 2>(src_al, dst, g, b, lane); g += 64 * 2; }
-    if (g + 64 <= n_full) { pack_shifted_group<W, 1>(src_al, dst, g, b, lane); g += 64; }
-    // the last words of the tile (fewer than 64): not every lane has one, so each loads both of its words
-    const uint32_t i = g + lane;
-    if (i < n_full) st16(dst + i, funnel<W>(ld16(src_al + i), ld16(src_al + i + 1), b));
-}
-
 // Output words [lo, hi) of one tile (16-byte words of its destination): source bytes where the tile has them,
 // the masked tail word, zero padding behind it. All lanes of the wave in step; the tile's fields are wave-uniform.
-template <int SHAPE>
 __device__ __forceinline__ void pack_range(uint64_t src, u32x4 *dst, uint32_t copy_bytes, uint32_t total_bytes, uint32_t lo, uint32_t hi,
                                            uint32_t lane) {
     const uint32_t n_total = total_bytes >> 4;   // 16-byte words to write
@@ -174,28 +143,8 @@ __device__ __forceinline__ void pack_range(uint64_t src, u32x4 *dst, uint32_t co
     const u32x4 *s = reinterpret_cast<const u32x4 *>(src - sh); // the aligned words that cover the tile's source bytes
     const uint32_t b = sh & 3;
 
-    if (SHAPE == kShapeFat) {
-        copy_whole(reinterpret_cast<const uint8_t *>(src) + 16ull * lo, dst + lo, n, lane);
-    } else if (sh == 0) {
-        uint32_t i = lo + lane;
-        for (; i + 64 * (kUnroll - 1) < c_hi; i += 64 * kUnroll) {
-            u32x4 v[kUnroll];
-#pragma unroll
-            for (int u = 0; u < kUnroll; u++) v[u] = ld16(s + i + 64 * u);
-#pragma unroll
-            for (int u = 0; u < kUnroll; u++) st16(dst + i + 64 * u, v[u]);
-        }
-        for (; i < c_hi; i += 64) st16(dst + i, ld16(s + i));
-    } else {
-        // the exchange reads aligned source word lo + n as the upper half of the last output word: it exists,
-        // because lo + n <= n_full and word n_full holds tensor bytes (or lies in the line of the last one)
-        switch (sh >> 2) {
-            case 0: pack_shifted<0>(s + lo, dst + lo, n, b, lane); break;
-            case 1: pack_shifted<1>(s + lo, dst + lo, n, b, lane); break;
-            case 2: pack_shifted<2>(s + lo, dst + lo, n, b, lane); break;
-            default: pack_shifted<3>(s + lo, dst + lo, n, b, lane); break;
-        }
-    }
+    // the n words that lie wholly inside the tensor, read at the tensor's own (possibly misaligned) addresses
+    copy_rolling(reinterpret_cast<const uint8_t *>(src) + 16ull * lo, dst + lo, n, lane);
     if (own_tail && lane == 0) {
         // The tail word never comes from an unaligned load (that would read up to 15 bytes past the tensor, possibly
         // into an unmapped page): aligned word n_full holds source bytes, word n_full + 1 only if sh + tail > 16.
@@ -216,7 +165,6 @@ __device__ __forceinline__ void pack_range(uint64_t src, u32x4 *dst, uint32_t co
     for (uint32_t i = (z0 > lo ? z0 : lo) + lane; i < hi; i += 64) st16(dst + i, u32x4{0, 0, 0, 0});
 }
 
-template <int SHAPE>
 __global__ __launch_bounds__(kBlock) void pack_kernel(const ckpt_tile *__restrict__ tiles, uint64_t n_tiles,
                                                      uint8_t *__restrict__ slot_base, uint64_t slot_data_off) {
     const uint32_t lane = threadIdx.x & 63;
@@ -232,7 +180,7 @@ __global__ __launch_bounds__(kBlock) void pack_kernel(const ckpt_tile *__restric
     const uint64_t src = uniform_u64(tp->src);
     const uint64_t dst_off = uniform_u64(tp->dst_off);
     u32x4 *dst = reinterpret_cast<u32x4 *>(slot_base + (dst_off - slot_data_off));
-    pack_range<SHAPE>(src, dst, uniform_u32(tp->copy_bytes), uniform_u32(tp->total_bytes), 0, uint32_t(kPackTileBytes / 16), lane);
+    pack_range(src, dst, uniform_u32(tp->copy_bytes), uniform_u32(tp->total_bytes), 0, uint32_t(kPackTileBytes / 16), lane);
 }
 
 // ---------------------------------------------------------------- scatter: staging -> tensors
@@ -355,14 +303,10 @@ hipError_t launch_build_tiles(const TileBatch &bt, ckpt_tile *dev_table, hipStre
 
 static inline unsigned grid_for(uint64_t n_tiles) { return unsigned((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock); }
 
-hipError_t launch_pack(const ckpt_tile *dev_tiles, uint64_t n_tiles, void *slot_base, uint64_t slot_data_off, int shape, hipStream_t stream) {
+hipError_t launch_pack(const ckpt_tile *dev_tiles, uint64_t n_tiles, void *slot_base, uint64_t slot_data_off, hipStream_t stream) {
     if (n_tiles == 0) return hipSuccess;
-    if (shape == kShapeFat)
-        hipLaunchKernelGGL(pack_kernel<kShapeFat>, dim3(grid_for(n_tiles)), dim3(kBlock), 0, stream, dev_tiles, n_tiles,
-                           static_cast<uint8_t *>(slot_base), slot_data_off);
-    else
-        hipLaunchKernelGGL(pack_kernel<kShapeSlim>, dim3(grid_for(n_tiles)), dim3(kBlock), 0, stream, dev_tiles, n_tiles,
-                           static_cast<uint8_t *>(slot_base), slot_data_off);
+    hipLaunchKernelGGL(pack_kernel, dim3(grid_for(n_tiles)), dim3(kBlock), 0, stream, dev_tiles, n_tiles, static_cast<uint8_t *>(slot_base),
+                       slot_data_off);
     return hipGetLastError();
 }
 

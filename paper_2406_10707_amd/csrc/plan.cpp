@@ -31,8 +31,6 @@ int resolve_config(const ckpt_config *in, ResolvedConfig *out, std::string *err)
     c.keep_last = in->keep_last;
     c.prealloc_files = in->prealloc_files;
     c.direct_min_bytes = in->direct_min_bytes;
-    c.pack_shape = in->pack_shape;
-    if (c.pack_shape < 0 || c.pack_shape > 2) { *err = "config: pack_shape must be 0 (by measurement), 1 (slim) or 2 (fat)"; return CKPT_EINVAL; }
     if (c.direct_min_bytes != 0 && c.direct_min_bytes < kAlign) { *err = "config: direct_min_bytes must be 0 or at least 4096"; return CKPT_EINVAL; }
     if (c.direct_min_bytes != 0 && in->window_policy != CKPT_WINDOW_D2H) { *err = "config: direct_min_bytes needs window_policy CKPT_WINDOW_D2H"; return CKPT_EINVAL; }
     if (c.keep_last < 0 || c.prealloc_files < 0 || c.prealloc_files > 16) { *err = "config: keep_last must be >= 0 and prealloc_files 0..16"; return CKPT_EINVAL; }

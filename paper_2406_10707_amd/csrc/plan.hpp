@@ -45,7 +45,7 @@ struct DerivedPairs {
 
 struct ResolvedConfig {
     uint64_t host_ring_bytes, dma_chunk_bytes, pack_superchunk_bytes, dev_staging_bytes, direct_min_bytes;
-    int n_dma_streams, n_io_threads, window_policy, o_direct, fsync_on_commit, io_mode, keep_last, prealloc_files, pack_shape;
+    int n_dma_streams, n_io_threads, window_policy, o_direct, fsync_on_commit, io_mode, keep_last, prealloc_files;
 };
 
 struct Plan {

@@ -119,18 +119,6 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
     // The copies further down may block this thread on ring back-pressure; pack launches are
     // therefore enqueued before the copies they do not depend on.
     const uint64_t ahead = s->policy == CKPT_WINDOW_PACK ? c->n_stage : std::min<uint64_t>(c->n_stage, 2);
-    // Which shape of the pack kernel a launch uses (cfg.pack_shape 0): the fat one when the stream the snapshot was
-    // requested on has run dry (nothing of the caller's is executing or waiting there: a snapshot taken at the end of
-    // a run, between phases, or with no training going on), the slim one while that stream still has work, because
-    // beside a training step's kernels only the slim shape finds registers. Asked before every launch: it costs a
-    // host call, and the answer changes in the middle of a snapshot when the caller's work ends.
-    auto choose_shape = [&](uint64_t) -> int {
-        if (c->cfg.pack_shape == 1) return 0;
-        if (c->cfg.pack_shape == 2) return 1;
-        if (hipStreamQuery(s->stream) == hipSuccess) return 1;
-        (void)hipGetLastError();    // "not ready" is an answer, not an error
-        return 0;
-    };
     auto enqueue_pack = [&](uint64_t sc) {
         const uint64_t stage = sc % c->n_stage;
         if (sc >= ahead)
@@ -138,9 +126,7 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
                 if ((e = hipStreamWaitEvent(c->pack_stream, c->ev_stage_done[(sc - ahead) % c->n_stage][k], 0)) != hipSuccess) hip_fail("wait stage", e);
         if ((e = hipEventRecord(c->ev_pack_start[sc], c->pack_stream)) != hipSuccess) hip_fail("record", e);
         const uint64_t t0 = p.sc_first_tile[sc], t1 = p.sc_first_tile[sc + 1];
-        const int shape = choose_shape(sc);
-        s->fat_launches += shape;
-        if ((e = launch_pack(s->dev_tiles + t0, t1 - t0, c->staging + stage * SC, sc * SC, shape, c->pack_stream)) != hipSuccess) hip_fail("pack launch", e);
+        if ((e = launch_pack(s->dev_tiles + t0, t1 - t0, c->staging + stage * SC, sc * SC, c->pack_stream)) != hipSuccess) hip_fail("pack launch", e);
         if ((e = hipEventRecord(c->ev_packed[sc], c->pack_stream)) != hipSuccess) hip_fail("record", e);
         if (sc + 1 == p.n_superchunks) {   // every read of the tensors is now in the pack stream
             std::lock_guard<std::mutex> lk(c->mu);

@@ -100,20 +100,20 @@ int main(int argc, char **argv) {
     std::vector<uint8_t> want(p.data_bytes, 0);
     for (size_t k = 0; k < hulls.size(); k++) memcpy(&want[p.tensors[k].file_off - p.header_bytes], hulls[k].base + hulls[k].lead, hulls[k].nbytes);
 
-    // pack super-chunk by super-chunk into an exactly sized slot, once with each shape of the kernel
-    for (int shape = 0; shape < 2; shape++) {
+    // pack super-chunk by super-chunk into an exactly sized slot
+    {
     std::vector<uint8_t> image(p.data_bytes);
     for (uint64_t sc = 0; sc < p.n_superchunks; sc++) {
         uint64_t bytes = p.superchunk_bytes(sc);
         uint8_t *slot = static_cast<uint8_t *>(aligned_alloc(16, bytes));
         memset(slot, 0xCC, bytes);
         uint64_t t0 = p.sc_first_tile[sc], t1 = p.sc_first_tile[sc + 1];
-        launch_pack(p.tiles.data() + t0, t1 - t0, slot, sc * SC, shape, nullptr);
+        launch_pack(p.tiles.data() + t0, t1 - t0, slot, sc * SC, nullptr);
         memcpy(&image[sc * SC], slot, bytes);
         free(slot);
     }
     if (image != want) {
-        for (uint64_t i = 0; i < p.data_bytes; i++) if (image[i] != want[i]) { printf("pack mismatch (shape %d) at data offset %llu\n", shape, (unsigned long long)i); break; }
+        for (uint64_t i = 0; i < p.data_bytes; i++) if (image[i] != want[i]) { printf("pack mismatch at data offset %llu\n", (unsigned long long)i); break; }
         return 1;
     }
     }

@@ -36,16 +36,17 @@ def test_image_equals_the_oracles_data_region(config):
 
 
 def test_image_of_edge_sizes_and_every_misalignment():
-    """Sizes around every internal boundary (16 B word, 4 KiB unit, 32 KiB tile) at every byte misalignment
-    0..15 of the source, several tiles and a ragged tail each, more tensors than one descriptor batch holds."""
-    sizes = [1, 2, 15, 16, 17, 4095, 4096, 4097, 32767, 32768, 32769, 65535, 100000, 3 * 32768 + 5]
+    """Sizes around every internal boundary (16 B word, 4 KiB unit, 32 KiB tile: whole tiles take the kernel's rolling
+    pipeline, shorter ones its group cascade and the masked tail word), each at every byte misalignment 0..15 of the
+    source, several tiles and a ragged tail each, more tensors than one descriptor batch holds."""
+    sizes = [1, 2, 15, 16, 17, 4095, 4096, 4097, 32767, 32768, 32769, 65535, 65536, 100000, 3 * 32768 + 5, 32768 + 16 * 64 * 15 + 16 * 37 + 3]
     tensors, off = [], 0
-    for rep in range(8):
-        for i, n in enumerate(sizes):
-            off += (rep * len(sizes) + i) % 16 + 1
-            tensors.append(shards.TensorSpec(f"e{rep}_{i}", shards.U8, (n,), buffer=0, offset=off, role="raw"))
+    for i, n in enumerate(sizes):
+        for m in range(16):
+            off = (off + 15) // 16 * 16 + m
+            tensors.append(shards.TensorSpec(f"e{i}_{m}", shards.U8, (n,), buffer=0, offset=off, role="raw"))
             off += n
-    assert len(tensors) > 96 and {t.offset % 16 for t in tensors} == set(range(16))
+    assert len(tensors) > 96 and all(t.offset % 16 == k % 16 for k, t in enumerate(tensors))
     spec = shards.ShardSpec("edges", 5, tensors, flat_buffers=[(off + 255) // 256 * 256])
     shard = harness.DeviceShard(spec)
     stream = harness.Stream()

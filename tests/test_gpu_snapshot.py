@@ -63,36 +63,6 @@ def test_tiny_shard_file_equals_oracle(config, policy, tmp_path):
     ck.destroy()
 
 
-@pytest.mark.parametrize("shape", [B.CKPT_PACK_AUTO, B.CKPT_PACK_SLIM, B.CKPT_PACK_FAT], ids=["auto", "slim", "fat"])
-@pytest.mark.parametrize("config", [1, 5])
-def test_both_shapes_of_the_pack_kernel_write_the_oracles_file(config, shape, tmp_path):
-    """The pack kernel has a slim and a fat shape (few registers against the whole tile in flight); whichever a launch
-    uses, forced or chosen by the state of the caller's stream, the file is the oracle's, and the statistics say which shape ran."""
-    _say(f"pack shape {shape} config {config}")
-    spec = shards.make_shard(config, tiny=True)
-    shard = harness.DeviceShard(spec)
-    shard.upload_host_values()
-    stream = harness.Stream()
-    ck = B.Checkpointer(B.make_config(out_dir=str(tmp_path), pack_shape=shape, **SMALL))
-    ck.register_tensors(shard.descs())
-    host = [shards.host_values(spec, k) for k in range(len(spec.tensors))]
-    for it in (1, 2, 3):
-        ck.snapshot_async(it, stream.cuda_stream)
-        ck.flush(it)
-        assert open(ck.file_name(it), "rb").read() == oracle.serialize_bytes(shard.oracle_tensors(host), it)
-        st = ck.stats(it)
-        if shape == B.CKPT_PACK_SLIM:
-            assert st["pack_fat_launches"] == 0
-        elif shape == B.CKPT_PACK_FAT:
-            assert st["pack_fat_launches"] == st["pack_launches"]
-        else:
-            assert st["pack_fat_launches"] == st["pack_launches"]            # the stream has nothing else to do here: fat
-    with pytest.raises(B.CkptError) as e:
-        B.Checkpointer(B.make_config(out_dir=str(tmp_path), pack_shape=3))
-    assert e.value.code == B.CKPT_EINVAL
-    ck.destroy()
-
-
 @pytest.mark.parametrize("mode", ["pwrite", "o_direct", "mmap+fsync"])
 def test_sink_modes_write_the_same_file(mode, tmp_path):
     _say(f"sink mode {mode}")
