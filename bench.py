@@ -40,7 +40,7 @@ def parse_args():
     ap.add_argument("--compute-ms", type=float, default=0.0, help="0: the workload's own forward+backward length")
     ap.add_argument("--ring-gib", type=float, default=0.0, help="0: the whole data region, at most 16 GiB")
     ap.add_argument("--staging-gib", type=float, default=0.0, help="0: two super-chunks")
-    ap.add_argument("--chunk-mib", type=int, default=64)
+    ap.add_argument("--chunk-mib", type=int, default=256)
     ap.add_argument("--superchunk-mib", type=int, default=1024)
     ap.add_argument("--dma-streams", type=int, default=2)
     ap.add_argument("--io-threads", type=int, default=6)

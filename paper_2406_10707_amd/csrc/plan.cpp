@@ -18,7 +18,7 @@ uint64_t dtype_size(int32_t dtype) {
 
 int resolve_config(const ckpt_config *in, ResolvedConfig *out, std::string *err) {
     ResolvedConfig c;
-    c.dma_chunk_bytes = in->dma_chunk_bytes ? in->dma_chunk_bytes : (64ull << 20);
+    c.dma_chunk_bytes = in->dma_chunk_bytes ? in->dma_chunk_bytes : (256ull << 20);
     c.pack_superchunk_bytes = in->pack_superchunk_bytes ? in->pack_superchunk_bytes : (1ull << 30);
     c.host_ring_bytes = in->host_ring_bytes ? in->host_ring_bytes : (8ull << 30);
     c.dev_staging_bytes = in->dev_staging_bytes ? in->dev_staging_bytes : 2 * c.pack_superchunk_bytes;

@@ -55,7 +55,7 @@ def main():
             peak = max(peak, n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
         del d, h
         data_upper = spec.payload_bytes + 4096 * len(spec.tensors)
-        chunk = 64 << 20
+        chunk = 256 << 20
         ring = min(16 << 30, -(-data_upper // chunk) * chunk)
         ck = B.Checkpointer(B.make_config(out_dir=out_dir, host_ring_bytes=ring, dma_chunk_bytes=chunk, n_io_threads=6, keep_last=1,
                                           prealloc_files=2))

@@ -161,7 +161,7 @@ def test_full_size_llama7b_version_2():
         stream = harness.Stream()
         shard.fill_device(stream)
         shard.update(1, stream)
-        ck = B.Checkpointer(B.make_config(out_dir=d, host_ring_bytes=16 << 30, dma_chunk_bytes=64 << 20, pack_superchunk_bytes=1 << 30,
+        ck = B.Checkpointer(B.make_config(out_dir=d, host_ring_bytes=16 << 30, dma_chunk_bytes=256 << 20, pack_superchunk_bytes=1 << 30,
                                           n_dma_streams=2, n_io_threads=12, keep_last=1))
         ck.declare_derived(pairs)
         ck.register_tensors(shard.descs())

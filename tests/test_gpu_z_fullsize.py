@@ -89,7 +89,7 @@ def _poison(shard, stream, byte=0xA5):
 
 
 def _config(d, direct_min=0, keep_last=1):
-    return B.make_config(out_dir=d, host_ring_bytes=16 << 30, dma_chunk_bytes=64 << 20, pack_superchunk_bytes=1 << 30,
+    return B.make_config(out_dir=d, host_ring_bytes=16 << 30, dma_chunk_bytes=256 << 20, pack_superchunk_bytes=1 << 30,
                          n_dma_streams=2, n_io_threads=12, keep_last=keep_last, direct_min_bytes=direct_min)
 
 

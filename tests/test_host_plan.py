@@ -225,7 +225,7 @@ def test_full_size_tile_counts():
     descs, _ = _fake_descs(spec)
     plan = B.Plan(descs)
     lay = plan.layout()
-    assert lay["n_superchunks"] == -(-lay["data_bytes"] // (1 << 30)) and lay["n_chunks"] == -(-lay["data_bytes"] // (64 << 20))
+    assert lay["n_superchunks"] == -(-lay["data_bytes"] // (1 << 30)) and lay["n_chunks"] == -(-lay["data_bytes"] // (256 << 20))   # the defaults: 1 GiB per pack launch, 256 MiB per copy
     assert lay["data_bytes"] // lay["tile_bytes"] <= lay["n_tiles"] <= lay["data_bytes"] // lay["tile_bytes"] + 2 * lay["n_tensors"]
     plan.close()
 
