@@ -370,7 +370,7 @@ int ckpt_pack_image_noalloc(const ckpt_tensor_desc *tensors, size_t n, void *dev
 
 int ckpt_get_layout(ckpt_ctx *ctx, ckpt_layout *out);
 /* ckpt_init copies one ring slot's worth (at most 64 MiB) from device memory into the pinned ring on a copy
- * stream and times it: *d2h_gbps is that rate in GB/s (-1 if it could not be measured). The paper's design rests on
+ * stream (once untimed, then the best of three timed): *d2h_gbps is that rate in GB/s (-1 if it could not be measured). The paper's design rests on
  * a copy engine that moves checkpoints without taking compute resources from training; whether the copies of
  * this process go that way is a property of the HIP runtime it has loaded. On MI355X the system runtime reaches
  * about 56 GB/s here; a figure far below the link's rate means the runtime executes copies with kernels on the
