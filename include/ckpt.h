@@ -82,7 +82,10 @@ typedef struct {
                                        only: one directory per context (per GPU, per rank) */
     uint64_t host_ring_bytes;       /* pinned host ring; the paper's one knob. default 8 GiB; rounded down to
                                        whole DMA chunks, at least 2 chunks */
-    uint64_t dma_chunk_bytes;       /* one device-to-host copy and one ring slot. default 256 MiB; multiple of 32 KiB */
+    uint64_t dma_chunk_bytes;       /* one device-to-host copy and one ring slot. default 256 MiB; multiple of 32 KiB.
+                                       Larger copies come closer to the link's rate (copies run one after the other with
+                                       a fixed gap between two); smaller ones start the pipeline sooner, which a shard
+                                       of only a few GB notices (64 MiB suits those) */
     uint64_t pack_superchunk_bytes; /* bytes one pack launch produces. default 1 GiB; multiple of dma_chunk_bytes */
     uint64_t dev_staging_bytes;     /* device staging; default 2 super-chunks; rounded down to whole super-chunks, at least 2
                                        (or the whole data region when that is smaller) */
