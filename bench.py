@@ -353,6 +353,8 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
                 os.unlink(ck.file_name(it))
                 live_files.remove(it)
 
+    baseline_trace = []      # per-step times of every no-checkpoint phase, for --dump
+
     def baseline_phase(n, library_calls=False):
         """Same steps with checkpointing off: (median step ms, median GEMM-phase ms). After an idle period
         the card runs a few per cent faster for some seconds, so the first ~4 s of steps are discarded.
@@ -362,6 +364,9 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
         for i in range(skip + n):
             iteration(1000000 + i, library_calls, marks, snap=False)
         stream.synchronize()
+        baseline_trace.append({"library_calls": library_calls, "discarded": skip,
+                               "iter_ms": [round(m[0].elapsed_time(m[2]), 3) for m in marks],
+                               "gemm_ms": [round(m[0].elapsed_time(m[1]), 3) for m in marks]})
         return (statistics.median(m[0].elapsed_time(m[2]) for m in marks[skip:]),
                 statistics.median(m[0].elapsed_time(m[1]) for m in marks[skip:]))
 
@@ -621,7 +626,7 @@ def run(args, B, harness, spec, every, compute_ms, out_dir):
     if args.dump:
         with open(args.dump, "w") as f:
             json.dump({"main": main, "variant": variant, "requested": requested, "snapshots": all_stats,
-                       "baseline_iter_ms": base_iter_ms, "baseline_gemm_ms": base_gemm_ms}, f, indent=1)
+                       "baseline_iter_ms": base_iter_ms, "baseline_gemm_ms": base_gemm_ms, "baseline_phases": baseline_trace}, f, indent=1)
 
     # the same kernel without a GEMM competing for the CUs: the snapshot requested by the last timed step
     # (its pack launches run while the host waits for the device at the end of the region)

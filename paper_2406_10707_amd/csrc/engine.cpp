@@ -238,7 +238,8 @@ int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out) {
     }
     for (int k = 0; k < kBoundaryEvents; k++) {   // one per snapshot in flight; none is created on the per-iteration path
         hipEvent_t ev;
-        if ((e = hipEventCreate(&ev)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
+        // blocking: the submit thread sleeps on a boundary until the device reaches it
+        if ((e = hipEventCreateWithFlags(&ev, hipEventBlockingSync)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));
         c->ev_boundary_free.push_back(ev);
     }
     if ((e = hipEventCreate(&c->ev_first_copy)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));

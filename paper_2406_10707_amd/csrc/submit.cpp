@@ -30,7 +30,14 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
         }
     }
 
-    // everything below comes after the boundary on the device timeline
+    // Everything below comes after the boundary on the device timeline. This thread first waits, on the host, until
+    // the device has reached the boundary, and only then enqueues the snapshot's kernels and copies. A caller's
+    // host thread may be whole steps ahead of its device; work enqueued at request time would sit behind an
+    // unsignalled event at the head of the pack and copy queues all that while, and the command processor pays
+    // for blocked queues on every dispatch of the caller's own stream: measured, 12 to 20 us per kernel launch, which
+    // made every step between a request and its boundary 1.7 % slower (the Adam phase of the 7B workload 42.1
+    // instead of 36.2 ms, its GEMM phase +1.1 %). The device-side wait below stays as the ordering guarantee.
+    if ((e = hipEventSynchronize(s->ev_boundary)) != hipSuccess) hip_fail("boundary sync", e);
     if ((e = hipStreamWaitEvent(c->pack_stream, s->ev_boundary, 0)) != hipSuccess) hip_fail("wait boundary", e);
 
     // Data reduction: with derived tensors declared, the captured state is checked on the device first (every bf16
