@@ -359,7 +359,7 @@ int ckpt_register_tensors(ckpt_ctx *c, const ckpt_tensor_desc *tensors, size_t n
     for (uint64_t s = 0; s < c->n_stage; s++)
         for (size_t k = 0; k < c->dma.size(); k++) {
             hipEvent_t ev;
-            HIP_TRY(c, hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+            HIP_TRY(c, hipEventCreateWithFlags(&ev, hipEventDisableTiming | hipEventBlockingSync));   // the submit thread sleeps on these
             c->ev_stage_done[s].push_back(ev);
         }
     if (posix_memalign(reinterpret_cast<void **>(&c->hdr_buf), 4096, std::max(p.header_bytes, reduce ? rp.header_bytes : 0)) != 0) return fail(CKPT_ENOMEM, "header buffer");

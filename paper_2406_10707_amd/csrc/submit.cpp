@@ -118,19 +118,22 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
         for (size_t k = 0; k < nk; k++)
             if ((e = hipStreamWaitEvent(c->dma[k], s->ev_boundary, 0)) != hipSuccess) hip_fail("wait boundary", e);
     double bp_ms = 0;
-    // Pack launches run `ahead` super-chunks in front of the copies: as far as staging allows when the
-    // window closes with the last pack (policy PACK: get the reads of the tensors over with), two
-    // otherwise (under the paper's rule nothing is gained by packing earlier, and a burst of pack
-    // kernels would only compete with the forward pass). Pack sc waits, on the device, for the copies of
-    // super-chunk sc - ahead, which also frees its staging slot (ahead <= n_stage, copies are in order).
-    // The copies further down may block this thread on ring back-pressure; pack launches are
-    // therefore enqueued before the copies they do not depend on.
+    // Pack launches run ahead of the copies: as far as staging allows when the window closes with the last pack
+    // (policy PACK: get the reads of the tensors over with), `ahead` = two staging slots otherwise (under the
+    // paper's rule nothing is gained by packing earlier, and a burst of pack kernels would only compete with the
+    // forward pass). Pack sc needs the staging slot that the copies of super-chunk sc - ahead read (ahead <= n_stage,
+    // copies are in order): this thread waits for those copies on the host and launches the pack then.
     const uint64_t ahead = s->policy == CKPT_WINDOW_PACK ? c->n_stage : std::min<uint64_t>(c->n_stage, 2);
     auto enqueue_pack = [&](uint64_t sc) {
         const uint64_t stage = sc % c->n_stage;
         if (sc >= ahead)
-            for (size_t k = 0; k < nk; k++)
-                if ((e = hipStreamWaitEvent(c->pack_stream, c->ev_stage_done[(sc - ahead) % c->n_stage][k], 0)) != hipSuccess) hip_fail("wait stage", e);
+            for (size_t k = 0; k < nk; k++) {
+                // host first (this thread sleeps until the staging slot is free), so that the pack queue never holds a
+                // launch parked behind an unsignalled event while the copies run: see the boundary wait above.
+                hipEvent_t freed = c->ev_stage_done[(sc - ahead) % c->n_stage][k];
+                if ((e = hipEventSynchronize(freed)) != hipSuccess) hip_fail("stage sync", e);
+                if ((e = hipStreamWaitEvent(c->pack_stream, freed, 0)) != hipSuccess) hip_fail("wait stage", e);
+            }
         if ((e = hipEventRecord(c->ev_pack_start[sc], c->pack_stream)) != hipSuccess) hip_fail("record", e);
         const uint64_t t0 = p.sc_first_tile[sc], t1 = p.sc_first_tile[sc + 1];
         if ((e = launch_pack(s->dev_tiles + t0, t1 - t0, c->staging + stage * SC, sc * SC, c->pack_stream)) != hipSuccess) hip_fail("pack launch", e);
@@ -202,7 +205,10 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
             }
             c->cv_io.notify_one();
         }
-        if (sc + ahead < p.n_superchunks) enqueue_pack(sc + ahead);
+        // The next pack launch goes out one round late, after this super-chunk's copies have been enqueued: its host-side
+        // wait is for the copies of the previous super-chunk, and the copy engines have this one's to go on with. The
+        // pack of super-chunk sc + 1 was launched a round ago, before the copies above that wait for it.
+        if (sc >= 1 && sc - 1 + ahead < p.n_superchunks) enqueue_pack(sc - 1 + ahead);
     }
     std::vector<uint8_t>().swap(s->host_capture);   // every byte of it is in a ring slot by now
     std::lock_guard<std::mutex> lk(c->mu);
