@@ -349,11 +349,13 @@ int ckpt_register_tensors(ckpt_ctx *c, const ckpt_tensor_desc *tensors, size_t n
         HIP_TRY(c, hipEventCreate(&c->ev_derived));
     }
     for (uint64_t s = 0; s < p.n_superchunks; s++) {
-        hipEvent_t a, b;
+        hipEvent_t a, b, d;
         HIP_TRY(c, hipEventCreate(&a));
         HIP_TRY(c, hipEventCreate(&b));
+        HIP_TRY(c, hipEventCreate(&d));
         c->ev_pack_start.push_back(a);
         c->ev_packed.push_back(b);
+        c->ev_pack_end.push_back(d);
     }
     c->ev_stage_done.resize(c->n_stage);
     for (uint64_t s = 0; s < c->n_stage; s++)
@@ -624,6 +626,7 @@ int ckpt_destroy(ckpt_ctx *c) {
     for (auto ev : c->ev_slot) (void)hipEventDestroy(ev);
     for (auto ev : c->ev_pack_start) (void)hipEventDestroy(ev);
     for (auto ev : c->ev_packed) (void)hipEventDestroy(ev);
+    for (auto ev : c->ev_pack_end) (void)hipEventDestroy(ev);
     for (auto &v : c->ev_stage_done) for (auto ev : v) (void)hipEventDestroy(ev);
     for (auto ev : c->ev_job_tail) (void)hipEventDestroy(ev);
     if (c->ev_first_copy) (void)hipEventDestroy(c->ev_first_copy);

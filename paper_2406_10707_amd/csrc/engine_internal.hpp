@@ -30,7 +30,9 @@
 #include "plan.hpp"
 
 namespace dsllm {
-hipError_t launch_pack(const ckpt_tile *dev_tiles, uint64_t n_tiles, void *slot_base, uint64_t slot_data_off, hipStream_t stream);
+// t_start / t_stop (each may be null): events that receive the kernel's own start and end time
+hipError_t launch_pack(const ckpt_tile *dev_tiles, uint64_t n_tiles, void *slot_base, uint64_t slot_data_off, hipStream_t stream,
+                       hipEvent_t t_start = nullptr, hipEvent_t t_stop = nullptr);
 hipError_t launch_scatter(const ckpt_tile *dev_tiles, uint64_t n_tiles, const void *slot_base, uint64_t slot_data_off, hipStream_t stream);
 hipError_t launch_verify_pairs(const PairTile *dev_tiles, uint64_t n_tiles, uint32_t *dev_flag, hipStream_t stream);
 hipError_t launch_derive_pairs(const PairTile *dev_tiles, uint64_t n_tiles, hipStream_t stream);
@@ -143,7 +145,7 @@ struct ckpt_ctx {
     hipStream_t pack_stream = nullptr;
     std::vector<hipStream_t> dma;
     std::vector<hipEvent_t> ev_slot;                      // per ring slot: copy into/out of the slot done
-    std::vector<hipEvent_t> ev_pack_start, ev_packed;     // per super-chunk
+    std::vector<hipEvent_t> ev_pack_start, ev_pack_end, ev_packed;   // per super-chunk: the kernel's start and end (timing), its completion in the pack stream (ordering)
     std::vector<std::vector<hipEvent_t>> ev_stage_done;   // [stage slot][dma stream]
     std::vector<hipEvent_t> ev_job_tail;                  // per dma stream
     hipEvent_t ev_first_copy = nullptr, ev_user = nullptr;

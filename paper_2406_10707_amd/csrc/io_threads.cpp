@@ -11,7 +11,7 @@ static void finish_d2h_stats(ckpt_ctx *c, Snap *s) {
     float ms = 0;
     const uint64_t n_sc = s->plan->n_superchunks;
     for (uint64_t i = 0; i < n_sc; i++)
-        if (hipEventElapsedTime(&ms, c->ev_pack_start[i], c->ev_packed[i]) == hipSuccess) pack_sum += ms;
+        if (hipEventElapsedTime(&ms, c->ev_pack_start[i], c->ev_pack_end[i]) == hipSuccess) pack_sum += ms;
     for (size_t k = 0; k < c->dma.size(); k++) {
         if (hipEventElapsedTime(&ms, s->ev_boundary, c->ev_job_tail[k]) == hipSuccess && ms > req_d2h) req_d2h = ms;
         if (hipEventElapsedTime(&ms, c->ev_first_copy, c->ev_job_tail[k]) == hipSuccess && ms > span) span = ms;

@@ -9,6 +9,7 @@
 // a tensor's edges, is built from aligned 16-byte words and byte shifts (v_alignbyte) or written byte by
 // byte, so nothing outside a tensor is ever read past its 16-byte line or written at all.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/ckpt.h"
@@ -303,10 +304,15 @@ hipError_t launch_build_tiles(const TileBatch &bt, ckpt_tile *dev_table, hipStre
 
 static inline unsigned grid_for(uint64_t n_tiles) { return unsigned((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock); }
 
-hipError_t launch_pack(const ckpt_tile *dev_tiles, uint64_t n_tiles, void *slot_base, uint64_t slot_data_off, hipStream_t stream) {
+hipError_t launch_pack(const ckpt_tile *dev_tiles, uint64_t n_tiles, void *slot_base, uint64_t slot_data_off, hipStream_t stream,
+                       hipEvent_t t_start, hipEvent_t t_stop) {
     if (n_tiles == 0) return hipSuccess;
-    hipLaunchKernelGGL(pack_kernel, dim3(grid_for(n_tiles)), dim3(kBlock), 0, stream, dev_tiles, n_tiles, static_cast<uint8_t *>(slot_base),
-                       slot_data_off);
+    if (t_start || t_stop)   // the events take the kernel's own start and end, not the moments two host calls around it were processed
+        hipExtLaunchKernelGGL(pack_kernel, dim3(grid_for(n_tiles)), dim3(kBlock), 0, stream, t_start, t_stop, 0, dev_tiles, n_tiles,
+                              static_cast<uint8_t *>(slot_base), slot_data_off);
+    else
+        hipLaunchKernelGGL(pack_kernel, dim3(grid_for(n_tiles)), dim3(kBlock), 0, stream, dev_tiles, n_tiles, static_cast<uint8_t *>(slot_base),
+                           slot_data_off);
     return hipGetLastError();
 }
 

@@ -134,9 +134,9 @@ static void submit_one(ckpt_ctx *c, const std::shared_ptr<Snap> &sp) {
                 if ((e = hipEventSynchronize(freed)) != hipSuccess) hip_fail("stage sync", e);
                 if ((e = hipStreamWaitEvent(c->pack_stream, freed, 0)) != hipSuccess) hip_fail("wait stage", e);
             }
-        if ((e = hipEventRecord(c->ev_pack_start[sc], c->pack_stream)) != hipSuccess) hip_fail("record", e);
         const uint64_t t0 = p.sc_first_tile[sc], t1 = p.sc_first_tile[sc + 1];
-        if ((e = launch_pack(s->dev_tiles + t0, t1 - t0, c->staging + stage * SC, sc * SC, c->pack_stream)) != hipSuccess) hip_fail("pack launch", e);
+        if ((e = launch_pack(s->dev_tiles + t0, t1 - t0, c->staging + stage * SC, sc * SC, c->pack_stream, c->ev_pack_start[sc], c->ev_pack_end[sc])) != hipSuccess)
+            hip_fail("pack launch", e);
         if ((e = hipEventRecord(c->ev_packed[sc], c->pack_stream)) != hipSuccess) hip_fail("record", e);
         if (sc + 1 == p.n_superchunks) {   // every read of the tensors is now in the pack stream
             std::lock_guard<std::mutex> lk(c->mu);

@@ -108,7 +108,7 @@ int main(int argc, char **argv) {
         uint8_t *slot = static_cast<uint8_t *>(aligned_alloc(16, bytes));
         memset(slot, 0xCC, bytes);
         uint64_t t0 = p.sc_first_tile[sc], t1 = p.sc_first_tile[sc + 1];
-        launch_pack(p.tiles.data() + t0, t1 - t0, slot, sc * SC, nullptr);
+        launch_pack(p.tiles.data() + t0, t1 - t0, slot, sc * SC, nullptr, nullptr, nullptr);
         memcpy(&image[sc * SC], slot, bytes);
         free(slot);
     }

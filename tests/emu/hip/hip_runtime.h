@@ -219,3 +219,10 @@ static inline void emu_run_grid(dim3 grid, dim3 block, F body) {
 // queued on the stream like any other operation (arguments captured by value)
 #define hipLaunchKernelGGL(kernel, grid, block, shmem, stream, ...) \
     emu_submit(stream, [=] { emu_run_grid(grid, block, [&] { kernel(__VA_ARGS__); }); })
+// the launch that also fills a start and a stop event: here the events are recorded around the launch
+#define hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, start_ev, stop_ev, flags, ...)          \
+    do {                                                                                                  \
+        if (start_ev) (void)hipEventRecord(start_ev, stream);                                             \
+        hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                              \
+        if (stop_ev) (void)hipEventRecord(stop_ev, stream);                                               \
+    } while (0)
