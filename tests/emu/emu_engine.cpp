@@ -315,6 +315,90 @@ static int failed_chunk_scenario(const std::string &dir, int keep_last) {
     return 0;
 }
 
+// ---- nothing is enqueued before the boundary: the caller's host is ahead of its device (the stream still has a long
+// forward pass to run when the snapshot is requested). Until the device reaches the boundary the library must not put
+// anything on its own streams: work parked behind an unsignalled event slows every launch of the caller (measured on
+// the GPU). Then the snapshot proceeds and the file is the state at the boundary.
+static hipStream_t g_callers_stream = nullptr;
+static std::atomic<bool> g_boundary_held{false};
+static std::atomic<int> g_early_submissions{0};
+static void count_early(hipStream_t s) { if (g_boundary_held.load() && s != g_callers_stream) g_early_submissions++; }
+
+static int held_boundary_scenario(const std::string &dir, int policy) {
+    std::string what = "held boundary, policy " + std::to_string(policy);
+    std::vector<Tensor> ts;
+    for (int k = 0; k < 20; k++) {
+        Tensor t;
+        t.lead = (5 * k) % 16;
+        t.nbytes = 30000 + 6101 * k;
+        t.base = static_cast<uint8_t *>(aligned_alloc(16, (t.lead + t.nbytes + 15) / 16 * 16));
+        for (uint64_t i = 0; i < t.lead + t.nbytes; i++) t.base[i] = uint8_t(rnd());
+        t.name = "t" + std::to_string(k);
+        t.shape = int64_t(t.nbytes);
+        ts.push_back(t);
+    }
+    std::vector<ckpt_tensor_desc> descs;
+    for (auto &t : ts) {
+        ckpt_tensor_desc d{};
+        d.name = t.name.c_str(); d.dtype = CKPT_U8; d.ndim = 1; d.shape = &t.shape; d.dev_ptr = t.base + t.lead; d.nbytes = t.nbytes;
+        descs.push_back(d);
+    }
+    ckpt_config cfg{};
+    cfg.out_dir = dir.c_str();
+    cfg.host_ring_bytes = 256 << 10;
+    cfg.dma_chunk_bytes = 64 << 10;
+    cfg.pack_superchunk_bytes = 128 << 10;
+    cfg.n_dma_streams = 2;
+    cfg.n_io_threads = 2;
+    cfg.window_policy = policy;
+    ckpt_ctx *ctx = nullptr;
+    REQUIRE(ckpt_init(&cfg, &ctx) == CKPT_OK);
+    REQUIRE(ckpt_register_tensors(ctx, descs.data(), descs.size()) == CKPT_OK);
+    ckpt_layout lay;
+    REQUIRE(ckpt_get_layout(ctx, &lay) == CKPT_OK && lay.n_superchunks >= 4);
+    ckpt_plan *plan = nullptr;
+    REQUIRE(ckpt_plan_create(descs.data(), descs.size(), &cfg, &plan) == CKPT_OK);
+    std::vector<uint64_t> offs(descs.size());
+    REQUIRE(ckpt_plan_offsets(plan, offs.data(), offs.size()) == CKPT_OK);
+    hipStream_t compute;
+    hipStreamCreateWithFlags(&compute, hipStreamNonBlocking);
+    g_callers_stream = compute;
+    g_emu_submit_hook = count_early;
+    char name[4096];
+    for (int it = 1; it <= 3; it++) {
+        std::mutex m;
+        std::condition_variable cv;
+        bool release = false;
+        std::vector<uint8_t> img(lay.file_bytes, 0);
+        // the "forward pass and update" the device has not finished yet: it ends when the test lets it
+        g_boundary_held = true;
+        emu_submit(compute, [&, it] {
+            { std::unique_lock<std::mutex> lk(m); cv.wait(lk, [&] { return release; }); }
+            for (auto &t : ts) for (uint64_t i = 0; i < t.nbytes; i++) t.base[t.lead + i] = uint8_t(t.base[t.lead + i] * 29 + it);
+            ckpt_plan_header(plan, uint64_t(it), img.data(), lay.header_bytes);
+            for (size_t k = 0; k < ts.size(); k++) memcpy(img.data() + offs[k], ts[k].base + ts[k].lead, ts[k].nbytes);
+            g_boundary_held = false;      // the next thing in this stream is the boundary event
+        });
+        REQUIRE(ckpt_snapshot_async(ctx, uint64_t(it), compute) == CKPT_OK);      // returns at once, boundary not reached
+        usleep(150 * 1000);                                                          // time for a premature enqueue to happen
+        REQUIRE(g_early_submissions.load() == 0);
+        { std::lock_guard<std::mutex> lk(m); release = true; cv.notify_all(); }
+        REQUIRE(ckpt_wait_immutable_window_end(ctx, compute, 0) == CKPT_OK);
+        REQUIRE(ckpt_flush(ctx, uint64_t(it)) == CKPT_OK);
+        hipStreamSynchronize(compute);
+        REQUIRE(g_early_submissions.load() == 0);
+        REQUIRE(ckpt_file_name(ctx, uint64_t(it), name, sizeof name) == CKPT_OK);
+        REQUIRE(read_file(name) == img);
+    }
+    g_emu_submit_hook = nullptr;
+    ckpt_plan_destroy(plan);
+    REQUIRE(ckpt_destroy(ctx) == CKPT_OK);
+    hipStreamDestroy(compute);
+    for (auto &t : ts) free(t.base);
+    printf("ok %s\n", what.c_str());
+    return 0;
+}
+
 // ---- data reduction: bf16 copies declared as roundings of f32 masters. The update keeps them so (version-2
 // files, the copies left out) except at one iteration, where one element is off (that snapshot must be the full
 // version-1 file). Every file against an image built here; restore of both versions into poisoned memory.
@@ -555,6 +639,17 @@ int main(int argc, char **argv) {
         return 0;
     }
     if (std::string(argv[1]) == "--crash" && argc >= 5) return crash_child(argv[2], atoi(argv[3]), atol(argv[4]));
+    if (std::string(argv[1]) == "--held-boundary" && argc >= 3) {
+        rng_state = 17;
+        const std::string root = argv[2];
+        int n = 0;
+        for (int policy : {CKPT_WINDOW_D2H, CKPT_WINDOW_PACK}) {
+            const std::string d = root + "/h" + std::to_string(n++);
+            mkdir(d.c_str(), 0755);
+            if (held_boundary_scenario(d, policy)) return 1;
+        }
+        return 0;
+    }
     if (std::string(argv[1]) == "--derived" && argc >= 3) {
         rng_state = argc > 3 ? strtoull(argv[3], 0, 10) : 5;
         const std::string root = argv[2];

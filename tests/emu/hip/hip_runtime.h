@@ -14,6 +14,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <deque>
+#include <atomic>
 #include <functional>
 #include <mutex>
 #include <thread>
@@ -126,7 +127,12 @@ struct hipPointerAttribute_t { hipMemoryType type; int device; };
 typedef void *hipDeviceptr_t;
 
 // the null stream of the model executes immediately in the calling thread
-inline void emu_submit(hipStream_t s, std::function<void()> f) { if (s) s->push(std::move(f)); else f(); }
+// a test may watch what is enqueued where (called with the stream of every submission, before it is queued)
+inline std::atomic<void (*)(hipStream_t)> g_emu_submit_hook{nullptr};
+inline void emu_submit(hipStream_t s, std::function<void()> f) {
+    if (auto hook = g_emu_submit_hook.load()) hook(s);
+    if (s) s->push(std::move(f)); else f();
+}
 
 inline hipError_t hipSetDevice(int) { return hipSuccess; }
 inline hipError_t hipGetDevice(int *d) { *d = 0; return hipSuccess; }

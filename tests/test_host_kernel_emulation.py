@@ -83,6 +83,16 @@ def test_failed_chunk_write_never_yields_a_named_file(emu_engine, tmp_path):
     assert out.count("ok failed chunk") == 2
 
 
+def test_nothing_is_enqueued_before_the_device_reaches_the_boundary(emu_engine, tmp_path):
+    """The caller's host requests a snapshot while its stream still has the whole step to run. Until the device
+    reaches the boundary the library must keep its own streams empty (work parked behind an unsignalled event
+    slows every kernel launch of the caller on the GPU); afterwards the file is the state at the boundary."""
+    r = subprocess.run([emu_engine, "--held-boundary", str(tmp_path)], capture_output=True, text=True, timeout=300)
+    out = r.stdout + r.stderr
+    assert r.returncode == 0 and "FAILED" not in out and "ThreadSanitizer" not in out, out[-6000:]
+    assert out.count("ok held boundary") == 2
+
+
 def _crash_expected(it):
     """The file the oracle writes for iteration `it` of the crash child's shard (tests/emu/emu_engine.cpp: crash_byte)."""
     import numpy as np
