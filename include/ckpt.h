@@ -265,7 +265,10 @@ int ckpt_declare_derived(ckpt_ctx *ctx, const uint32_t *derived, const uint32_t 
  * work already enqueued on `hip_stream_compute` has run. Returns without waiting for any copy; the
  * caller goes on with the next forward/backward pass. Pack kernels, copies and file writes are
  * issued by library threads; if the ring is full they wait for flushed slots (never for the
- * caller). CKPT_ESTATE: nothing registered, or a previous snapshot's window was never closed with
+ * caller). A library thread waits, on the host, until the device has reached this point of the stream, and issues
+ * the snapshot's kernels and copies only then (work parked in other queues behind an event that has not fired
+ * slows every kernel launch of the caller's stream): the stream must get there without further calls into the
+ * library. CKPT_ESTATE: nothing registered, or a previous snapshot's window was never closed with
  * ckpt_wait_immutable_window_end / ckpt_flush, or `iter` is still in flight. A latched I/O error of
  * an earlier snapshot is returned here (CKPT_EIO / CKPT_EHIP) and cleared. */
 int ckpt_snapshot_async(ckpt_ctx *ctx, uint64_t iter, void *hip_stream_compute);
