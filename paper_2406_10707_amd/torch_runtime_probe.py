@@ -55,8 +55,10 @@ def main():
             peak = max(peak, n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
         del d, h
         data_upper = spec.payload_bytes + 4096 * len(spec.tensors)
-        chunk = 256 << 20
-        ring = min(16 << 30, -(-data_upper // chunk) * chunk)
+        # a shard of under 2 GB that is checkpointed every step: 64 MiB copies (the pipeline starts sooner) and a ring of twice
+        # the shard, so that a snapshot's copies never wait for the previous snapshot's slots to be written out
+        chunk = 64 << 20
+        ring = min(16 << 30, 2 * (-(-data_upper // chunk) * chunk))
         ck = B.Checkpointer(B.make_config(out_dir=out_dir, host_ring_bytes=ring, dma_chunk_bytes=chunk, n_io_threads=6, keep_last=1,
                                           prealloc_files=2))
         ck.register_tensors(descs)
