@@ -380,7 +380,9 @@ int ckpt_get_layout(ckpt_ctx *ctx, ckpt_layout *out);
  * a copy engine that moves checkpoints without taking compute resources from training; whether the copies of
  * this process go that way is a property of the HIP runtime it has loaded. On MI355X the system runtime reaches
  * about 56 GB/s here; a figure far below the link's rate means the runtime executes copies with kernels on the
- * compute units, and snapshots will both run slower and slow training down. */
+ * compute units, and snapshots will both run slower and slow training down. One exception seen on MI355X boxes: for
+ * the first second or so after ANOTHER process has released tens of GB of pinned or file memory, every pinned copy of a
+ * new process runs at about half the link's rate (30 GB/s), this probe included; copies a second later are at full rate. */
 int ckpt_get_init_probe(ckpt_ctx *ctx, double *d2h_gbps);
 /* Measurements of one requested snapshot; CKPT_EINVAL if unknown (records of the 1024 most recent
  * requests are kept). Device-timeline fields are filled

@@ -216,6 +216,7 @@ int ckpt_init(const ckpt_config *cfg, ckpt_ctx **out) {
     remove_stale_spares(c->out_dir);
     trace("init: creating streams and events");
     c->slot_state.assign(c->n_slots, SLOT_FREE);
+    c->slot_reads_left.assign(c->n_slots, 0);
     hipError_t e = hipSuccess;
     auto cleanup_fail = [&](int code, const std::string &m) { trace(("init: failed: " + m).c_str()); ckpt_destroy(c.release()); return fail(code, m); };
     if ((e = hipStreamCreateWithFlags(&c->pack_stream, hipStreamNonBlocking)) != hipSuccess) return cleanup_fail(CKPT_EHIP, hipGetErrorString(e));

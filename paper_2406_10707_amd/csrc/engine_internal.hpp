@@ -110,10 +110,12 @@ struct IoJob {
     std::shared_ptr<Snap> snap;   // WRITE
     int fd = -1;                  // READ
     uint64_t slot = 0, file_off = 0, nbytes = 0;
+    uint64_t slot_off = 0;        // READ: where in the slot this piece of the chunk goes
     bool last = false;
     uint64_t seq = 0;             // READ: chunk sequence number
 };
 
+constexpr uint64_t kReadPiecesPerChunk = 8;   // restore reads a chunk in this many pieces, spread over the I/O threads
 constexpr int kBoundaryEvents = 8;          // boundary events created at set-up (snapshots in flight at a time)
 constexpr size_t kMaxSnapRecords = 1024;   // per-snapshot records (measurements, states) kept per context
 
@@ -159,6 +161,7 @@ struct ckpt_ctx {
     std::deque<std::shared_ptr<Snap>> submit_q;
     std::deque<IoJob> io_q;
     std::vector<int> slot_state;
+    std::vector<uint32_t> slot_reads_left;                // restore: pieces of the slot's chunk still being read
     bool stopping = false;
     std::thread submit_thread;
     std::vector<std::thread> io_threads;

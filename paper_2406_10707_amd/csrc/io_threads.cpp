@@ -81,12 +81,15 @@ void dsllm::io_thread_main(ckpt_ctx *c) {
         uint8_t *slot_ptr = c->ring + job.slot * c->cfg.dma_chunk_bytes;
         std::string err;
         if (job.kind == IoJob::READ) {
-            bool ok = c->cfg.o_direct ? (bounce ? direct_read(job.fd, bounce, slot_ptr, job.nbytes, job.file_off, &err) : (err = "no bounce buffer", false))
-                                      : pread_all(job.fd, slot_ptr, job.nbytes, job.file_off, &err);
+            uint8_t *piece = slot_ptr + job.slot_off;
+            bool ok = c->cfg.o_direct ? (bounce ? direct_read(job.fd, bounce, piece, job.nbytes, job.file_off, &err) : (err = "no bounce buffer", false))
+                                      : pread_all(job.fd, piece, job.nbytes, job.file_off, &err);
             if (!ok) c->latch(CKPT_EIO, err);
             std::lock_guard<std::mutex> lk(c->mu);
-            c->slot_state[job.slot] = SLOT_READ_DONE;
-            c->cv_state.notify_all();
+            if (--c->slot_reads_left[job.slot] == 0) {   // the chunk's last piece
+                c->slot_state[job.slot] = SLOT_READ_DONE;
+                c->cv_state.notify_all();
+            }
             continue;
         }
         // WRITE: the chunk's copy must have landed in the slot first

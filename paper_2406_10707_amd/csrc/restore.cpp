@@ -43,18 +43,27 @@ static int restore_body(ckpt_ctx *c, int fd, const char *path, hipStream_t strea
         for (; issued < upto && issued < p.n_chunks; issued++) {
             const uint64_t slot = (base + issued) % c->n_slots;
             if (issued >= c->n_slots) HIP_TRY(c, hipEventSynchronize(c->ev_slot[slot]));   // previous chunk's copy out of the slot
-            IoJob job;
-            job.kind = IoJob::READ;
-            job.fd = fd;
-            job.slot = slot;
-            job.file_off = p.header_bytes + issued * CH;
-            job.nbytes = p.chunk_bytes(issued);
+            // A chunk is read in pieces by as many I/O threads as there are pieces: one thread per whole chunk would
+            // leave a small shard (fewer chunks than threads, or one more) waiting for its slowest read.
+            const uint64_t nbytes = p.chunk_bytes(issued);
+            const uint64_t kReadPieceBytes = CH / kReadPiecesPerChunk;   // CH is a multiple of 32 KiB: pieces are 4 KiB multiples
+            const uint64_t n_pieces = (nbytes + kReadPieceBytes - 1) / kReadPieceBytes;
             {
                 std::lock_guard<std::mutex> lk(c->mu);
                 c->slot_state[slot] = SLOT_BUSY;
-                c->io_q.push_back(job);
+                c->slot_reads_left[slot] = uint32_t(n_pieces);
+                for (uint64_t q = 0; q < n_pieces; q++) {
+                    IoJob job;
+                    job.kind = IoJob::READ;
+                    job.fd = fd;
+                    job.slot = slot;
+                    job.slot_off = q * kReadPieceBytes;
+                    job.file_off = p.header_bytes + issued * CH + job.slot_off;
+                    job.nbytes = std::min<uint64_t>(kReadPieceBytes, nbytes - job.slot_off);
+                    c->io_q.push_back(job);
+                }
             }
-            c->cv_io.notify_one();
+            c->cv_io.notify_all();
         }
         return CKPT_OK;
     };
