@@ -295,6 +295,18 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr) and "{" not in r.stdout
 
 
+def test_bench_finds_the_measured_traffic_ratio_of_every_workload():
+    """bench.py's `roofline.traffic` is the algorithmic bytes per launch times the HBM traffic ratio that the counter
+    runs measured on the same workload; the summaries under profiles/ must hold one for each of the five workloads."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    for config in (1, 2, 3, 4, 5):
+        ratio = bench.traffic_ratio(config)
+        assert ratio is not None and 0.99 < ratio < 1.02, (config, ratio)
+
+
 def test_headers_compile_as_plain_c(tmp_path):
     """The boundary is a C ABI: both headers must be valid C99 on their own."""
     import shutil
